@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the Ouroboros verification step on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic input:
+ouro_verify_attn -> ouro_lmhead_argmax -> ouro_accept, enqueued back to back on one
+stream with inputs resident in HBM.  The default workload is the Llama-2-7B-shaped
+config (batch 1, 32 heads x 128, KV length 2048, draft block 64, vocabulary 32000).
+
+Prints ONE JSON line: whole-job throughput in draft tokens verified per second, the
+roofline of the dominant kernel (measured with HIP events on the launch stream inside
+the timed region), and the CPU oracle timed on the host as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (default 2: Llama-2-7B-shaped layer)")
+    ap.add_argument("--rotate", type=int, default=0, help="copies of KV cache and LM-head weight cycled through "
+                    "(0: enough copies to exceed 1 GB, so that the 256 MB last-level cache cannot hold them)")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU-oracle baseline leg")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--branch", default="uniform", choices=["uniform", "last"])
+    return ap.parse_args()
+
+
+def attn_algorithmic_bytes(cfg, total_cache_rows):
+    e = 2 if cfg.dtype == "bf16" else 4
+    kv = 2 * (total_cache_rows + cfg.B * cfg.T) * cfg.Hkv * cfg.D * e
+    qo = 2 * cfg.B * cfg.T * cfg.Hq * cfg.D * e
+    return kv + qo + 4 * cfg.B * cfg.T
+
+
+def attn_flops(cfg, seqlens):
+    return sum(4 * cfg.T * cfg.Hq * (int(L) + cfg.T) * cfg.D for L in seqlens)
+
+
+def lmhead_algorithmic_bytes(cfg):
+    e = 2 if cfg.dtype == "bf16" else 4
+    return cfg.V * cfg.hidden * e + cfg.R * cfg.hidden * e + 4 * cfg.R
+
+
+def lmhead_flops(cfg):
+    return 2 * cfg.R * cfg.hidden * cfg.V
+
+
+def cpu_baseline(cfg, inp, w, draws, budget_s):
+    """Time the oracle (as it stands) on the host on a bounded sample and scale to one full step."""
+    import numpy as np
+    from oracle import verify_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    # attention: sample (sequence, head) pairs until a third of the budget is spent
+    pairs = [(b, h) for b in range(cfg.B) for h in range(cfg.Hq)]
+    rng = np.random.default_rng(0)
+    rng.shuffle(pairs)
+    seqlens = np.diff(inp["cu_seqlens"])
+    t0 = time.perf_counter()
+    done, work_done = 0, 0.0
+    for (b, h) in pairs:
+        O.verify_attention(inp["q"], inp["k_cache"], inp["v_cache"], inp["cu_seqlens"], inp["k_blk"], inp["v_blk"],
+                           inp["pid"], inp["boff"], heads=[(b, h)])
+        done += 1
+        work_done += float(seqlens[b] + cfg.T)
+        if time.perf_counter() - t0 > budget_s / 3:
+            break
+    t_att_sample = time.perf_counter() - t0
+    work_all = float(sum((seqlens[b] + cfg.T) for b in range(cfg.B)) * cfg.Hq)
+    t_att = t_att_sample * work_all / work_done
+    # LM head: sample rows (cost is linear in rows)
+    rows = min(cfg.R, 64)
+    hid = inp["q"].reshape(cfg.R, cfg.hidden)[:rows]          # any [rows, hidden] values: timing only
+    t0 = time.perf_counter()
+    lm = O.lmhead_argmax(hid, w)
+    t_lm_sample = time.perf_counter() - t0
+    t_lm = t_lm_sample * cfg.R / rows
+    # acceptance: full
+    amax = np.resize(lm["argmax"], (cfg.B, cfg.T))
+    t0 = time.perf_counter()
+    O.accept(draws["tok"], amax, inp["pid"], inp["boff"], draws["root_pred"], cfg.gamma, cfg.K, cfg.beta_p)
+    t_acc = time.perf_counter() - t0
+    t_step = t_att + t_lm + t_acc
+    return {
+        "value": cfg.R / t_step, "unit": "draft tokens verified/s", "cores": int(cores), "kind": "oracle",
+        "sample": "attention on %d of %d (sequence, head) pairs, LM head on %d of %d rows, acceptance in full; "
+                  "scaled linearly to one step" % (done, len(pairs), rows, cfg.R),
+        "step_seconds_scaled": t_step,
+        "stage_seconds_scaled": {"attention": t_att, "lmhead_argmax": t_lm, "accept": t_acc},
+    }
+
+
+def load_traffic(workload_key):
+    """HBM bytes per launch of the dominant kernel from committed rocprofv3 --pmc summaries, if present."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload_key)
+    except Exception:
+        return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (use --gpus 1)." % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2402_13720_amd import binding as ob, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    cfg = W.CONFIGS[args.config]
+    seed = W.seed_for(args.config)
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+
+    inp = W.make_attention_inputs(cfg, seed, branch=args.branch)
+    w = W.make_lmhead_weight(cfg, seed)
+    draws = W.make_token_draws(cfg, seed)
+    seqlens = np.diff(inp["cu_seqlens"])
+    total_rows = int(inp["cu_seqlens"][-1])
+    max_seqlen = int(seqlens.max())
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, inp, w, draws, args.cpu_seconds)
+
+    # ---- device-resident inputs; KV cache and W in several copies that the steps cycle through ----
+    e = 2 if cfg.dtype == "bf16" else 4
+    rot_bytes = 2 * total_rows * cfg.Hkv * cfg.D * e + cfg.V * cfg.hidden * e
+    nrot = args.rotate if args.rotate > 0 else max(1, min(8, int(np.ceil(1.0e9 / rot_bytes))))
+    up = lambda x: torch.from_numpy(x).to(dev).to(dt).contiguous()
+    q, k_blk, v_blk = up(inp["q"]), up(inp["k_blk"]), up(inp["v_blk"])
+    kc0, vc0, w0 = up(inp["k_cache"]), up(inp["v_cache"]), up(w)
+    kcs = [kc0] + [kc0.clone() for _ in range(nrot - 1)]
+    vcs = [vc0] + [vc0.clone() for _ in range(nrot - 1)]
+    ws = [w0] + [w0.clone() for _ in range(nrot - 1)]
+    cu = torch.from_numpy(inp["cu_seqlens"]).to(dev)
+    meta = ob.pack_meta(inp["pid"], inp["boff"]).to(dev)
+    root = torch.from_numpy(draws["root_pred"]).to(dev)
+
+    out = torch.empty_like(q)
+    hidden = out.view(cfg.R, cfg.hidden)
+    arg = torch.empty(cfg.R, dtype=torch.int32, device=dev)
+    ws_attn = torch.empty(max(ob.ouro_verify_attn_workspace(q, k_blk, max_seqlen), 256), dtype=torch.uint8, device=dev)
+    ws_lm = torch.empty(max(ob.ouro_lmhead_argmax_workspace(hidden, w0), 256), dtype=torch.uint8, device=dev)
+    acc_out = ob.alloc_accept_outputs(cfg.B, cfg.gamma, cfg.K, cfg.beta_p, dev)
+
+    # draft ids: half of the block positions carry the token they will be compared with (the greedy
+    # token of their parent row); the other half are uniform.  Values do not affect timing.
+    ob.ouro_verify_attn(q, kcs[0], vcs[0], cu, k_blk, v_blk, meta, max_seqlen, out=out, workspace=ws_attn)
+    ob.ouro_lmhead_argmax(hidden, ws[0], argmax_out=arg, workspace=ws_lm)
+    torch.cuda.synchronize()
+    amax = arg.cpu().numpy().reshape(cfg.B, cfg.T)
+    exp = np.empty_like(amax)
+    for b in range(cfg.B):
+        for t in range(cfg.T):
+            if inp["pid"][b, t] == 0:
+                p = t - 1
+            elif t > 0 and inp["pid"][b, t - 1] == inp["pid"][b, t]:
+                p = t - 1
+            else:
+                p = int(inp["boff"][b, t])
+            exp[b, t] = draws["root_pred"][b] if p < 0 else amax[b, p]
+    tok = torch.from_numpy(W.plant_tokens(draws["tok"], draws["chosen"], exp)).to(dev)
+
+    stream = torch.cuda.current_stream()
+
+    def step(i, ev=None):
+        r = i % nrot
+        if ev is not None:
+            ev[0].record(stream)
+        ob.ouro_verify_attn(q, kcs[r], vcs[r], cu, k_blk, v_blk, meta, max_seqlen, out=out, workspace=ws_attn)
+        if ev is not None:
+            ev[1].record(stream)
+        ob.ouro_lmhead_argmax(hidden, ws[r], argmax_out=arg, workspace=ws_lm)
+        if ev is not None:
+            ev[2].record(stream)
+        ob.ouro_accept(tok, arg.view(cfg.B, cfg.T), meta, root, cfg.gamma, cfg.K, cfg.beta_p, outs=acc_out)
+        if ev is not None:
+            ev[3].record(stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_step = elapsed * 1e3 / args.steps
+    seg = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(3)] for ev in events])   # ms
+    t_attn, t_lm, t_acc = (float(x) for x in seg.mean(axis=0))
+    tokens = cfg.R
+
+    lm_bytes = lmhead_algorithmic_bytes(cfg)
+    at_bytes = attn_algorithmic_bytes(cfg, total_rows)
+    lm_gbs = lm_bytes / (t_lm * 1e-3) / 1e9
+    at_gbs = at_bytes / (t_attn * 1e-3) / 1e9
+    lm_tflops = lmhead_flops(cfg) / (t_lm * 1e-3) / 1e12
+    at_tflops = attn_flops(cfg, seqlens) / (t_attn * 1e-3) / 1e12
+    workload = "cfg%d:%s" % (cfg.cfg_id, cfg.name)
+    lm_mfma_bound = cfg.R >= 312          # arithmetic intensity ~R flop/B against a machine balance of ~312
+    if lm_mfma_bound:
+        roofline = {"kernel": "ouro_lmhead_argmax", "bound": "mfma", "achieved": lm_tflops,
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": lm_tflops / MFMA_BF16_PEAK_TFLOPS,
+                    "traffic": load_traffic(workload)}
+    else:
+        roofline = {"kernel": "ouro_lmhead_argmax", "bound": "hbm", "achieved": lm_gbs, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": lm_gbs / HBM_PEAK_GBS, "traffic": load_traffic(workload)}
+    result = {
+        "metric": "draft tokens verified per second (one verification step: attention + LM head/argmax + accept)",
+        "value": tokens / (ms_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "verify_step_latency_us": ms_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": workload, "B": cfg.B, "T": cfg.T, "gamma": cfg.gamma, "K": cfg.K, "beta": cfg.beta_p,
+                   "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D, "cache_rows": total_rows, "V": cfg.V,
+                   "branch": args.branch, "rotated_copies": nrot},
+        "kernel_us": {"ouro_verify_attn": t_attn * 1e3, "ouro_lmhead_argmax": t_lm * 1e3, "ouro_accept": t_acc * 1e3},
+        "roofline": roofline,
+        "roofline_attn": {"kernel": "ouro_verify_attn", "bound": "hbm", "achieved": at_gbs, "peak": HBM_PEAK_GBS,
+                          "unit": "GB/s", "frac": at_gbs / HBM_PEAK_GBS, "mfma_tflops": at_tflops},
+        "lmhead_mfma_frac": lm_tflops / MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else None,
+        "cpu_baseline": cpu,
+        "accepted_per_sequence": acc_out["n_accept"].cpu().tolist()[:16],
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,194 @@
+/*
+ * ouro.h -- C ABI of the MI355X (gfx950) verification-step library.
+ *
+ * One verification pass of Ouroboros speculative decoding (Sec. 2, Eq. (2)-(3);
+ * Sec. 3.2, Eq. (7)-(9)): the target model scores a whole draft block -- a main
+ * draft d_1..gamma followed by K candidate phrase suffixes -- in one parallel
+ * pass against the KV cache, under an attention mask that gives every block row
+ * exactly the context its own lengthened draft would have; the greedy token of
+ * every row is taken, and the longest accepted prefix is selected.
+ *
+ * Three stages, three entry points:
+ *   ouro_verify_attn     masked draft-block attention against the KV cache
+ *   ouro_lmhead_argmax   LM-head product fused with the arg-max over the vocabulary
+ *   ouro_accept          accepted-prefix decision over main draft + phrases
+ *
+ * General contract
+ *   - Every data pointer in a descriptor is DEVICE memory owned by the caller and
+ *     must stay valid until the work enqueued on the stream has finished.
+ *     Descriptors themselves are HOST memory, read during the call only.
+ *   - Calls only enqueue work on the given HIP stream (a hipStream_t passed as
+ *     void*; NULL = the default stream).  They never allocate, free or
+ *     synchronise, keep no state between calls, and may be called from several
+ *     threads on different streams with disjoint outputs and workspaces.
+ *   - Return value: OURO_OK (0) or a negative OURO_E_* code.  On an error nothing
+ *     has been enqueued, except OURO_E_HIP which reports a failed launch (the
+ *     hipError_t is kept per thread for ouro_last_hip_error()).
+ *   - All shape/pointer/alignment/workspace checks run on the host before any
+ *     HIP call, so they can be exercised on a machine without a GPU.
+ *   - Inputs must be finite; NaN handling is unspecified.
+ */
+#ifndef OURO_H
+#define OURO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OURO_VERSION 100 /* major*10000 + minor*100 + patch */
+
+/* Exported from libouro.so (everything else in the library has hidden visibility). */
+#define OURO_API __attribute__((visibility("default")))
+
+enum {
+  OURO_OK = 0,
+  OURO_E_NULLPTR = -1,             /* a required pointer is NULL */
+  OURO_E_BAD_SHAPE = -2,           /* a size is out of range or inconsistent */
+  OURO_E_UNSUPPORTED_DTYPE = -3,
+  OURO_E_WORKSPACE_TOO_SMALL = -4,
+  OURO_E_MISALIGNED = -5,          /* a pointer is not 16-byte aligned */
+  OURO_E_HIP = -6,                 /* a HIP call failed; see ouro_last_hip_error() */
+  OURO_E_BAD_STRUCT = -7,          /* struct_size does not match this header */
+  OURO_E_BAD_META = -8             /* ouro_validate_meta_host only */
+};
+
+typedef enum { OURO_F32 = 0, OURO_BF16 = 1 } ouro_dtype;
+
+/*
+ * Per-token block metadata, 4 bytes.  The block of T tokens is laid out as the main
+ * draft (block indices 0..gamma-1) followed by the phrases (Eq. (7)); a phrase
+ * occupies a contiguous ascending index range.
+ *   main token i      : phrase_id = 0, branch_off = i
+ *   token of phrase j : phrase_id = j (1..K), branch_off = b_j, the 0-based main-draft
+ *                       index the phrase hangs off.  The paper's layout (every phrase
+ *                       starts with d_gamma, Sec. 3.2) is b_j = gamma-1.  b_j = -1: the
+ *                       phrase hangs off the last cached token and sees no main token.
+ * The attention mask is computed from these pairs inside the kernel; no dense mask is
+ * ever read from memory.  Row q sees block key k iff
+ *   phrase_id[k] == 0 ? k <= branch_off[q] : (phrase_id[k] == phrase_id[q] && k <= q),
+ * which is the conditioning set of Eq. (2) for main rows and of Eq. (8) for phrase rows.
+ */
+typedef struct {
+  int16_t phrase_id;
+  int16_t branch_off;
+} ouro_tok_meta;
+
+/* ------------------------------------------------------------------------------------ */
+/* Draft-block attention (the attention of the single verifying forward, Sec. 3.2).      */
+/*                                                                                       */
+/* For sequence b, query head h and block row t:                                         */
+/*   out = softmax(scale * q . K_vis^T) . V_vis                                          */
+/* over the L_b cached keys of the sequence (all visible) followed by the block keys      */
+/* visible to row t.  Query head h reads KV head h / (Hq / Hkv).  Q and K arrive with     */
+/* positional rotation already applied.  bf16: products on bf16 MFMA, fp32 accumulation,  */
+/* probabilities rounded to bf16 before the value product, bf16 output.  f32: fp32        */
+/* arithmetic throughout.                                                                */
+/* ------------------------------------------------------------------------------------ */
+typedef struct {
+  uint32_t struct_size;        /* sizeof(ouro_attn_desc) */
+  int32_t dtype;               /* ouro_dtype of q, k_*, v_*, out */
+  int32_t B;                   /* sequences, >= 0 (0: nothing to do) */
+  int32_t T;                   /* block tokens per sequence, 1..128 */
+  int32_t Hq;                  /* query heads */
+  int32_t Hkv;                 /* key/value heads, divides Hq */
+  int32_t D;                   /* head dim: 128 (bf16) ; 64 or 128 (f32) */
+  int32_t max_seqlen;          /* host-side upper bound on every L_b (sizes the launch; no device read-back) */
+  const void* q;               /* [B, T, Hq, D] */
+  const void* k_cache;         /* [sum_b L_b, Hkv, D], sequence b at rows cu_seqlens[b] .. cu_seqlens[b+1]-1 */
+  const void* v_cache;         /* same layout; may be NULL only if max_seqlen == 0 */
+  const int64_t* cu_seqlens;   /* [B+1], cu[0] = 0, non-decreasing; 0 <= L_b <= max_seqlen */
+  const void* k_blk;           /* [B, T, Hkv, D] keys of the block tokens (not yet in the cache) */
+  const void* v_blk;           /* [B, T, Hkv, D] */
+  const ouro_tok_meta* meta;   /* [B, T] */
+  float softmax_scale;         /* <= 0: 1/sqrt(D) */
+  void* out;                   /* [B, T, Hq, D], same dtype as q */
+  float* lse;                  /* optional [B, Hq, T]: natural-log softmax denominator; NULL to skip */
+  void* workspace;             /* >= ouro_verify_attn_workspace() bytes, 16-byte aligned; contents arbitrary */
+  size_t workspace_bytes;
+} ouro_attn_desc;
+
+/* Host-only: bytes of workspace the call will need for this descriptor (data pointers are
+ * not read).  Returns 0 if the descriptor is invalid or no workspace is needed. */
+OURO_API size_t ouro_verify_attn_workspace(const ouro_attn_desc* desc);
+OURO_API int ouro_verify_attn(const ouro_attn_desc* desc, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------ */
+/* LM head fused with the greedy pick (Eq. (2) under greedy decoding).                   */
+/*   logits[r, v] = sum_k hidden[r, k] * w[v, k]   ;   argmax_out[r] = arg max_v logits   */
+/* Ties go to the smallest v.  The logits are never written to memory.  bf16: bf16 MFMA   */
+/* with fp32 accumulation; f32: fp32 arithmetic.                                          */
+/* ------------------------------------------------------------------------------------ */
+typedef struct {
+  uint32_t struct_size;        /* sizeof(ouro_lmhead_desc) */
+  int32_t dtype;               /* ouro_dtype of hidden and w */
+  int32_t R;                   /* rows (B*T block tokens), >= 0 */
+  int32_t Hd;                  /* hidden size, multiple of 64 (bf16) / 4 (f32) */
+  int32_t V;                   /* vocabulary, >= 1 */
+  int32_t reserved;
+  const void* hidden;          /* [R, Hd] row-major (the attention output viewed as [B*T, Hq*D]) */
+  const void* w;               /* [V, Hd] row-major: row v is the output embedding of token v */
+  int32_t* argmax_out;         /* [R] */
+  float* max_out;              /* optional [R]: the winning logit (fp32); NULL to skip */
+  void* workspace;             /* >= ouro_lmhead_argmax_workspace() bytes, 16-byte aligned */
+  size_t workspace_bytes;
+} ouro_lmhead_desc;
+
+OURO_API size_t ouro_lmhead_argmax_workspace(const ouro_lmhead_desc* desc);
+OURO_API int ouro_lmhead_argmax(const ouro_lmhead_desc* desc, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------ */
+/* Acceptance (Eq. (3) for the main draft, Eq. (9) for each phrase, and the rule after    */
+/* Eq. (9): extend the accepted draft by the phrase with the longest accepted run).       */
+/*                                                                                       */
+/* Block position t is compared with the greedy token predicted by the row of the token   */
+/* that precedes it in its own lengthened draft (root_pred for a position that follows     */
+/* the cached prefix directly).  A = leading matches of the main draft; Ahat'_j = leading  */
+/* matches inside phrase j's beta block tokens; phrase j is usable iff A >= b_j + 1 and    */
+/* then yields b_j + 1 + Ahat'_j accepted tokens; the longest candidate wins, the main      */
+/* draft first and then the lowest phrase id on ties.  bonus = the prediction of the last   */
+/* accepted row (root_pred if nothing is accepted, -1 if root_pred is NULL as well).        */
+/* ------------------------------------------------------------------------------------ */
+typedef struct {
+  uint32_t struct_size;        /* sizeof(ouro_accept_desc) */
+  int32_t B;                   /* sequences, >= 0 */
+  int32_t T;                   /* == gamma + K * beta, 1..128 */
+  int32_t gamma;               /* main draft length, >= 1 */
+  int32_t K;                   /* phrases, 0..63 */
+  int32_t beta;                /* block tokens per phrase (the paper's beta - 1) */
+  const int32_t* draft_tok;    /* [B, T] */
+  const int32_t* argmax;       /* [B, T] greedy token of every block row */
+  const ouro_tok_meta* meta;   /* [B, T] */
+  const int32_t* root_pred;    /* [B] target's prediction after the cached prefix; NULL: positions that follow
+                                  the prefix directly (main token 0) count as accepted without a check */
+  int32_t* n_accept;           /* [B] number of accepted block tokens */
+  int32_t* path;               /* [B] 0 = main draft only, j = main draft up to b_j then phrase j */
+  int32_t* bonus;              /* [B] */
+  int32_t* accept_idx;         /* [B, gamma + beta] accepted block indices in order, -1 padded */
+  int32_t* main_A;             /* optional [B] */
+  int32_t* phrase_A;           /* optional [B, K] */
+  int32_t* n_match;            /* optional [B]: number of main-draft positions equal to the target's
+                                  prediction, accepted or not (#Match, Eq. (10)) */
+} ouro_accept_desc;
+
+OURO_API int ouro_accept(const ouro_accept_desc* desc, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------ */
+/* Host-side helpers                                                                     */
+/* ------------------------------------------------------------------------------------ */
+/* Debug check of a HOST copy of one sequence's metadata against the layout rules above
+ * (main tokens first with branch_off = index, phrases contiguous and ascending with ids
+ * 1..K, -1 <= b_j < gamma).  Returns OURO_OK or OURO_E_BAD_META / OURO_E_NULLPTR /
+ * OURO_E_BAD_SHAPE.  Not called on the hot path. */
+OURO_API int ouro_validate_meta_host(const ouro_tok_meta* meta_host, int32_t T, int32_t gamma, int32_t K, int32_t beta);
+
+OURO_API const char* ouro_status_string(int status);
+OURO_API int ouro_last_hip_error(void);   /* hipError_t of the calling thread's last OURO_E_HIP, else 0 */
+OURO_API int ouro_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OURO_H */

@@ -1,0 +1,226 @@
+"""Thin ctypes binding of libouro.so (the C ABI declared in include/ouro.h).
+
+Argument marshalling only: every step of the verification path runs in the HIP
+kernels of the library.  PyTorch provides device memory and the stream.  There is
+no fallback: if the library cannot be loaded, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libouro.so")
+
+OURO_F32, OURO_BF16 = 0, 1
+
+
+class ouro_attn_desc(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("dtype", C.c_int32),
+        ("B", C.c_int32), ("T", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+        ("max_seqlen", C.c_int32),
+        ("q", C.c_void_p), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("cu_seqlens", C.c_void_p),
+        ("k_blk", C.c_void_p), ("v_blk", C.c_void_p), ("meta", C.c_void_p),
+        ("softmax_scale", C.c_float),
+        ("out", C.c_void_p), ("lse", C.c_void_p),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
+class ouro_lmhead_desc(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("dtype", C.c_int32),
+        ("R", C.c_int32), ("Hd", C.c_int32), ("V", C.c_int32), ("reserved", C.c_int32),
+        ("hidden", C.c_void_p), ("w", C.c_void_p), ("argmax_out", C.c_void_p), ("max_out", C.c_void_p),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
+class ouro_accept_desc(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("B", C.c_int32), ("T", C.c_int32), ("gamma", C.c_int32), ("K", C.c_int32), ("beta", C.c_int32),
+        ("draft_tok", C.c_void_p), ("argmax", C.c_void_p), ("meta", C.c_void_p), ("root_pred", C.c_void_p),
+        ("n_accept", C.c_void_p), ("path", C.c_void_p), ("bonus", C.c_void_p), ("accept_idx", C.c_void_p),
+        ("main_A", C.c_void_p), ("phrase_A", C.c_void_p), ("n_match", C.c_void_p),
+    ]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libouro.so is not built (%s).  Run `python -m paper_2402_13720_amd.build` "
+            "(or __graft_entry__.build()) first; there is no fallback path." % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    lib.ouro_verify_attn_workspace.restype = C.c_size_t
+    lib.ouro_verify_attn_workspace.argtypes = [C.POINTER(ouro_attn_desc)]
+    lib.ouro_verify_attn.restype = C.c_int
+    lib.ouro_verify_attn.argtypes = [C.POINTER(ouro_attn_desc), C.c_void_p]
+    lib.ouro_lmhead_argmax_workspace.restype = C.c_size_t
+    lib.ouro_lmhead_argmax_workspace.argtypes = [C.POINTER(ouro_lmhead_desc)]
+    lib.ouro_lmhead_argmax.restype = C.c_int
+    lib.ouro_lmhead_argmax.argtypes = [C.POINTER(ouro_lmhead_desc), C.c_void_p]
+    lib.ouro_accept.restype = C.c_int
+    lib.ouro_accept.argtypes = [C.POINTER(ouro_accept_desc), C.c_void_p]
+    lib.ouro_validate_meta_host.restype = C.c_int
+    lib.ouro_validate_meta_host.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    lib.ouro_status_string.restype = C.c_char_p
+    lib.ouro_status_string.argtypes = [C.c_int]
+    lib.ouro_last_hip_error.restype = C.c_int
+    lib.ouro_version.restype = C.c_int
+    return lib
+
+
+lib = _load()
+
+
+class OuroError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.ouro_status_string(status).decode()
+        if status == -6:
+            msg += " (hipError %d)" % lib.ouro_last_hip_error()
+        super().__init__("%s: %s [%d]" % (where, msg, status))
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise OuroError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return OURO_F32
+    if t.dtype == torch.bfloat16:
+        return OURO_BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def _stream(stream) -> Optional[int]:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def pack_meta(pid, boff) -> torch.Tensor:
+    """(phrase_id, branch_off) int16 arrays/tensors [B,T] -> one int16 tensor [B,T,2] (the ouro_tok_meta layout)."""
+    pid = torch.as_tensor(pid, dtype=torch.int16)
+    boff = torch.as_tensor(boff, dtype=torch.int16)
+    return torch.stack([pid, boff], dim=-1).contiguous()
+
+
+def make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen,
+                   lse=None, workspace=None, softmax_scale: float = 0.0) -> ouro_attn_desc:
+    B, T, Hq, D = q.shape
+    d = ouro_attn_desc()
+    d.struct_size = C.sizeof(ouro_attn_desc)
+    d.dtype = _dtype_code(q)
+    d.B, d.T, d.Hq, d.Hkv, d.D = B, T, Hq, k_blk.shape[2], D
+    d.max_seqlen = int(max_seqlen)
+    d.q, d.k_cache, d.v_cache = _ptr(q), _ptr(k_cache), _ptr(v_cache)
+    d.cu_seqlens, d.k_blk, d.v_blk, d.meta = _ptr(cu_seqlens), _ptr(k_blk), _ptr(v_blk), _ptr(meta)
+    d.softmax_scale = float(softmax_scale)
+    d.out, d.lse = _ptr(out), _ptr(lse)
+    d.workspace = _ptr(workspace)
+    d.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return d
+
+
+def ouro_verify_attn_workspace(q, k_blk, max_seqlen: int) -> int:
+    """Workspace bytes for a call with these shapes (host-only query)."""
+    B, T, Hq, D = q.shape
+    d = ouro_attn_desc()
+    d.struct_size = C.sizeof(ouro_attn_desc)
+    d.dtype = _dtype_code(q)
+    d.B, d.T, d.Hq, d.Hkv, d.D, d.max_seqlen = B, T, Hq, k_blk.shape[2], D, int(max_seqlen)
+    return int(lib.ouro_verify_attn_workspace(C.byref(d)))
+
+
+def ouro_verify_attn(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, max_seqlen: int,
+                     out=None, lse=None, workspace=None, softmax_scale: float = 0.0, stream=None):
+    """Masked draft-block attention.  Tensors are device tensors laid out as in include/ouro.h.
+    Allocates out/workspace with torch when not given; returns out."""
+    for t in (q, k_blk, v_blk):
+        assert t.is_contiguous()
+    assert cu_seqlens.dtype == torch.int64 and meta.dtype == torch.int16 and meta.is_contiguous()
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need = ouro_verify_attn_workspace(q, k_blk, max_seqlen)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    d = make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen, lse, workspace,
+                       softmax_scale)
+    _check(lib.ouro_verify_attn(C.byref(d), _stream(stream)), "ouro_verify_attn")
+    return out
+
+
+def make_lmhead_desc(hidden, w, argmax_out, max_out=None, workspace=None) -> ouro_lmhead_desc:
+    d = ouro_lmhead_desc()
+    d.struct_size = C.sizeof(ouro_lmhead_desc)
+    d.dtype = _dtype_code(hidden)
+    d.R, d.Hd, d.V = hidden.shape[0], hidden.shape[1], w.shape[0]
+    d.hidden, d.w, d.argmax_out, d.max_out = _ptr(hidden), _ptr(w), _ptr(argmax_out), _ptr(max_out)
+    d.workspace = _ptr(workspace)
+    d.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return d
+
+
+def ouro_lmhead_argmax_workspace(hidden, w) -> int:
+    d = make_lmhead_desc(hidden, w, None)
+    return int(lib.ouro_lmhead_argmax_workspace(C.byref(d)))
+
+
+def ouro_lmhead_argmax(hidden, w, argmax_out=None, max_out=None, workspace=None, stream=None):
+    """LM head + vocabulary arg-max.  hidden [R,Hd], w [V,Hd]; returns int32 [R]."""
+    assert hidden.is_contiguous() and w.is_contiguous() and hidden.dtype == w.dtype
+    assert hidden.shape[1] == w.shape[1]
+    if argmax_out is None:
+        argmax_out = torch.empty(hidden.shape[0], dtype=torch.int32, device=hidden.device)
+    if workspace is None:
+        need = ouro_lmhead_argmax_workspace(hidden, w)
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=hidden.device)
+    d = make_lmhead_desc(hidden, w, argmax_out, max_out, workspace)
+    _check(lib.ouro_lmhead_argmax(C.byref(d), _stream(stream)), "ouro_lmhead_argmax")
+    return argmax_out
+
+
+def make_accept_desc(draft_tok, argmax, meta, root_pred, gamma, K, beta, outs) -> ouro_accept_desc:
+    B, T = draft_tok.shape
+    d = ouro_accept_desc()
+    d.struct_size = C.sizeof(ouro_accept_desc)
+    d.B, d.T, d.gamma, d.K, d.beta = B, T, gamma, K, beta
+    d.draft_tok, d.argmax, d.meta, d.root_pred = _ptr(draft_tok), _ptr(argmax), _ptr(meta), _ptr(root_pred)
+    d.n_accept, d.path, d.bonus = _ptr(outs["n_accept"]), _ptr(outs["path"]), _ptr(outs["bonus"])
+    d.accept_idx = _ptr(outs["accept_idx"])
+    d.main_A, d.phrase_A, d.n_match = _ptr(outs.get("main_A")), _ptr(outs.get("phrase_A")), _ptr(outs.get("n_match"))
+    return d
+
+
+def alloc_accept_outputs(B: int, gamma: int, K: int, beta: int, device) -> dict:
+    i32 = dict(dtype=torch.int32, device=device)
+    return {
+        "n_accept": torch.empty(B, **i32), "path": torch.empty(B, **i32), "bonus": torch.empty(B, **i32),
+        "accept_idx": torch.empty(B, gamma + beta, **i32), "main_A": torch.empty(B, **i32),
+        "phrase_A": torch.empty(B, max(K, 1), **i32)[:, :K].contiguous() if K else torch.empty(B, 0, **i32),
+        "n_match": torch.empty(B, **i32),
+    }
+
+
+def ouro_accept(draft_tok, argmax, meta, root_pred, gamma: int, K: int, beta: int, outs=None, stream=None) -> dict:
+    """Longest-accepted-prefix decision.  draft_tok/argmax int32 [B,T]; returns dict of int32 tensors."""
+    assert draft_tok.dtype == torch.int32 and argmax.dtype == torch.int32
+    assert draft_tok.is_contiguous() and argmax.is_contiguous()
+    B, T = draft_tok.shape
+    if outs is None:
+        outs = alloc_accept_outputs(B, gamma, K, beta, draft_tok.device)
+    d = make_accept_desc(draft_tok, argmax.view(B, T), meta, root_pred, gamma, K, beta, outs)
+    _check(lib.ouro_accept(C.byref(d), _stream(stream)), "ouro_accept")
+    return outs

@@ -1,0 +1,97 @@
+// Acceptance: longest accepted prefix over the main draft and the candidate phrases
+// (Eq. (3) for A, Eq. (9) for the per-phrase run, and the selection rule after Eq. (9)).
+//
+// One 64-lane wave per sequence.  Every lane first decides match[t] for its block
+// positions (draft id == greedy token predicted by the row of the preceding token of the
+// same lengthened draft).  Lane 0 then walks the main draft, lane j walks phrase j, and a
+// wave-wide max over (length, lowest path id) picks the winner.
+#include "ouro_internal.hpp"
+
+namespace ouro {
+
+namespace {
+
+constexpr int kMaxT = 128;
+
+__global__ __launch_bounds__(64) void accept_kernel(ouro_accept_desc d) {
+  __shared__ unsigned char match[kMaxT];
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int T = d.T, gamma = d.gamma, K = d.K, beta = d.beta;
+  const int32_t* tok = d.draft_tok + static_cast<size_t>(b) * T;
+  const int32_t* arg = d.argmax + static_cast<size_t>(b) * T;
+  const ouro_tok_meta* meta = d.meta + static_cast<size_t>(b) * T;
+  const bool have_root = d.root_pred != nullptr;
+  const int32_t root = have_root ? d.root_pred[b] : -1;
+
+  for (int t = lane; t < T; t += 64) {
+    int parent;
+    if (t < gamma) {
+      parent = t - 1;                                   // main draft: previous main token (or the prefix)
+    } else {
+      const int within = (t - gamma) % beta;
+      parent = within == 0 ? static_cast<int>(meta[t].branch_off) : t - 1;
+    }
+    bool m;
+    if (parent < 0) m = have_root ? (tok[t] == root) : true;
+    else m = tok[t] == arg[parent];
+    match[t] = m ? 1 : 0;
+  }
+  __syncthreads();
+
+  // lane 0: main draft; lane j (1..K): phrase j.
+  int run = 0, start = 0, len = 0;
+  if (lane == 0) { start = 0; len = gamma; }
+  else if (lane <= K) { start = gamma + (lane - 1) * beta; len = beta; }
+  while (run < len && match[start + run]) ++run;
+
+  const int A = __shfl(run, 0);
+  int bj = -1;
+  int total = -1;
+  if (lane == 0) total = A;
+  else if (lane <= K) {
+    bj = meta[start].branch_off;
+    if (A >= bj + 1) total = bj + 1 + run;
+  }
+  // max over lanes of (total, lower lane first): key = total * 64 + (63 - lane); total >= -1.
+  int key = (total + 1) * 64 + (63 - lane);
+  for (int off = 32; off >= 1; off >>= 1) key = max(key, __shfl_xor(key, off));
+  const int win = 63 - (key & 63);
+  const int n_acc = (key >> 6) - 1;
+  const int win_b = __shfl(bj, win);
+  const int win_start = __shfl(start, win);
+
+  // accepted block indices, in order
+  const int width = gamma + beta;
+  int32_t* idx = d.accept_idx + static_cast<size_t>(b) * width;
+  const int n_main = win == 0 ? n_acc : win_b + 1;
+  for (int i = lane; i < width; i += 64) {
+    int v = -1;
+    if (i < n_acc) v = i < n_main ? i : win_start + (i - n_main);
+    idx[i] = v;
+  }
+  if (lane == 0) {
+    int last = -1;
+    if (n_acc > 0) last = (n_acc <= n_main) ? n_acc - 1 : win_start + (n_acc - n_main) - 1;
+    d.n_accept[b] = n_acc;
+    d.path[b] = win;
+    d.bonus[b] = last >= 0 ? arg[last] : root;
+    if (d.main_A) d.main_A[b] = A;
+  }
+  if (d.phrase_A && lane >= 1 && lane <= K) d.phrase_A[static_cast<size_t>(b) * K + (lane - 1)] = run;
+  if (d.n_match) {
+    int cnt = 0;
+    for (int t = lane; t < gamma; t += 64) cnt += match[t];
+    for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off);
+    if (lane == 0) d.n_match[b] = cnt;
+  }
+}
+
+}  // namespace
+
+int launch_accept(const ouro_accept_desc& d, hipStream_t stream) {
+  hipLaunchKernelGGL(accept_kernel, dim3(d.B), dim3(64), 0, stream, d);
+  return check_launch();
+}
+
+}  // namespace ouro

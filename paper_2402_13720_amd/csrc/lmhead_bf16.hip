@@ -1,0 +1,220 @@
+// bf16 LM head fused with the vocabulary arg-max, weight-streaming variant for gfx950.
+//
+// logits^T[v, r] = sum_k W[v, k] * hidden[r, k]   (Eq. (2): next-token scores of every block
+// row), then arg max over v per row r, lowest id on ties.  With R = B*T <= 128 rows the
+// product is bound by streaming W from HBM exactly once, so the kernel is organised around
+// keeping many bytes in flight per compute unit rather than around MFMA occupancy:
+//
+//   * a workgroup (4 waves) owns a slab of MT*32 vocabulary rows and NT*32 hidden rows;
+//   * the hidden dimension is cut into 64-wide k-tiles dealt round-robin to the 4 waves
+//     (split-K inside the workgroup), so the waves never synchronise in the main loop and
+//     together read 512 contiguous bytes of every W row per round;
+//   * per k-tile a wave moves its W tile (MT*32 x 64) and hidden tile (NT*32 x 64) with
+//     coalesced 16-byte loads into registers, then into its private XOR-swizzled LDS
+//     region, and issues MT*NT v_mfma_f32_32x32x16_bf16 per 16-wide k step; the loads of
+//     the wave's next k-tile are issued before the math of the current one;
+//   * after the loop the 4 partial accumulator sets are summed through LDS (fixed order),
+//     and the arg-max epilogue reduces lane -> wave -> workgroup; one (value, index) pair
+//     per (slab, row) goes to the workspace, the logits never leave the chip.
+#include <math.h>
+
+#include "ouro_internal.hpp"
+
+namespace ouro {
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef unsigned __attribute__((ext_vector_type(4))) u32x4;   // 16-byte staging register
+
+struct LmArgs {
+  const __bf16* hidden;
+  const __bf16* w;
+  float2* part;     // [nslab][R]
+  int R, Hd, V;
+};
+
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+// 16-byte slot of chunk c (0..7) of row `row` in a tile with 128-byte rows.  The XOR term
+// makes 16 lanes that read one chunk column of 16 consecutive rows hit 16 distinct banks.
+__device__ __forceinline__ int tile_slot(int row, int c) { return row * 8 + (c ^ ((row >> 1) & 7)); }
+
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int MT, int NT>
+struct LmCfg {
+  static constexpr int kWRows = MT * 32, kHRows = NT * 32;
+  static constexpr int kWaveLds = (kWRows + kHRows) * 128;        // main-loop tiles of one wave
+  static constexpr int kTiles = MT * NT;
+  static constexpr int kRedBytes = 4 * 4 * 4096;                  // reduction round: 4 waves x 4 tiles x 4 KB
+  static constexpr int kMainBytes = 4 * kWaveLds > kRedBytes ? 4 * kWaveLds : kRedBytes;
+  static constexpr int kBestOff = kMainBytes;                     // [MT][kHRows] (value, index)
+  static constexpr int kLdsBytes = kBestOff + MT * kHRows * 8;
+};
+
+template <int MT, int NT>
+__global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
+  using C = LmCfg<MT, NT>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int col = lane & 31, half = lane >> 5;
+  const int slab0 = blockIdx.x * C::kWRows;
+  const int r0 = blockIdx.y * C::kHRows;
+  const int R = a.R, Hd = a.Hd, V = a.V;
+  unsigned char* wl = lds + wave * C::kWaveLds;
+  unsigned char* hl = wl + C::kWRows * 128;
+
+  // lane (lr = lane/8, lc = lane%8) moves chunk lc of rows 8*p + lr
+  const int lr = lane >> 3, lc = lane & 7;
+  u32x4 wreg[MT * 4], hreg[NT * 4];
+  // Row pointers of this lane are fixed for the whole kernel; only the k offset moves.
+  const __bf16* wrow[MT * 4];
+  const __bf16* hrow[NT * 4];
+#pragma unroll
+  for (int p = 0; p < MT * 4; ++p)
+    wrow[p] = a.w + static_cast<size_t>(min(slab0 + 8 * p + lr, V - 1)) * Hd + 8 * lc;   // rows past V: duplicate, masked later
+#pragma unroll
+  for (int p = 0; p < NT * 4; ++p)
+    hrow[p] = a.hidden + static_cast<size_t>(min(r0 + 8 * p + lr, R - 1)) * Hd + 8 * lc;
+#define OURO_LM_ISSUE_LOADS(KT)                                                            \
+  {                                                                                        \
+    const size_t koff = static_cast<size_t>(KT) * 64;                                      \
+    _Pragma("unroll") for (int p = 0; p < MT * 4; ++p)                                     \
+        wreg[p] = *reinterpret_cast<const u32x4*>(wrow[p] + koff);                         \
+    _Pragma("unroll") for (int p = 0; p < NT * 4; ++p)                                     \
+        hreg[p] = *reinterpret_cast<const u32x4*>(hrow[p] + koff);                         \
+  }
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.f;
+
+  const int nkt = Hd / 64;
+  int kt = wave;
+  if (kt < nkt) OURO_LM_ISSUE_LOADS(kt)
+  for (; kt < nkt; kt += 4) {
+#pragma unroll
+    for (int p = 0; p < MT * 4; ++p) *reinterpret_cast<u32x4*>(wl + tile_slot(8 * p + lr, lc) * 16) = wreg[p];
+#pragma unroll
+    for (int p = 0; p < NT * 4; ++p) *reinterpret_cast<u32x4*>(hl + tile_slot(8 * p + lr, lc) * 16) = hreg[p];
+    if (kt + 4 < nkt) OURO_LM_ISSUE_LOADS(kt + 4)
+    wave_lds_fence();
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      bf16x8 af[MT], bf[NT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        af[mt] = *reinterpret_cast<const bf16x8*>(wl + tile_slot(32 * mt + col, 2 * s + half) * 16);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        bf[nt] = *reinterpret_cast<const bf16x8*>(hl + tile_slot(32 * nt + col, 2 * s + half) * 16);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bf[nt], acc[mt][nt], 0, 0, 0);
+    }
+    wave_lds_fence();
+  }
+
+#undef OURO_LM_ISSUE_LOADS
+
+  // ---- sum the 4 waves' accumulators, 4 tiles per round; wave w reduces tile 4*round + w ----
+  float* bestv = reinterpret_cast<float*>(lds + C::kBestOff);
+  int* besti = reinterpret_cast<int*>(lds + C::kBestOff + MT * C::kHRows * 4);
+  constexpr int kRounds = C::kTiles / 4;
+  static_assert(C::kTiles % 4 == 0, "tiles per wave must be a multiple of 4");
+#pragma unroll
+  for (int rd = 0; rd < kRounds; ++rd) {
+    __syncthreads();                                          // main-loop LDS (or previous round) no longer read
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      const int tile = rd * 4 + tt;
+      const int mt = tile / NT, nt = tile % NT;
+      f32x4* dst = reinterpret_cast<f32x4*>(lds) + ((wave * 4 + tt) * 4) * 64 + lane;
+#pragma unroll
+      for (int ig = 0; ig < 4; ++ig) {
+        f32x4 v4 = {acc[mt][nt][4 * ig + 0], acc[mt][nt][4 * ig + 1], acc[mt][nt][4 * ig + 2], acc[mt][nt][4 * ig + 3]};
+        dst[ig * 64] = v4;
+      }
+    }
+    __syncthreads();
+    const int tile = rd * 4 + wave;
+    const int mt = tile / NT, nt = tile % NT;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int ig = 0; ig < 4; ++ig) {
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int wv = 0; wv < 4; ++wv) sum += reinterpret_cast<const f32x4*>(lds)[((wv * 4 + wave) * 4 + ig) * 64 + lane];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int v = slab0 + 32 * mt + 8 * ig + 4 * half + e;   // accumulator register 4*ig+e of this lane
+        const float x = v < V ? sum[e] : -INFINITY;
+        if (x > bv) { bv = x; bi = v; }                          // v ascending within the lane
+      }
+    }
+    const float ov = __shfl_xor(bv, 32);
+    const int oi = __shfl_xor(bi, 32);
+    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    if (half == 0) {
+      bestv[mt * C::kHRows + 32 * nt + col] = bv;
+      besti[mt * C::kHRows + 32 * nt + col] = bi;
+    }
+  }
+  __syncthreads();
+  for (int rl = threadIdx.x; rl < C::kHRows; rl += 256) {
+    if (r0 + rl >= R) continue;
+    float bv = bestv[rl];
+    int bi = besti[rl];
+#pragma unroll
+    for (int mt = 1; mt < MT; ++mt) {
+      const float v2 = bestv[mt * C::kHRows + rl];
+      const int i2 = besti[mt * C::kHRows + rl];
+      if (better(v2, i2, bv, bi)) { bv = v2; bi = i2; }
+    }
+    a.part[static_cast<size_t>(blockIdx.x) * R + r0 + rl] = make_float2(bv, __int_as_float(bi));
+  }
+}
+
+template <int MT, int NT>
+int launch_variant(const LmArgs& a, const LmPlan& plan, hipStream_t stream) {
+  using C = LmCfg<MT, NT>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_bf16_kernel<MT, NT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+    if (e != hipSuccess) return hip_failed(e);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((lmhead_bf16_kernel<MT, NT>), dim3(plan.nslab, plan.nrtile), dim3(256), C::kLdsBytes, stream, a);
+  return check_launch();
+}
+
+}  // namespace
+
+int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream) {
+  LmArgs a{};
+  a.hidden = static_cast<const __bf16*>(d.hidden);
+  a.w = static_cast<const __bf16*>(d.w);
+  a.part = static_cast<float2*>(d.workspace);
+  a.R = d.R;
+  a.Hd = d.Hd;
+  a.V = d.V;
+  if (plan.variant == 1) return launch_variant<4, 2>(a, plan, stream);
+  return launch_variant<4, 4>(a, plan, stream);
+}
+
+}  // namespace ouro

@@ -1,0 +1,194 @@
+// Host side of the C ABI: descriptor validation, launch planning, dispatch.
+// Every check here runs before the first HIP call so that it works without a GPU.
+#include <algorithm>
+#include <cmath>
+
+#include "ouro_internal.hpp"
+
+namespace ouro {
+
+static thread_local int g_last_hip_error = 0;
+
+int hip_failed(hipError_t e) {
+  g_last_hip_error = static_cast<int>(e);
+  return OURO_E_HIP;
+}
+
+// Keys per wave work item.  A wave streams `chunk` keys of one (sequence, KV head) for its
+// query rows and leaves one fp32 partial; small chunks fill the 1024 SIMDs of the chip,
+// large chunks keep the partial traffic (rows * D * 4 bytes per item) small against the
+// K/V bytes of the chunk (chunk * D * 4 bytes).  Aim at about four items per SIMD, but
+// never less than 4 key tiles per item unless the whole sequence is shorter.
+AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
+  AttnPlan p{};
+  const int G = d.Hq / d.Hkv;
+  const int M = d.T * G;
+  p.qt = M > 32 ? 2 : 1;
+  p.rows_wave = 32 * p.qt;
+  p.nrb = (M + p.rows_wave - 1) / p.rows_wave;
+  const long maxn = static_cast<long>(d.max_seqlen) + d.T;
+  const long tiles = (maxn + 31) / 32;
+  const long groups = std::max<long>(1, static_cast<long>(d.B) * d.Hkv * p.nrb);
+  long want = (4096 + groups - 1) / groups;          // chunk slots per sequence to reach ~4 items per SIMD
+  want = std::max<long>(1, std::min(want, (tiles + 3) / 4));
+  long tiles_per_chunk = (tiles + want - 1) / want;
+  p.chunk = static_cast<int>(tiles_per_chunk * 32);
+  p.nch = static_cast<int>((maxn + p.chunk - 1) / p.chunk);
+  if (p.nch > 1) {
+    const size_t items = static_cast<size_t>(groups) * p.nch;
+    p.part_o_bytes = round_up(items * p.rows_wave * d.D * sizeof(float), 256);
+    p.part_ml_bytes = round_up(items * p.rows_wave * 2 * sizeof(float), 256);
+  }
+  return p;
+}
+
+LmPlan plan_lmhead(const ouro_lmhead_desc& d) {
+  LmPlan p{};
+  if (d.dtype == OURO_F32) {
+    p.variant = 0;
+    p.slab = 32;
+    p.rtile = 1024;
+  } else if (d.R <= 64) {
+    p.variant = 1;
+    p.slab = 128;
+    p.rtile = 64;
+  } else {
+    p.variant = 2;
+    p.slab = 128;
+    p.rtile = 128;
+  }
+  p.nslab = (d.V + p.slab - 1) / p.slab;
+  p.nrtile = (d.R + p.rtile - 1) / p.rtile;
+  p.part_bytes = round_up(static_cast<size_t>(p.nslab) * std::max(d.R, 1) * 8, 256);
+  return p;
+}
+
+static int validate_attn(const ouro_attn_desc* d, bool need_pointers) {
+  if (!d) return OURO_E_NULLPTR;
+  if (d->struct_size != sizeof(ouro_attn_desc)) return OURO_E_BAD_STRUCT;
+  if (d->dtype != OURO_F32 && d->dtype != OURO_BF16) return OURO_E_UNSUPPORTED_DTYPE;
+  if (d->B < 0 || d->B > 65535 || d->T < 1 || d->T > 128 || d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0) return OURO_E_BAD_SHAPE;
+  if (d->max_seqlen < 0) return OURO_E_BAD_SHAPE;
+  if (d->dtype == OURO_BF16 ? d->D != 128 : (d->D != 64 && d->D != 128)) return OURO_E_BAD_SHAPE;
+  if (static_cast<long>(d->T) * (d->Hq / d->Hkv) > 32768) return OURO_E_BAD_SHAPE;
+  if (!need_pointers || d->B == 0) return OURO_OK;
+  if (!d->q || !d->cu_seqlens || !d->k_blk || !d->v_blk || !d->meta || !d->out) return OURO_E_NULLPTR;
+  if (d->max_seqlen > 0 && (!d->k_cache || !d->v_cache)) return OURO_E_NULLPTR;
+  if (!aligned16(d->q) || !aligned16(d->k_cache) || !aligned16(d->v_cache) || !aligned16(d->k_blk) ||
+      !aligned16(d->v_blk) || !aligned16(d->out) || !aligned16(d->workspace))
+    return OURO_E_MISALIGNED;
+  return OURO_OK;
+}
+
+static int validate_lmhead(const ouro_lmhead_desc* d, bool need_pointers) {
+  if (!d) return OURO_E_NULLPTR;
+  if (d->struct_size != sizeof(ouro_lmhead_desc)) return OURO_E_BAD_STRUCT;
+  if (d->dtype != OURO_F32 && d->dtype != OURO_BF16) return OURO_E_UNSUPPORTED_DTYPE;
+  if (d->R < 0 || d->V < 1 || d->Hd < 1) return OURO_E_BAD_SHAPE;
+  if (d->Hd % (d->dtype == OURO_BF16 ? 64 : 4) != 0) return OURO_E_BAD_SHAPE;
+  if (!need_pointers || d->R == 0) return OURO_OK;
+  if (!d->hidden || !d->w || !d->argmax_out) return OURO_E_NULLPTR;
+  if (!aligned16(d->hidden) || !aligned16(d->w) || !aligned16(d->workspace)) return OURO_E_MISALIGNED;
+  return OURO_OK;
+}
+
+static int validate_accept(const ouro_accept_desc* d) {
+  if (!d) return OURO_E_NULLPTR;
+  if (d->struct_size != sizeof(ouro_accept_desc)) return OURO_E_BAD_STRUCT;
+  if (d->B < 0 || d->gamma < 1 || d->K < 0 || d->K > 63 || d->beta < 0 || d->T < 1 || d->T > 128) return OURO_E_BAD_SHAPE;
+  if (static_cast<long>(d->gamma) + static_cast<long>(d->K) * d->beta != d->T) return OURO_E_BAD_SHAPE;
+  if (d->K > 0 && d->beta < 1) return OURO_E_BAD_SHAPE;
+  if (d->B == 0) return OURO_OK;
+  if (!d->draft_tok || !d->argmax || !d->meta || !d->n_accept || !d->path || !d->bonus || !d->accept_idx)
+    return OURO_E_NULLPTR;
+  return OURO_OK;
+}
+
+}  // namespace ouro
+
+using namespace ouro;
+
+extern "C" {
+
+size_t ouro_verify_attn_workspace(const ouro_attn_desc* desc) {
+  if (validate_attn(desc, false) != OURO_OK || desc->dtype != OURO_BF16 || desc->B == 0) return 0;
+  AttnPlan p = plan_attn_bf16(*desc);
+  return p.part_o_bytes + p.part_ml_bytes;
+}
+
+int ouro_verify_attn(const ouro_attn_desc* desc, void* hip_stream) {
+  int st = validate_attn(desc, true);
+  if (st != OURO_OK) return st;
+  if (desc->B == 0) return OURO_OK;
+  const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / std::sqrt(static_cast<float>(desc->D));
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (desc->dtype == OURO_F32) return launch_attn_f32(*desc, scale, stream);
+  AttnPlan p = plan_attn_bf16(*desc);
+  const size_t need = p.part_o_bytes + p.part_ml_bytes;
+  if (need > 0) {
+    if (!desc->workspace) return OURO_E_NULLPTR;
+    if (desc->workspace_bytes < need) return OURO_E_WORKSPACE_TOO_SMALL;
+  }
+  return launch_attn_bf16(*desc, p, scale, stream);
+}
+
+size_t ouro_lmhead_argmax_workspace(const ouro_lmhead_desc* desc) {
+  if (validate_lmhead(desc, false) != OURO_OK || desc->R == 0) return 0;
+  return plan_lmhead(*desc).part_bytes;
+}
+
+int ouro_lmhead_argmax(const ouro_lmhead_desc* desc, void* hip_stream) {
+  int st = validate_lmhead(desc, true);
+  if (st != OURO_OK) return st;
+  if (desc->R == 0) return OURO_OK;
+  LmPlan p = plan_lmhead(*desc);
+  if (!desc->workspace) return OURO_E_NULLPTR;
+  if (desc->workspace_bytes < p.part_bytes) return OURO_E_WORKSPACE_TOO_SMALL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  st = desc->dtype == OURO_F32 ? launch_lmhead_f32(*desc, p, stream) : launch_lmhead_bf16(*desc, p, stream);
+  if (st != OURO_OK) return st;
+  return launch_lmhead_final(*desc, p, stream);
+}
+
+int ouro_accept(const ouro_accept_desc* desc, void* hip_stream) {
+  int st = validate_accept(desc);
+  if (st != OURO_OK) return st;
+  if (desc->B == 0) return OURO_OK;
+  return launch_accept(*desc, static_cast<hipStream_t>(hip_stream));
+}
+
+int ouro_validate_meta_host(const ouro_tok_meta* m, int32_t T, int32_t gamma, int32_t K, int32_t beta) {
+  if (!m) return OURO_E_NULLPTR;
+  if (T < 1 || gamma < 1 || K < 0 || beta < 0 || static_cast<long>(gamma) + static_cast<long>(K) * beta != T)
+    return OURO_E_BAD_SHAPE;
+  for (int i = 0; i < gamma; ++i)
+    if (m[i].phrase_id != 0 || m[i].branch_off != i) return OURO_E_BAD_META;
+  for (int j = 1; j <= K; ++j) {
+    const int lo = gamma + (j - 1) * beta;
+    const int bj = m[lo].branch_off;
+    if (bj < -1 || bj >= gamma) return OURO_E_BAD_META;
+    for (int i = 0; i < beta; ++i)
+      if (m[lo + i].phrase_id != j || m[lo + i].branch_off != bj) return OURO_E_BAD_META;
+  }
+  return OURO_OK;
+}
+
+const char* ouro_status_string(int status) {
+  switch (status) {
+    case OURO_OK: return "ok";
+    case OURO_E_NULLPTR: return "a required pointer is NULL";
+    case OURO_E_BAD_SHAPE: return "a size is out of range or inconsistent";
+    case OURO_E_UNSUPPORTED_DTYPE: return "unsupported dtype";
+    case OURO_E_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case OURO_E_MISALIGNED: return "a pointer is not 16-byte aligned";
+    case OURO_E_HIP: return "a HIP call failed";
+    case OURO_E_BAD_STRUCT: return "struct_size does not match the header";
+    case OURO_E_BAD_META: return "block metadata violates the layout rules";
+    default: return "unknown status";
+  }
+}
+
+int ouro_last_hip_error(void) { return g_last_hip_error; }
+int ouro_version(void) { return OURO_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,55 @@
+// Internal declarations shared by the translation units of libouro (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ouro.h"
+
+namespace ouro {
+
+// Records a failed HIP call for ouro_last_hip_error() and returns OURO_E_HIP.
+int hip_failed(hipError_t e);
+
+inline int check_launch() {
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? OURO_OK : hip_failed(e);
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- attention ------------------------------------------------------------------------
+// Launch plan of the bf16 split-KV kernel, derived on the host from shapes only.
+struct AttnPlan {
+  int qt;          // 32-row query tiles per wave (1 or 2)
+  int rows_wave;   // 32 * qt
+  int nrb;         // row blocks per (sequence, KV head): ceil(T * G / rows_wave)
+  int chunk;       // keys per wave work item (multiple of 32)
+  int nch;         // chunk slots per sequence: ceil((max_seqlen + T) / chunk)
+  size_t part_o_bytes;   // fp32 partial outputs
+  size_t part_ml_bytes;  // fp32 (max, sum) pairs
+};
+AttnPlan plan_attn_bf16(const ouro_attn_desc& d);
+
+int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale, hipStream_t stream);
+int launch_attn_f32(const ouro_attn_desc& d, float scale, hipStream_t stream);
+
+// ---- LM head --------------------------------------------------------------------------
+struct LmPlan {
+  int variant;     // 0: fp32 VALU, 1: bf16 skinny (R tile 64), 2: bf16 skinny (R tile 128)
+  int slab;        // vocabulary rows per workgroup
+  int nslab;       // ceil(V / slab)
+  int rtile;       // rows per grid.y slice
+  int nrtile;
+  size_t part_bytes;   // [nslab][R] (float value, int32 index) pairs
+};
+LmPlan plan_lmhead(const ouro_lmhead_desc& d);
+int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
+int launch_lmhead_f32(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
+int launch_lmhead_final(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
+
+// ---- acceptance -----------------------------------------------------------------------
+int launch_accept(const ouro_accept_desc& d, hipStream_t stream);
+
+}  // namespace ouro

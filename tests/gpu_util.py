@@ -1,0 +1,42 @@
+"""Helpers shared by the GPU parity tests: upload seeded host inputs, call the C ABI through the binding."""
+import numpy as np
+import torch
+
+from paper_2402_13720_amd import workloads as W
+
+DEV = "cuda:0"
+
+
+def torch_dtype(cfg):
+    return torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+
+
+def upload_attention(cfg, inp):
+    from paper_2402_13720_amd import binding as ob
+    dt = torch_dtype(cfg)
+    t = {}
+    for k in ("q", "k_cache", "v_cache", "k_blk", "v_blk"):
+        t[k] = torch.from_numpy(inp[k]).to(DEV).to(dt).contiguous()
+    t["cu_seqlens"] = torch.from_numpy(inp["cu_seqlens"]).to(DEV)
+    t["meta"] = ob.pack_meta(inp["pid"], inp["boff"]).to(DEV)
+    t["max_seqlen"] = int(np.diff(inp["cu_seqlens"]).max()) if cfg.B else 0
+    return t
+
+
+def run_attention(cfg, inp, want_lse=True, max_seqlen=None):
+    from paper_2402_13720_amd import binding as ob
+    t = upload_attention(cfg, inp)
+    lse = torch.full((cfg.B, cfg.Hq, cfg.T), float("nan"), dtype=torch.float32, device=DEV) if want_lse else None
+    out = ob.ouro_verify_attn(t["q"], t["k_cache"], t["v_cache"], t["cu_seqlens"], t["k_blk"], t["v_blk"], t["meta"],
+                              max_seqlen=t["max_seqlen"] if max_seqlen is None else max_seqlen, lse=lse)
+    torch.cuda.synchronize()
+    return out, lse, t
+
+
+def to_np64(x):
+    return x.detach().float().cpu().numpy().astype(np.float64)
+
+
+def attn_tol(cfg):
+    # spec tolerances: max-abs 2e-2 for bf16 outputs, 1e-5 for fp32
+    return 2e-2 if cfg.dtype == "bf16" else 1e-5

@@ -1,0 +1,145 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad descriptors before touching HIP."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+ob = pytest.importorskip("paper_2402_13720_amd.binding", reason="libouro.so not built")
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "ouro.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ouro_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert {"ouro_verify_attn", "ouro_lmhead_argmax", "ouro_accept", "ouro_verify_attn_workspace",
+            "ouro_lmhead_argmax_workspace", "ouro_validate_meta_host", "ouro_status_string",
+            "ouro_last_hip_error", "ouro_version"} <= set(names)
+    for n in names:
+        assert hasattr(ob.lib, n), n
+
+
+def test_version_and_status_strings():
+    assert ob.lib.ouro_version() == 100
+    assert ob.lib.ouro_status_string(0) == b"ok"
+    for code in range(-8, 0):
+        assert ob.lib.ouro_status_string(code) not in (b"ok", b"unknown status")
+    assert ob.lib.ouro_status_string(-99) == b"unknown status"
+
+
+def test_struct_sizes_match_the_header_layout():
+    # 8 int32 + 7 pointers + float(+pad) + 4 pointers/size_t
+    assert C.sizeof(ob.ouro_attn_desc) == 32 + 7 * 8 + 8 + 4 * 8
+    assert C.sizeof(ob.ouro_lmhead_desc) == 24 + 6 * 8
+    assert C.sizeof(ob.ouro_accept_desc) == 24 + 11 * 8
+
+
+def _attn_desc(**kw):
+    d = ob.ouro_attn_desc()
+    d.struct_size = C.sizeof(ob.ouro_attn_desc)
+    d.dtype, d.B, d.T, d.Hq, d.Hkv, d.D, d.max_seqlen = ob.OURO_BF16, 1, 64, 32, 32, 128, 2048
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_attn_descriptor_validation_runs_before_any_hip_call():
+    f = ob.lib.ouro_verify_attn
+    assert f(None, None) == -1
+    assert f(C.byref(_attn_desc(struct_size=8)), None) == -7
+    assert f(C.byref(_attn_desc(dtype=5)), None) == -3
+    assert f(C.byref(_attn_desc(T=0)), None) == -2
+    assert f(C.byref(_attn_desc(T=129)), None) == -2
+    assert f(C.byref(_attn_desc(Hq=32, Hkv=5)), None) == -2
+    assert f(C.byref(_attn_desc(D=64)), None) == -2                      # bf16 needs D = 128
+    assert f(C.byref(_attn_desc(max_seqlen=-1)), None) == -2
+    assert f(C.byref(_attn_desc()), None) == -1                          # data pointers are NULL
+    assert f(C.byref(_attn_desc(B=0)), None) == 0                        # nothing to do
+    ok = dict(q=256, k_cache=256, v_cache=256, cu_seqlens=256, k_blk=256, v_blk=256, meta=256, out=256)
+    assert f(C.byref(_attn_desc(**{**ok, "q": 260})), None) == -5        # misaligned
+    assert f(C.byref(_attn_desc(**ok)), None) == -1                      # workspace needed but NULL
+    assert f(C.byref(_attn_desc(**ok, workspace=256, workspace_bytes=16)), None) == -4
+
+
+def test_attn_workspace_query():
+    ws = ob.lib.ouro_verify_attn_workspace
+    assert ws(None) == 0
+    assert ws(C.byref(_attn_desc(T=0))) == 0
+    n = ws(C.byref(_attn_desc()))
+    assert n > 0 and n % 256 == 0
+    assert ws(C.byref(_attn_desc(dtype=ob.OURO_F32))) == 0
+    assert ws(C.byref(_attn_desc(max_seqlen=0, T=16))) == 0              # single chunk: no partials
+    assert ws(C.byref(_attn_desc(B=16, max_seqlen=8192, T=32))) > n
+
+
+def _lm_desc(**kw):
+    d = ob.ouro_lmhead_desc()
+    d.struct_size = C.sizeof(ob.ouro_lmhead_desc)
+    d.dtype, d.R, d.Hd, d.V = ob.OURO_BF16, 64, 4096, 32000
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_lmhead_descriptor_validation():
+    f = ob.lib.ouro_lmhead_argmax
+    assert f(None, None) == -1
+    assert f(C.byref(_lm_desc(struct_size=4)), None) == -7
+    assert f(C.byref(_lm_desc(dtype=2)), None) == -3
+    assert f(C.byref(_lm_desc(Hd=4000 + 8)), None) == -2                 # bf16: Hd multiple of 64
+    assert f(C.byref(_lm_desc(V=0)), None) == -2
+    assert f(C.byref(_lm_desc(R=0)), None) == 0
+    assert f(C.byref(_lm_desc()), None) == -1
+    ok = dict(hidden=512, w=512, argmax_out=512)
+    assert f(C.byref(_lm_desc(**ok)), None) == -1                        # workspace NULL
+    assert f(C.byref(_lm_desc(**ok, workspace=512, workspace_bytes=8)), None) == -4
+    need = ob.lib.ouro_lmhead_argmax_workspace(C.byref(_lm_desc()))
+    assert need >= 250 * 64 * 8
+
+
+def _acc_desc(**kw):
+    d = ob.ouro_accept_desc()
+    d.struct_size = C.sizeof(ob.ouro_accept_desc)
+    d.B, d.T, d.gamma, d.K, d.beta = 1, 64, 16, 8, 6
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_accept_descriptor_validation():
+    f = ob.lib.ouro_accept
+    assert f(None, None) == -1
+    assert f(C.byref(_acc_desc(struct_size=1)), None) == -7
+    assert f(C.byref(_acc_desc(T=63)), None) == -2                       # T != gamma + K*beta
+    assert f(C.byref(_acc_desc(gamma=0, T=48)), None) == -2
+    assert f(C.byref(_acc_desc(K=64, beta=1, gamma=64, T=128)), None) == -2
+    assert f(C.byref(_acc_desc()), None) == -1
+    assert f(C.byref(_acc_desc(B=0)), None) == 0
+
+
+def test_validate_meta_host():
+    from paper_2402_13720_amd import workloads as W
+    cfg = W.CONFIGS[2]
+    pid, boff = W.make_block_meta(cfg, np.random.default_rng(0))
+    meta = np.stack([pid[0], boff[0]], axis=-1).astype(np.int16).copy()
+    f = ob.lib.ouro_validate_meta_host
+    p = meta.ctypes.data_as(C.c_void_p)
+    assert f(p, cfg.T, cfg.gamma, cfg.K, cfg.beta_p) == 0
+    assert f(None, cfg.T, cfg.gamma, cfg.K, cfg.beta_p) == -1
+    assert f(p, cfg.T + 1, cfg.gamma, cfg.K, cfg.beta_p) == -2
+    bad = meta.copy(); bad[3, 1] = 2                                     # main token with wrong branch_off
+    assert f(bad.ctypes.data_as(C.c_void_p), cfg.T, cfg.gamma, cfg.K, cfg.beta_p) == -8
+    bad = meta.copy(); bad[cfg.gamma + 1, 0] = 5                         # phrase id broken inside a phrase
+    assert f(bad.ctypes.data_as(C.c_void_p), cfg.T, cfg.gamma, cfg.K, cfg.beta_p) == -8
+    bad = meta.copy(); bad[cfg.gamma:cfg.gamma + cfg.beta_p, 1] = cfg.gamma   # branch beyond the main draft
+    assert f(bad.ctypes.data_as(C.c_void_p), cfg.T, cfg.gamma, cfg.K, cfg.beta_p) == -8
+    ok = meta.copy(); ok[cfg.gamma:cfg.gamma + cfg.beta_p, 1] = -1       # phrase hanging off the prefix
+    assert f(ok.ctypes.data_as(C.c_void_p), cfg.T, cfg.gamma, cfg.K, cfg.beta_p) == 0

@@ -1,0 +1,118 @@
+"""GPU parity: ouro_verify_attn (through the C ABI) against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import verify_oracle as O
+from paper_2402_13720_amd import workloads as W
+from gpu_util import DEV, attn_tol, run_attention, to_np64
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle(inp, heads=None):
+    return O.verify_attention(inp["q"], inp["k_cache"], inp["v_cache"], inp["cu_seqlens"], inp["k_blk"], inp["v_blk"],
+                              inp["pid"], inp["boff"], heads=heads)
+
+
+def _check(cfg, inp, heads=None, lse_tol=None):
+    out, lse, _ = run_attention(cfg, inp)
+    ref = _oracle(inp, heads)
+    got = to_np64(out)
+    got_lse = to_np64(lse)
+    assert np.isfinite(got).all()
+    if heads is None:
+        err = np.abs(got - ref["out"]).max()
+        lerr = np.abs(got_lse - ref["lse"]).max()
+    else:
+        err = max(np.abs(got[b, :, h] - ref["out"][b, :, h]).max() for b, h in heads)
+        lerr = max(np.abs(got_lse[b, h] - ref["lse"][b, h]).max() for b, h in heads)
+    print("%s: max-abs err %.3g, lse err %.3g" % (cfg.name, err, lerr), flush=True)
+    assert err <= attn_tol(cfg), err
+    assert lerr <= (lse_tol or (1e-2 if cfg.dtype == "bf16" else 1e-5)), lerr
+    return out
+
+
+def test_config1_fp32_tiny():
+    cfg = W.CONFIGS[1]
+    for trial in range(3):
+        _check(cfg, W.make_attention_inputs(cfg, W.seed_for(1, trial)))
+
+
+@pytest.mark.parametrize("kw", [
+    dict(D=128, Hq=4, Hkv=2, B=3, L=(0, 70)),
+    dict(D=64, Hq=6, Hkv=1, B=2, L=(60, 130), gamma=5, K=3, beta_p=7),
+    dict(D=64, B=2, L=(0, 0)),
+    dict(D=128, gamma=9, K=0, beta_p=0, L=33),
+])
+def test_fp32_shapes(kw):
+    cfg = W.scaled(W.CONFIGS[1], **kw)
+    _check(cfg, W.make_attention_inputs(cfg, 77))
+
+
+@pytest.mark.parametrize("kw", [
+    dict(B=2, Hq=4, Hkv=2, L=(0, 300), gamma=10, K=5, beta_p=6),        # 80 rows per KV head: 2 row blocks, ragged
+    dict(B=3, Hq=2, Hkv=2, L=(1, 200), gamma=3, K=2, beta_p=4),         # 11 rows: one partially filled tile
+    dict(B=1, Hq=8, Hkv=1, L=517, gamma=16, K=8, beta_p=6),             # GQA 8: 512 rows, 8 row blocks
+    dict(B=2, Hq=2, Hkv=2, L=(0, 0), gamma=8, K=4, beta_p=6),           # empty cache
+    dict(B=1, Hq=2, Hkv=2, L=1000, gamma=32, K=16, beta_p=6),           # T = 128
+    dict(B=4, Hq=2, Hkv=1, L=(30, 2000), gamma=8, K=4, beta_p=6),       # very uneven lengths
+    dict(B=1, Hq=1, Hkv=1, L=95, gamma=1, K=0, beta_p=0),               # a single row
+])
+@pytest.mark.parametrize("branch", ["uniform", "last"])
+def test_bf16_small_shapes(kw, branch):
+    cfg = W.scaled(W.CONFIGS[2], **kw)
+    _check(cfg, W.make_attention_inputs(cfg, 1234, branch=branch))
+
+
+def test_bf16_phrase_hanging_off_the_prefix():
+    cfg = W.scaled(W.CONFIGS[2], B=1, Hq=2, Hkv=2, L=70, gamma=4, K=3, beta_p=5)
+    inp = W.make_attention_inputs(cfg, 5)
+    inp["boff"][0, cfg.gamma:cfg.gamma + cfg.beta_p] = -1
+    _check(cfg, inp)
+
+
+def test_bf16_max_seqlen_hint_may_exceed_actual_lengths():
+    cfg = W.scaled(W.CONFIGS[2], B=2, Hq=2, Hkv=2, L=(10, 100))
+    inp = W.make_attention_inputs(cfg, 6)
+    a, _, _ = run_attention(cfg, inp)
+    b, _, _ = run_attention(cfg, inp, max_seqlen=4096)
+    ref = _oracle(inp)["out"]
+    assert np.abs(to_np64(a) - ref).max() <= 2e-2 and np.abs(to_np64(b) - ref).max() <= 2e-2
+
+
+def test_bf16_mask_probe_through_the_kernel():
+    """Q = 0 and V = one-hot(key index): output * (number of visible keys) is the mask row (closed form)."""
+    cfg = W.scaled(W.CONFIGS[2], B=1, Hq=1, Hkv=1, L=64, gamma=16, K=8, beta_p=6)
+    inp = W.make_attention_inputs(cfg, 8)
+    inp["q"][:] = 0
+    eye = np.eye(128, dtype=np.float32)
+    inp["v_cache"] = eye[:64, None, :].copy()
+    inp["v_blk"] = eye[None, 64:, None, :].copy()
+    out, lse, _ = run_attention(cfg, inp)
+    nvis = np.exp(to_np64(lse)[0, 0])                     # scores are all zero: lse = log(#visible)
+    rec = np.rint(to_np64(out)[0, :, 0, :] * nvis[:, None])
+    want = O.dense_mask(inp["pid"][0], inp["boff"][0], 64).astype(float)
+    assert np.array_equal(rec, want)
+    assert np.allclose(nvis, want.sum(1), atol=1e-3)
+
+
+@pytest.mark.parametrize("cfg_id", [2, 3, 4])
+def test_full_size_configs(cfg_id):
+    cfg = W.CONFIGS[cfg_id]
+    inp = W.make_attention_inputs(cfg, W.seed_for(cfg_id))
+    heads = None if cfg_id == 2 else [(0, h) for h in range(0, cfg.Hq, 5)]
+    out = _check(cfg, inp, heads)
+    # run-to-run determinism (fixed merge order, no float atomics)
+    out2, _, _ = run_attention(cfg, inp)
+    assert torch.equal(out, out2)
+
+
+def test_full_size_config5_sampled_heads():
+    cfg = W.CONFIGS[5]
+    inp = W.make_attention_inputs(cfg, W.seed_for(5))
+    lens = np.diff(inp["cu_seqlens"])
+    order = np.argsort(lens)
+    seqs = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]       # shortest, median, longest sequence
+    heads = [(b, h) for b in seqs for h in (0, 13, 31)]
+    _check(cfg, inp, heads)
