@@ -164,8 +164,8 @@ def main():
     out = torch.empty_like(q)
     hidden = out.view(cfg.R, cfg.hidden)
     arg = torch.empty(cfg.R, dtype=torch.int32, device=dev)
-    ws_attn = torch.empty(max(ob.ouro_verify_attn_workspace(q, k_blk, max_seqlen), 256), dtype=torch.uint8, device=dev)
-    ws_lm = torch.empty(max(ob.ouro_lmhead_argmax_workspace(hidden, w0), 256), dtype=torch.uint8, device=dev)
+    ws_attn = ob.alloc_workspace(ob.ouro_verify_attn_workspace(q, k_blk, max_seqlen), dev)
+    ws_lm = ob.alloc_workspace(ob.ouro_lmhead_argmax_workspace(hidden, w0), dev)
     acc_out = ob.alloc_accept_outputs(cfg.B, cfg.gamma, cfg.K, cfg.beta_p, dev)
 
     # draft ids: half of the block positions carry the token they will be compared with (the greedy
@@ -187,20 +187,30 @@ def main():
     tok = torch.from_numpy(W.plant_tokens(draws["tok"], draws["chosen"], exp)).to(dev)
 
     stream = torch.cuda.current_stream()
+    hs = stream.cuda_stream or None
+    import ctypes as C
+    # descriptors are built once per rotated copy; a step is then three C-ABI calls
+    d_attn = [ob.make_attn_desc(q, kcs[r], vcs[r], cu, k_blk, v_blk, meta, out, max_seqlen, None, ws_attn)
+              for r in range(nrot)]
+    d_lm = [ob.make_lmhead_desc(hidden, ws[r], arg, None, ws_lm) for r in range(nrot)]
+    d_acc = ob.make_accept_desc(tok, arg.view(cfg.B, cfg.T), meta, root, cfg.gamma, cfg.K, cfg.beta_p, acc_out)
+    f_attn, f_lm, f_acc = ob.lib.ouro_verify_attn, ob.lib.ouro_lmhead_argmax, ob.lib.ouro_accept
 
     def step(i, ev=None):
         r = i % nrot
         if ev is not None:
             ev[0].record(stream)
-        ob.ouro_verify_attn(q, kcs[r], vcs[r], cu, k_blk, v_blk, meta, max_seqlen, out=out, workspace=ws_attn)
+        st = f_attn(C.byref(d_attn[r]), hs)
         if ev is not None:
             ev[1].record(stream)
-        ob.ouro_lmhead_argmax(hidden, ws[r], argmax_out=arg, workspace=ws_lm)
+        st |= f_lm(C.byref(d_lm[r]), hs)
         if ev is not None:
             ev[2].record(stream)
-        ob.ouro_accept(tok, arg.view(cfg.B, cfg.T), meta, root, cfg.gamma, cfg.K, cfg.beta_p, outs=acc_out)
+        st |= f_acc(C.byref(d_acc), hs)
         if ev is not None:
             ev[3].record(stream)
+        if st != 0:
+            raise RuntimeError("a verification-step call failed (status bits %d)" % st)
 
     for i in range(args.warmup):
         step(i)

@@ -66,6 +66,8 @@ def _load() -> C.CDLL:
     lib.ouro_lmhead_argmax.argtypes = [C.POINTER(ouro_lmhead_desc), C.c_void_p]
     lib.ouro_accept.restype = C.c_int
     lib.ouro_accept.argtypes = [C.POINTER(ouro_accept_desc), C.c_void_p]
+    lib.ouro_workspace_init.restype = C.c_int
+    lib.ouro_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
     lib.ouro_validate_meta_host.restype = C.c_int
     lib.ouro_validate_meta_host.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.ouro_status_string.restype = C.c_char_p
@@ -116,6 +118,17 @@ def pack_meta(pid, boff) -> torch.Tensor:
     return torch.stack([pid, boff], dim=-1).contiguous()
 
 
+def alloc_workspace(nbytes: int, device) -> torch.Tensor:
+    """A zero-filled workspace (the library keeps ticket counters at its start; they must start at zero)."""
+    return torch.zeros(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def ouro_workspace_init(workspace: torch.Tensor, stream=None) -> None:
+    """Re-zero the counter area of a workspace (needed only after a call that did not complete)."""
+    _check(lib.ouro_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "ouro_workspace_init")
+
+
 def make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen,
                    lse=None, workspace=None, softmax_scale: float = 0.0) -> ouro_attn_desc:
     B, T, Hq, D = q.shape
@@ -155,7 +168,7 @@ def ouro_verify_attn(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, max_se
     if workspace is None:
         need = ouro_verify_attn_workspace(q, k_blk, max_seqlen)
         if need:
-            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+            workspace = alloc_workspace(need, q.device)
     d = make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen, lse, workspace,
                        softmax_scale)
     _check(lib.ouro_verify_attn(C.byref(d), _stream(stream)), "ouro_verify_attn")
@@ -185,8 +198,7 @@ def ouro_lmhead_argmax(hidden, w, argmax_out=None, max_out=None, workspace=None,
     if argmax_out is None:
         argmax_out = torch.empty(hidden.shape[0], dtype=torch.int32, device=hidden.device)
     if workspace is None:
-        need = ouro_lmhead_argmax_workspace(hidden, w)
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=hidden.device)
+        workspace = alloc_workspace(ouro_lmhead_argmax_workspace(hidden, w), hidden.device)
     d = make_lmhead_desc(hidden, w, argmax_out, max_out, workspace)
     _check(lib.ouro_lmhead_argmax(C.byref(d), _stream(stream)), "ouro_lmhead_argmax")
     return argmax_out

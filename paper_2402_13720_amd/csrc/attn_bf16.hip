@@ -1,4 +1,4 @@
-// bf16 draft-block attention for gfx950: split-KV, one independent wave per work item.
+// bf16 draft-block attention for gfx950: split-KV with in-workgroup key splitting.
 //
 // What is computed (Sec. 3.2, Eq. (8)): every block row attends to the whole cached prefix
 // of its sequence plus the block tokens of its own lengthened draft.  The block part of the
@@ -7,8 +7,10 @@
 //
 // Work decomposition.  Query rows of one (sequence, KV head) are the T*G rows of the G query
 // heads sharing that KV head (row = t*G + head_in_group), cut into row blocks of 32*QT rows.
-// The key axis [cache | block] is cut into chunks.  One 64-lane wave owns one
-// (sequence, KV head, chunk, row block) item and runs a flash-style loop over 32-key tiles:
+// The key axis [cache | block] is cut into chunks.  One workgroup (4 waves) owns one
+// (sequence, KV head, chunk, row block); its waves take the chunk's 32-key tiles round-robin,
+// so together they stream one contiguous window of K and V.  Each wave runs a flash-style
+// loop on its own tiles without ever synchronising with the other waves:
 //
 //   global --coalesced 16B loads--> registers --> wave-private LDS (K row-major swizzled,
 //   V transposed with in-register byte-permutes) --> MFMA operands
@@ -20,14 +22,16 @@
 //                                    S^T already is a valid B-operand layout, with the key
 //                                    order of V^T permuted to match when V is transposed)
 //
-// Waves never synchronise with each other (no s_barrier): each wave has its own LDS region
-// and LDS operations of one wave execute in order.  The next tile's global loads are issued
-// before the current tile's math, so a wave keeps 16 KB in flight.
-// If a sequence spans several chunks every item leaves an un-normalised fp32 partial
-// (O, running max, running sum); a second kernel merges the partials of a row in fixed
-// chunk order (deterministic) and writes bf16.
+// The next tile's global loads are issued before the current tile's math.  After the loop
+// the 4 wave states (O, running max, running sum) are merged pairwise through LDS, staged
+// row-major in LDS and written with coalesced 16-byte stores.  A sequence that spans several
+// chunks leaves one fp32 partial per workgroup; the workgroup that finishes last for a
+// (sequence, KV head, row block) -- found with a ticket counter in the workspace -- merges
+// the partials in ascending chunk order (deterministic) and writes bf16.  One launch.
+//
+// Workgroup ids are mapped so that workgroups reading the same K/V window (different row
+// blocks) are congruent modulo 8, i.e. land on the same XCD and share its L2.
 #include <math.h>
-#include <stdlib.h>
 
 #include "ouro_internal.hpp"
 
@@ -36,18 +40,17 @@ namespace ouro {
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(8 * sizeof(float)))) float f32x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
 typedef unsigned __attribute__((ext_vector_type(4))) u32x4;   // 16-byte staging register
 
 constexpr int kD = 128;
 constexpr int kKBytes = 32 * 256;             // K tile, 16-byte slots XOR-swizzled by row (no padding)
 constexpr int kVtBytes = 128 * 32 * 2;        // V^T tile, swizzled 16-byte slots
 constexpr int kWaveLds = kKBytes + kVtBytes;  // 16 KB per wave, 64 KB per workgroup
+constexpr int kStageRow = 132;                // floats per staged output row (128 + 4 pad: conflict-free 16B column writes)
+constexpr float kLn2 = 0.6931471805599453f;
 
 struct AttnArgs {
   const __bf16* q;
@@ -59,12 +62,24 @@ struct AttnArgs {
   const ouro_tok_meta* meta;
   __bf16* out;
   float* lse;
-  float* part_o;   // [group][chunk][rows_wave][128]
-  float* part_ml;  // [group][chunk][rows_wave][2]
-  long n_items;
+  unsigned* counters;  // [groups], zero on entry, zero on exit
+  float* part_ml;      // [group][chunk][rows_wg][2]
+  float* part_o;       // [group][chunk][rows_wg][128]
+  int n_x;             // B * Hkv * nch
   int T, Hq, Hkv, G, M;
   int nrb, nch, chunk;
   float scale_log2;
+};
+
+constexpr int cmax(int x, int y) { return x > y ? x : y; }
+
+template <int QT>
+struct AttnCfg {
+  static constexpr int kRows = 32 * QT;
+  static constexpr int kStateBytes = QT * 16 * 64 * 16;                 // O accumulators of one wave, lane-major
+  static constexpr int kMergeBytes = 2 * kStateBytes + 2 * QT * 64 * 8;  // two slots + their (max, sum) pairs
+  static constexpr int kStageBytes = kRows * kStageRow * 4 + kRows * 8;
+  static constexpr int kLdsBytes = cmax(cmax(4 * kWaveLds, kMergeBytes), kStageBytes);
 };
 
 // Slot (16 bytes = 8 keys of one head-dim element d) of the transposed V tile.
@@ -87,22 +102,29 @@ __device__ __forceinline__ void wave_lds_fence() {
 
 template <int QT>
 __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[4 * kWaveLds];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const long item = static_cast<long>(blockIdx.x) * 4 + wave;
-  if (item >= a.n_items) return;
-  const int rb = static_cast<int>(item % a.nrb);
-  const long tmp = item / a.nrb;
-  const int chunk = static_cast<int>(tmp % a.nch);
-  const int bg = static_cast<int>(tmp / a.nch);
+  using C = AttnCfg<QT>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  __shared__ unsigned s_ticket;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+
+  // ---- workgroup id -> (x = (sequence, KV head, chunk), row block); same x => same id modulo 8 ----
+  const int per = 8 * a.nrb;
+  const int blk = blockIdx.x / per, rem = blockIdx.x - blk * per;
+  const int rb = rem >> 3;
+  const int x = blk * 8 + (rem & 7);
+  if (x >= a.n_x) return;
+  const int chunk = x % a.nch;
+  const int bg = x / a.nch;
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
   const long cu0 = a.cu[b];
   const int L = static_cast<int>(a.cu[b + 1] - cu0);
   const int T = a.T;
   const int n = L + T;
   const int k_begin = chunk * a.chunk;
-  if (k_begin >= n) return;                       // chunk slot beyond this sequence
+  if (k_begin >= n) return;                       // chunk slot beyond this sequence (uniform for the workgroup)
   const int k_end = min(n, k_begin + a.chunk);
+  const int nchb = (n + a.chunk - 1) / a.chunk;   // chunks this sequence really has
 
   unsigned char* kl = lds + wave * kWaveLds;
   unsigned char* vl = kl + kKBytes;
@@ -111,11 +133,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
 
   // ---- query fragments (B operand of S^T = K . Q^T) and the row's metadata ----
   bf16x8 qf[QT][8];
-  int tq[QT], pidq[QT], boffq[QT], rowq[QT];
+  int tq[QT], pidq[QT], boffq[QT];
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
-    const int r = rb * (32 * QT) + qt * 32 + col;
-    rowq[qt] = r;
+    const int r = rb * C::kRows + qt * 32 + col;
     const int rr = min(r, M - 1);                 // rows past M are computed on a duplicate and never stored
     const int t = rr / G, hh = rr - t * G;
     const __bf16* qp = a.q + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
@@ -157,8 +178,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
       for (int i = 0; i < 16; ++i) o[qt][dt][i] = 0.f;
   }
 
-  OURO_ATTN_ISSUE_LOADS(k_begin)
-  for (int tile = k_begin; tile < k_end; tile += 32) {
+  // this wave's tiles: k_begin + 32*(wave + 4*i)
+  int tile = k_begin + 32 * wave;
+  if (tile < k_end) OURO_ATTN_ISSUE_LOADS(tile)
+  for (; tile < k_end; tile += 128) {
     // ---- registers -> LDS ----
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -174,23 +197,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
       t4.w = __builtin_amdgcn_perm(dword_of(vr[7], j >> 1), dword_of(vr[6], j >> 1), sel);
       *reinterpret_cast<u32x4*>(vl + vt_slot(c16, j, kq) * 16) = t4;
     }
-    if (tile + 32 < k_end) OURO_ATTN_ISSUE_LOADS(tile + 32)
+    if (tile + 128 < k_end) OURO_ATTN_ISSUE_LOADS(tile + 128)
     wave_lds_fence();
 
-    // ---- S^T = K . Q^T ----
-    f32x16 sacc[QT];
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[qt][i] = 0.f;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kl + k_slot(col, 2 * s + half) * 16);
-#pragma unroll
-      for (int qt = 0; qt < QT; ++qt) sacc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][s], sacc[qt], 0, 0, 0);
-    }
-
-    // ---- mask + online softmax (log2 domain).  Register i of a lane is key 8*(i/4) + 4*half + i%4 ----
+    // ---- mask data for this tile.  Register i of a lane is key 8*(i/4) + 4*half + i%4 ----
     const bool need_mask = tile + 32 > L;          // tile touches block keys or runs past n (wave-uniform)
     int pidk[16];
     if (need_mask) {
@@ -200,19 +210,30 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
         pidk[i] = (kb >= 0 && kb < T) ? a.meta[static_cast<size_t>(b) * T + kb].phrase_id : 0;
       }
     }
+
     bf16x8 pf[QT][2];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
+      // ---- S^T = K . Q^T ----
+      f32x16 sacc;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kl + k_slot(col, 2 * s + half) * 16);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][s], sacc, 0, 0, 0);
+      }
+      // ---- mask + online softmax (log2 domain) ----
       float tmax = -INFINITY;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        float s = sacc[qt][i] * a.scale_log2;
+        float s = sacc[i] * a.scale_log2;
         if (need_mask) {
           const int kb = tile + 8 * (i >> 2) + 4 * half + (i & 3) - L;
           const bool vis = kb < 0 || (kb < T && (pidk[i] == 0 ? kb <= boffq[qt] : (pidk[i] == pidq[qt] && kb <= tq[qt])));
           s = vis ? s : -INFINITY;
         }
-        sacc[qt][i] = s;
+        sacc[i] = s;
         tmax = fmaxf(tmax, s);
       }
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
@@ -224,8 +245,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
       f32x8 p0, p1;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        p0[i] = exp2f(sacc[qt][i] - m_safe);
-        p1[i] = exp2f(sacc[qt][8 + i] - m_safe);
+        p0[i] = exp2f(sacc[i] - m_safe);
+        p1[i] = exp2f(sacc[8 + i] - m_safe);
         psum += p0[i] + p1[i];
       }
       l_run[qt] = l_run[qt] * alpha + psum;         // per-half partial sum; halves are added at the end
@@ -250,84 +271,163 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     }
     wave_lds_fence();                               // reads of this tile precede the next tile's LDS writes
   }
-
 #undef OURO_ATTN_ISSUE_LOADS
 
-  // ---- epilogue ----
-  const int group = bg * a.nrb + rb;
+  // ---- merge the 4 wave states pairwise through LDS: (2,3) -> (0,1), then 1 -> 0 ----
+  f32x4* slot_o = reinterpret_cast<f32x4*>(lds);
+  float* slot_ml = reinterpret_cast<float*>(lds + 2 * C::kStateBytes);
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    const float l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32);
-    const int r = rowq[qt];
-    if (r >= M) continue;
-    const int t = tq[qt], hh = r - t * G;
-    if (a.nch == 1) {
-      const float inv = 1.0f / l_tot;
-      __bf16* op = a.out + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
+  for (int sft = 2; sft >= 1; sft >>= 1) {
+    __syncthreads();
+    if (wave >= sft && wave < 2 * sft) {
+      const int slot = wave - sft;
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
+      for (int qt = 0; qt < QT; ++qt) {
 #pragma unroll
-        for (int ig = 0; ig < 4; ++ig) {
-          f32x4 v4 = {o[qt][dt][4 * ig + 0] * inv, o[qt][dt][4 * ig + 1] * inv, o[qt][dt][4 * ig + 2] * inv,
-                      o[qt][dt][4 * ig + 3] * inv};
-          *reinterpret_cast<bf16x4*>(op + 32 * dt + 8 * ig + 4 * half) = __builtin_convertvector(v4, bf16x4);
-        }
-      if (a.lse && half == 0)
-        a.lse[(static_cast<size_t>(b) * Hq + g * G + hh) * T + t] = (m_run[qt] + log2f(l_tot)) * 0.6931471805599453f;
-    } else {
-      const size_t prow = (static_cast<size_t>(group) * a.nch + chunk) * (32 * QT) + qt * 32 + col;
-      float* po = a.part_o + prow * kD;
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int ig = 0; ig < 4; ++ig) {
+            f32x4 v4 = {o[qt][dt][4 * ig + 0], o[qt][dt][4 * ig + 1], o[qt][dt][4 * ig + 2], o[qt][dt][4 * ig + 3]};
+            slot_o[(slot * QT * 16 + (qt * 4 + dt) * 4 + ig) * 64 + lane] = v4;
+          }
+        slot_ml[((slot * QT + qt) * 64 + lane) * 2 + 0] = m_run[qt];
+        slot_ml[((slot * QT + qt) * 64 + lane) * 2 + 1] = l_run[qt];
+      }
+    }
+    __syncthreads();
+    if (wave < sft) {
+      const int slot = wave;
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
+        const float m_b = slot_ml[((slot * QT + qt) * 64 + lane) * 2 + 0];
+        const float l_b = slot_ml[((slot * QT + qt) * 64 + lane) * 2 + 1];
+        const float m_new = fmaxf(m_run[qt], m_b);
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+        const float fa = exp2f(m_run[qt] - m_safe), fb = exp2f(m_b - m_safe);
+        m_run[qt] = m_new;
+        l_run[qt] = l_run[qt] * fa + l_b * fb;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int ig = 0; ig < 4; ++ig) {
+            const f32x4 ob = slot_o[(slot * QT * 16 + (qt * 4 + dt) * 4 + ig) * 64 + lane];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[qt][dt][4 * ig + e] = o[qt][dt][4 * ig + e] * fa + ob[e] * fb;
+          }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- wave 0 stages the workgroup's state row-major: stage_o[row][132], stage_ml[row][2] ----
+  float* stage_o = reinterpret_cast<float*>(lds);
+  float* stage_ml = stage_o + C::kRows * kStageRow;
+  if (wave == 0) {
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      const float l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32);
+      const int row = qt * 32 + col;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int ig = 0; ig < 4; ++ig) {
           f32x4 v4 = {o[qt][dt][4 * ig + 0], o[qt][dt][4 * ig + 1], o[qt][dt][4 * ig + 2], o[qt][dt][4 * ig + 3]};
-          *reinterpret_cast<f32x4*>(po + 32 * dt + 8 * ig + 4 * half) = v4;
+          *reinterpret_cast<f32x4*>(stage_o + row * kStageRow + 32 * dt + 8 * ig + 4 * half) = v4;
         }
       if (half == 0) {
-        f32x2 ml = {m_run[qt], l_tot};
-        *reinterpret_cast<f32x2*>(a.part_ml + prow * 2) = ml;
+        stage_ml[row * 2 + 0] = m_run[qt];
+        stage_ml[row * 2 + 1] = l_tot;
       }
     }
   }
+  __syncthreads();
+
+  const int group = bg * a.nrb + rb;
+  const int row0 = rb * C::kRows;
+  if (nchb == 1) {
+    // ---- the workgroup saw every key of the sequence: normalise and write bf16, 16 B per thread ----
+    for (int p = tid; p < C::kRows * 16; p += 256) {
+      const int row = p >> 4, c = p & 15;
+      const int r = row0 + row;
+      if (r >= M) continue;
+      const float inv = 1.0f / stage_ml[row * 2 + 1];
+      const f32x4 x0 = *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 8 * c);
+      const f32x4 x1 = *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 8 * c + 4);
+      f32x8 v8 = {x0[0] * inv, x0[1] * inv, x0[2] * inv, x0[3] * inv, x1[0] * inv, x1[1] * inv, x1[2] * inv, x1[3] * inv};
+      const int t = r / G, hh = r - t * G;
+      __bf16* op = a.out + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
+      *reinterpret_cast<bf16x8*>(op + 8 * c) = __builtin_convertvector(v8, bf16x8);
+      if (a.lse && c == 0)
+        a.lse[(static_cast<size_t>(b) * Hq + g * G + hh) * T + t] =
+            (stage_ml[row * 2] + log2f(stage_ml[row * 2 + 1])) * kLn2;
+    }
+    return;
+  }
+
+  // ---- several chunks: leave a partial, the last workgroup of the group merges ----
+  {
+    const size_t pbase = (static_cast<size_t>(group) * a.nch + chunk) * C::kRows;
+    for (int p = tid; p < C::kRows * 32; p += 256) {
+      const int row = p >> 5, c = p & 31;
+      *reinterpret_cast<f32x4*>(a.part_o + (pbase + row) * kD + 4 * c) =
+          *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 4 * c);
+    }
+    for (int p = tid; p < C::kRows * 2; p += 256) a.part_ml[pbase * 2 + p] = stage_ml[p];
+  }
+  __threadfence();                                  // partial visible device-wide before the ticket is taken
+  __syncthreads();
+  if (tid == 0) s_ticket = __hip_atomic_fetch_add(a.counters + group, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (s_ticket != static_cast<unsigned>(nchb - 1)) return;
+  __threadfence();                                  // acquire: the other workgroups' partials
+  {
+    const size_t gbase = static_cast<size_t>(group) * a.nch * C::kRows;
+    for (int p = tid; p < C::kRows * 16; p += 256) {
+      const int row = p >> 4, c = p & 15;
+      const int r = row0 + row;
+      if (r >= M) continue;
+      float m_star = -INFINITY;
+      for (int ch = 0; ch < nchb; ++ch)
+        m_star = fmaxf(m_star, a.part_ml[(gbase + static_cast<size_t>(ch) * C::kRows + row) * 2]);
+      float lsum = 0.f;
+      f32x8 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int ch = 0; ch < nchb; ++ch) {
+        const size_t prow = gbase + static_cast<size_t>(ch) * C::kRows + row;
+        const float m_c = a.part_ml[prow * 2];
+        const float l_c = a.part_ml[prow * 2 + 1];
+        const float wgt = exp2f(m_c - m_star);
+        lsum += wgt * l_c;
+        const f32x4 x0 = *reinterpret_cast<const f32x4*>(a.part_o + prow * kD + 8 * c);
+        const f32x4 x1 = *reinterpret_cast<const f32x4*>(a.part_o + prow * kD + 8 * c + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[e] += wgt * x0[e];
+          acc[4 + e] += wgt * x1[e];
+        }
+      }
+      const float inv = 1.0f / lsum;
+      const int t = r / G, hh = r - t * G;
+      __bf16* op = a.out + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
+      *reinterpret_cast<bf16x8*>(op + 8 * c) = __builtin_convertvector(acc * inv, bf16x8);
+      if (a.lse && c == 0)
+        a.lse[(static_cast<size_t>(b) * Hq + g * G + hh) * T + t] = (m_star + log2f(lsum)) * kLn2;
+    }
+  }
+  if (tid == 0) __hip_atomic_store(a.counters + group, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
 }
 
-// Merge the chunk partials of one query row: out = sum_c 2^(m_c - m*) O_c / sum_c 2^(m_c - m*) l_c,
-// chunks visited in ascending order.  One wave per row, lane <-> two head-dim elements.
-__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a, int rows_wave) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const long w = static_cast<long>(blockIdx.x) * 4 + wave;
-  const long n_rows = static_cast<long>(a.n_items / a.nch) * rows_wave;   // groups * rows_wave
-  if (w >= n_rows) return;
-  const int row = static_cast<int>(w % rows_wave);
-  const int group = static_cast<int>(w / rows_wave);
-  const int rb = group % a.nrb, bg = group / a.nrb;
-  const int b = bg / a.Hkv, g = bg - b * a.Hkv;
-  const int r = rb * rows_wave + row;
-  if (r >= a.M) return;
-  const int n = static_cast<int>(a.cu[b + 1] - a.cu[b]) + a.T;
-  const int nchb = (n + a.chunk - 1) / a.chunk;
-  const size_t base = static_cast<size_t>(group) * a.nch * rows_wave + row;
-  float m_star = -INFINITY;
-  for (int c = 0; c < nchb; ++c) m_star = fmaxf(m_star, a.part_ml[(base + static_cast<size_t>(c) * rows_wave) * 2]);
-  float lsum = 0.f;
-  f32x2 acc = {0.f, 0.f};
-  for (int c = 0; c < nchb; ++c) {
-    const size_t prow = base + static_cast<size_t>(c) * rows_wave;
-    const f32x2 ml = *reinterpret_cast<const f32x2*>(a.part_ml + prow * 2);
-    const float wgt = exp2f(ml[0] - m_star);
-    lsum += wgt * ml[1];
-    const f32x2 po = *reinterpret_cast<const f32x2*>(a.part_o + prow * kD + 2 * lane);
-    acc[0] += wgt * po[0];
-    acc[1] += wgt * po[1];
+template <int QT>
+int launch_qt(const AttnArgs& a, unsigned grid, hipStream_t stream) {
+  using C = AttnCfg<QT>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<QT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+    if (e != hipSuccess) return hip_failed(e);
+    attr_set = true;
   }
-  const int t = r / a.G, hh = r - t * a.G;
-  const float inv = 1.0f / lsum;
-  f32x2 res = {acc[0] * inv, acc[1] * inv};
-  __bf16* op = a.out + ((static_cast<size_t>(b) * a.T + t) * a.Hq + g * a.G + hh) * kD;
-  *reinterpret_cast<bf16x2*>(op + 2 * lane) = __builtin_convertvector(res, bf16x2);
-  if (a.lse && lane == 0)
-    a.lse[(static_cast<size_t>(b) * a.Hq + g * a.G + hh) * a.T + t] = (m_star + log2f(lsum)) * 0.6931471805599453f;
+  hipLaunchKernelGGL(attn_bf16_kernel<QT>, dim3(grid), dim3(256), C::kLdsBytes, stream, a);
+  return check_launch();
 }
 
 }  // namespace
@@ -343,8 +443,10 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
   a.meta = d.meta;
   a.out = static_cast<__bf16*>(d.out);
   a.lse = d.lse;
-  a.part_o = static_cast<float*>(d.workspace);
-  a.part_ml = reinterpret_cast<float*>(static_cast<unsigned char*>(d.workspace) + plan.part_o_bytes);
+  unsigned char* ws = static_cast<unsigned char*>(d.workspace);
+  a.counters = reinterpret_cast<unsigned*>(ws);
+  a.part_ml = reinterpret_cast<float*>(ws + plan.counter_bytes);
+  a.part_o = reinterpret_cast<float*>(ws + plan.counter_bytes + plan.part_ml_bytes);
   a.T = d.T;
   a.Hq = d.Hq;
   a.Hkv = d.Hkv;
@@ -353,17 +455,10 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
   a.nrb = plan.nrb;
   a.nch = plan.nch;
   a.chunk = plan.chunk;
-  a.n_items = static_cast<long>(d.B) * d.Hkv * plan.nrb * plan.nch;
+  a.n_x = d.B * d.Hkv * plan.nch;
   a.scale_log2 = scale * 1.4426950408889634f;
-  const unsigned grid = static_cast<unsigned>((a.n_items + 3) / 4);
-  if (plan.qt == 2) hipLaunchKernelGGL(attn_bf16_kernel<2>, dim3(grid), dim3(256), 0, stream, a);
-  else hipLaunchKernelGGL(attn_bf16_kernel<1>, dim3(grid), dim3(256), 0, stream, a);
-  int st = check_launch();
-  if (st != OURO_OK || plan.nch == 1) return st;
-  const long n_rows = static_cast<long>(d.B) * d.Hkv * plan.nrb * plan.rows_wave;
-  hipLaunchKernelGGL(attn_combine_kernel, dim3(static_cast<unsigned>((n_rows + 3) / 4)), dim3(256), 0, stream, a,
-                     plan.rows_wave);
-  return check_launch();
+  const unsigned grid = static_cast<unsigned>((a.n_x + 7) / 8) * 8u * plan.nrb;
+  return plan.qt == 2 ? launch_qt<2>(a, grid, stream) : launch_qt<1>(a, grid, stream);
 }
 
 }  // namespace ouro

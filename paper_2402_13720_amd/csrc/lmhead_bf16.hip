@@ -15,7 +15,10 @@
 //     the wave's next k-tile are issued before the math of the current one;
 //   * after the loop the 4 partial accumulator sets are summed through LDS (fixed order),
 //     and the arg-max epilogue reduces lane -> wave -> workgroup; one (value, index) pair
-//     per (slab, row) goes to the workspace, the logits never leave the chip.
+//     per (slab, row) goes to the workspace, the logits never leave the chip;
+//   * the workgroup that finishes last (ticket counter in the workspace) reduces the pairs
+//     over the slabs and writes the result: one launch, no float atomics, order-independent
+//     because (larger value, then smaller index) is a total order.
 #include <math.h>
 
 #include "ouro_internal.hpp"
@@ -32,7 +35,10 @@ typedef unsigned __attribute__((ext_vector_type(4))) u32x4;   // 16-byte staging
 struct LmArgs {
   const __bf16* hidden;
   const __bf16* w;
-  float2* part;     // [nslab][R]
+  float2* part;        // [nslab][R]
+  unsigned* counters;  // [gridDim.y], zero on entry, zero on exit
+  int32_t* argmax_out;
+  float* max_out;
   int R, Hd, V;
 };
 
@@ -187,6 +193,42 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
     }
     a.part[static_cast<size_t>(blockIdx.x) * R + r0 + rl] = make_float2(bv, __int_as_float(bi));
   }
+
+  // ---- the workgroup that finishes last for this row slice reduces over the slabs ----
+  __shared__ unsigned s_ticket;
+  __threadfence();                                  // this slab's pairs visible device-wide before the ticket
+  __syncthreads();
+  if (threadIdx.x == 0)
+    s_ticket = __hip_atomic_fetch_add(a.counters + blockIdx.y, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (s_ticket != gridDim.x - 1) return;
+  __threadfence();
+  constexpr int kSlices = 256 / C::kHRows;          // threads per row, each scanning every kSlices-th slab
+  const int rl = threadIdx.x % C::kHRows, slice = threadIdx.x / C::kHRows;
+  const int nslab = gridDim.x;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  if (r0 + rl < R) {
+    for (int s = slice; s < nslab; s += kSlices) {
+      const float2 p = a.part[static_cast<size_t>(s) * R + r0 + rl];
+      const int i = __float_as_int(p.y);
+      if (better(p.x, i, bv, bi)) { bv = p.x; bi = i; }
+    }
+  }
+  bestv[slice * C::kHRows + rl] = bv;               // kSlices <= MT for both variants: the area is large enough
+  besti[slice * C::kHRows + rl] = bi;
+  __syncthreads();
+  if (slice == 0 && r0 + rl < R) {
+#pragma unroll
+    for (int sl = 1; sl < kSlices; ++sl) {
+      const float v2 = bestv[sl * C::kHRows + rl];
+      const int i2 = besti[sl * C::kHRows + rl];
+      if (better(v2, i2, bv, bi)) { bv = v2; bi = i2; }
+    }
+    a.argmax_out[r0 + rl] = bi;
+    if (a.max_out) a.max_out[r0 + rl] = bv;
+  }
+  if (threadIdx.x == 0) __hip_atomic_store(a.counters + blockIdx.y, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int MT, int NT>
@@ -209,7 +251,10 @@ int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_
   LmArgs a{};
   a.hidden = static_cast<const __bf16*>(d.hidden);
   a.w = static_cast<const __bf16*>(d.w);
-  a.part = static_cast<float2*>(d.workspace);
+  a.counters = static_cast<unsigned*>(d.workspace);
+  a.part = reinterpret_cast<float2*>(static_cast<unsigned char*>(d.workspace) + plan.counter_bytes);
+  a.argmax_out = d.argmax_out;
+  a.max_out = d.max_out;
   a.R = d.R;
   a.Hd = d.Hd;
   a.V = d.V;

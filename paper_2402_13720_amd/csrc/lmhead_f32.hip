@@ -9,6 +9,8 @@
 // reduces over slabs.
 #include <math.h>
 
+#include <algorithm>
+
 #include "ouro_internal.hpp"
 
 namespace ouro {
@@ -60,20 +62,34 @@ __global__ __launch_bounds__(256) void lmhead_f32_kernel(ouro_lmhead_desc d, int
   }
 }
 
-// part [nslab][R] -> argmax_out[R], max_out[R]
+// part [nslab][R] -> argmax_out[R], max_out[R].  One wave per row, lanes stride over slabs.
 __global__ __launch_bounds__(256) void lmhead_final_kernel(const float2* part, int nslab, int R, int32_t* arg_out,
                                                            float* max_out) {
-  const int r = blockIdx.x * 256 + threadIdx.x;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
   if (r >= R) return;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  for (int s = 0; s < nslab; ++s) {
+  for (int s = lane; s < nslab; s += 64) {
     const float2 p = part[static_cast<size_t>(s) * R + r];
     const int i = __float_as_int(p.y);
     if (better(p.x, i, bv, bi)) { bv = p.x; bi = i; }
   }
-  arg_out[r] = bi;
-  if (max_out) max_out[r] = bv;
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float ov = __shfl_xor(bv, off);
+    const int oi = __shfl_xor(bi, off);
+    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+  }
+  if (lane == 0) {
+    arg_out[r] = bi;
+    if (max_out) max_out[r] = bv;
+  }
+}
+
+// Zero fill with 16-byte stores (a kernel rather than a memset node, so that callers may capture it).
+__global__ __launch_bounds__(256) void zero_fill_kernel(uint4* p, size_t n16) {
+  for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += static_cast<size_t>(gridDim.x) * 256)
+    p[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 }  // namespace
@@ -82,13 +98,21 @@ int launch_lmhead_f32(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t
   dim3 grid(plan.nslab, plan.nrtile);
   const size_t smem = static_cast<size_t>(plan.rtile) * 4 * 2 * sizeof(float);
   hipLaunchKernelGGL(lmhead_f32_kernel, grid, dim3(256), smem, stream, d, plan.slab, plan.rtile,
-                     static_cast<float2*>(d.workspace));
+                     reinterpret_cast<float2*>(static_cast<unsigned char*>(d.workspace) + plan.counter_bytes));
   return check_launch();
 }
 
 int launch_lmhead_final(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream) {
-  hipLaunchKernelGGL(lmhead_final_kernel, dim3((d.R + 255) / 256), dim3(256), 0, stream,
-                     static_cast<const float2*>(d.workspace), plan.nslab, d.R, d.argmax_out, d.max_out);
+  hipLaunchKernelGGL(lmhead_final_kernel, dim3((d.R + 3) / 4), dim3(256), 0, stream,
+                     reinterpret_cast<const float2*>(static_cast<unsigned char*>(d.workspace) + plan.counter_bytes),
+                     plan.nslab, d.R, d.argmax_out, d.max_out);
+  return check_launch();
+}
+
+int launch_zero_fill(void* p, size_t bytes, hipStream_t stream) {
+  const size_t n16 = bytes / 16;
+  const unsigned grid = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 256));
+  hipLaunchKernelGGL(zero_fill_kernel, dim3(grid), dim3(256), 0, stream, static_cast<uint4*>(p), n16);
   return check_launch();
 }
 

@@ -2,6 +2,7 @@
 // Every check here runs before the first HIP call so that it works without a GPU.
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 
 #include "ouro_internal.hpp"
 
@@ -14,30 +15,40 @@ int hip_failed(hipError_t e) {
   return OURO_E_HIP;
 }
 
-// Keys per wave work item.  A wave streams `chunk` keys of one (sequence, KV head) for its
-// query rows and leaves one fp32 partial; small chunks fill the 1024 SIMDs of the chip,
-// large chunks keep the partial traffic (rows * D * 4 bytes per item) small against the
-// K/V bytes of the chunk (chunk * D * 4 bytes).  Aim at about four items per SIMD, but
-// never less than 4 key tiles per item unless the whole sequence is shorter.
+static long env_long(const char* name, long dflt) {
+  const char* v = std::getenv(name);
+  return v && *v ? std::atol(v) : dflt;
+}
+
+// Launch plan of the bf16 attention.  A workgroup streams `chunk` keys of one (sequence,
+// KV head) for its query rows and, when the sequence spans several chunks, leaves one fp32
+// partial.  Small chunks fill the 256 compute units; large chunks keep the partial traffic
+// (rows * 512 bytes per workgroup) small against the K/V bytes of a chunk (chunk * 512 bytes).
+// The default aims at about three workgroups per compute unit.  OURO_ATTN_CHUNK (keys) and
+// OURO_ATTN_QT (1 or 2) override the heuristic for tuning runs.
 AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
   AttnPlan p{};
   const int G = d.Hq / d.Hkv;
   const int M = d.T * G;
-  p.qt = M > 32 ? 2 : 1;
-  p.rows_wave = 32 * p.qt;
-  p.nrb = (M + p.rows_wave - 1) / p.rows_wave;
+  const long qt_env = env_long("OURO_ATTN_QT", 0);
+  p.qt = qt_env == 1 || qt_env == 2 ? static_cast<int>(qt_env) : (M > 64 ? 2 : 1);
+  p.rows_wg = 32 * p.qt;
+  p.nrb = (M + p.rows_wg - 1) / p.rows_wg;
   const long maxn = static_cast<long>(d.max_seqlen) + d.T;
   const long tiles = (maxn + 31) / 32;
   const long groups = std::max<long>(1, static_cast<long>(d.B) * d.Hkv * p.nrb);
-  long want = (4096 + groups - 1) / groups;          // chunk slots per sequence to reach ~4 items per SIMD
+  long want = (768 + groups - 1) / groups;           // chunk slots per sequence
   want = std::max<long>(1, std::min(want, (tiles + 3) / 4));
-  long tiles_per_chunk = (tiles + want - 1) / want;
+  long tiles_per_chunk = ((tiles + want - 1) / want + 3) / 4 * 4;
+  const long chunk_env = env_long("OURO_ATTN_CHUNK", 0);
+  if (chunk_env >= 128) tiles_per_chunk = chunk_env / 128 * 4;
   p.chunk = static_cast<int>(tiles_per_chunk * 32);
   p.nch = static_cast<int>((maxn + p.chunk - 1) / p.chunk);
   if (p.nch > 1) {
-    const size_t items = static_cast<size_t>(groups) * p.nch;
-    p.part_o_bytes = round_up(items * p.rows_wave * d.D * sizeof(float), 256);
-    p.part_ml_bytes = round_up(items * p.rows_wave * 2 * sizeof(float), 256);
+    const size_t slots = static_cast<size_t>(groups) * p.nch;
+    p.counter_bytes = round_up(static_cast<size_t>(groups) * sizeof(unsigned), 256);
+    p.part_ml_bytes = round_up(slots * p.rows_wg * 2 * sizeof(float), 256);
+    p.part_o_bytes = round_up(slots * p.rows_wg * d.D * sizeof(float), 256);
   }
   return p;
 }
@@ -59,6 +70,7 @@ LmPlan plan_lmhead(const ouro_lmhead_desc& d) {
   }
   p.nslab = (d.V + p.slab - 1) / p.slab;
   p.nrtile = (d.R + p.rtile - 1) / p.rtile;
+  p.counter_bytes = round_up(static_cast<size_t>(p.nrtile) * sizeof(unsigned), 256);
   p.part_bytes = round_up(static_cast<size_t>(p.nslab) * std::max(d.R, 1) * 8, 256);
   return p;
 }
@@ -71,6 +83,8 @@ static int validate_attn(const ouro_attn_desc* d, bool need_pointers) {
   if (d->max_seqlen < 0) return OURO_E_BAD_SHAPE;
   if (d->dtype == OURO_BF16 ? d->D != 128 : (d->D != 64 && d->D != 128)) return OURO_E_BAD_SHAPE;
   if (static_cast<long>(d->T) * (d->Hq / d->Hkv) > 32768) return OURO_E_BAD_SHAPE;
+  if (static_cast<long>(d->B) * d->Hkv * (d->T * (d->Hq / d->Hkv) / 32 + 1) * 4 > static_cast<long>(kMaxCounterBytes))
+    return OURO_E_BAD_SHAPE;
   if (!need_pointers || d->B == 0) return OURO_OK;
   if (!d->q || !d->cu_seqlens || !d->k_blk || !d->v_blk || !d->meta || !d->out) return OURO_E_NULLPTR;
   if (d->max_seqlen > 0 && (!d->k_cache || !d->v_cache)) return OURO_E_NULLPTR;
@@ -112,8 +126,7 @@ extern "C" {
 
 size_t ouro_verify_attn_workspace(const ouro_attn_desc* desc) {
   if (validate_attn(desc, false) != OURO_OK || desc->dtype != OURO_BF16 || desc->B == 0) return 0;
-  AttnPlan p = plan_attn_bf16(*desc);
-  return p.part_o_bytes + p.part_ml_bytes;
+  return plan_attn_bf16(*desc).total();
 }
 
 int ouro_verify_attn(const ouro_attn_desc* desc, void* hip_stream) {
@@ -124,7 +137,7 @@ int ouro_verify_attn(const ouro_attn_desc* desc, void* hip_stream) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (desc->dtype == OURO_F32) return launch_attn_f32(*desc, scale, stream);
   AttnPlan p = plan_attn_bf16(*desc);
-  const size_t need = p.part_o_bytes + p.part_ml_bytes;
+  const size_t need = p.total();
   if (need > 0) {
     if (!desc->workspace) return OURO_E_NULLPTR;
     if (desc->workspace_bytes < need) return OURO_E_WORKSPACE_TOO_SMALL;
@@ -134,7 +147,7 @@ int ouro_verify_attn(const ouro_attn_desc* desc, void* hip_stream) {
 
 size_t ouro_lmhead_argmax_workspace(const ouro_lmhead_desc* desc) {
   if (validate_lmhead(desc, false) != OURO_OK || desc->R == 0) return 0;
-  return plan_lmhead(*desc).part_bytes;
+  return plan_lmhead(*desc).total();
 }
 
 int ouro_lmhead_argmax(const ouro_lmhead_desc* desc, void* hip_stream) {
@@ -143,9 +156,10 @@ int ouro_lmhead_argmax(const ouro_lmhead_desc* desc, void* hip_stream) {
   if (desc->R == 0) return OURO_OK;
   LmPlan p = plan_lmhead(*desc);
   if (!desc->workspace) return OURO_E_NULLPTR;
-  if (desc->workspace_bytes < p.part_bytes) return OURO_E_WORKSPACE_TOO_SMALL;
+  if (desc->workspace_bytes < p.total()) return OURO_E_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  st = desc->dtype == OURO_F32 ? launch_lmhead_f32(*desc, p, stream) : launch_lmhead_bf16(*desc, p, stream);
+  if (desc->dtype == OURO_BF16) return launch_lmhead_bf16(*desc, p, stream);
+  st = launch_lmhead_f32(*desc, p, stream);
   if (st != OURO_OK) return st;
   return launch_lmhead_final(*desc, p, stream);
 }
@@ -155,6 +169,14 @@ int ouro_accept(const ouro_accept_desc* desc, void* hip_stream) {
   if (st != OURO_OK) return st;
   if (desc->B == 0) return OURO_OK;
   return launch_accept(*desc, static_cast<hipStream_t>(hip_stream));
+}
+
+int ouro_workspace_init(void* workspace, size_t bytes, void* hip_stream) {
+  if (!workspace) return bytes == 0 ? OURO_OK : OURO_E_NULLPTR;
+  if (!aligned16(workspace)) return OURO_E_MISALIGNED;
+  const size_t n = std::min(bytes, kMaxCounterBytes) / 16 * 16;
+  if (n == 0) return OURO_OK;
+  return launch_zero_fill(workspace, n, static_cast<hipStream_t>(hip_stream));
 }
 
 int ouro_validate_meta_host(const ouro_tok_meta* m, int32_t T, int32_t gamma, int32_t K, int32_t beta) {

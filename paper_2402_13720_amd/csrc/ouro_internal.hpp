@@ -23,12 +23,14 @@ inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Launch plan of the bf16 split-KV kernel, derived on the host from shapes only.
 struct AttnPlan {
   int qt;          // 32-row query tiles per wave (1 or 2)
-  int rows_wave;   // 32 * qt
-  int nrb;         // row blocks per (sequence, KV head): ceil(T * G / rows_wave)
-  int chunk;       // keys per wave work item (multiple of 32)
+  int rows_wg;     // query rows per workgroup: 32 * qt
+  int nrb;         // row blocks per (sequence, KV head): ceil(T * G / rows_wg)
+  int chunk;       // keys per workgroup (multiple of 128: the 4 waves take 32-key tiles round-robin)
   int nch;         // chunk slots per sequence: ceil((max_seqlen + T) / chunk)
-  size_t part_o_bytes;   // fp32 partial outputs
+  size_t counter_bytes;  // ticket counters, one per (sequence, KV head, row block); zero between calls
   size_t part_ml_bytes;  // fp32 (max, sum) pairs
+  size_t part_o_bytes;   // fp32 partial outputs
+  size_t total() const { return counter_bytes + part_ml_bytes + part_o_bytes; }
 };
 AttnPlan plan_attn_bf16(const ouro_attn_desc& d);
 
@@ -42,8 +44,14 @@ struct LmPlan {
   int nslab;       // ceil(V / slab)
   int rtile;       // rows per grid.y slice
   int nrtile;
-  size_t part_bytes;   // [nslab][R] (float value, int32 index) pairs
+  size_t counter_bytes;  // ticket counters, one per grid.y slice; zero between calls
+  size_t part_bytes;     // [nslab][R] (float value, int32 index) pairs
+  size_t total() const { return counter_bytes + part_bytes; }
 };
+
+// Bytes at the start of every workspace that hold ticket counters at most.
+constexpr size_t kMaxCounterBytes = 1u << 20;
+int launch_zero_fill(void* p, size_t bytes, hipStream_t stream);
 LmPlan plan_lmhead(const ouro_lmhead_desc& d);
 int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
 int launch_lmhead_f32(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);

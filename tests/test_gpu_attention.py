@@ -116,3 +116,31 @@ def test_full_size_config5_sampled_heads():
     seqs = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]       # shortest, median, longest sequence
     heads = [(b, h) for b in seqs for h in (0, 13, 31)]
     _check(cfg, inp, heads)
+
+
+def test_workspace_is_reusable_across_shapes_and_calls():
+    """The ticket counters at the start of the workspace are left zero by every call."""
+    from paper_2402_13720_amd import binding as ob
+    from gpu_util import upload_attention
+    ws = ob.alloc_workspace(64 << 20, DEV)
+    for kw, seed in [(dict(B=2, Hq=4, Hkv=2, L=(700, 3000)), 1), (dict(B=1, Hq=8, Hkv=8, L=5000), 2),
+                     (dict(B=2, Hq=4, Hkv=2, L=(700, 3000)), 1)]:
+        cfg = W.scaled(W.CONFIGS[2], **kw)
+        inp = W.make_attention_inputs(cfg, seed)
+        t = upload_attention(cfg, inp)
+        assert ob.ouro_verify_attn_workspace(t["q"], t["k_blk"], t["max_seqlen"]) <= ws.numel()
+        ref = _oracle(inp)["out"]
+        for _ in range(2):
+            out = ob.ouro_verify_attn(t["q"], t["k_cache"], t["v_cache"], t["cu_seqlens"], t["k_blk"], t["v_blk"],
+                                      t["meta"], t["max_seqlen"], workspace=ws)
+            torch.cuda.synchronize()
+            assert np.abs(to_np64(out) - ref).max() <= 2e-2
+        assert int(ws[:256].view(torch.int32).abs().sum()) == 0
+
+
+def test_workspace_init_clears_dirty_counters():
+    from paper_2402_13720_amd import binding as ob
+    ws = torch.full((1 << 21,), 255, dtype=torch.uint8, device=DEV)
+    ob.ouro_workspace_init(ws)
+    torch.cuda.synchronize()
+    assert int(ws[: 1 << 20].sum()) == 0 and int(ws[1 << 20:].min()) == 255

@@ -97,3 +97,19 @@ def test_full_size_config5_sampled_rows():
     s = W.seed_for(5)
     rows = np.random.default_rng(0).choice(cfg.R, size=96, replace=False)
     _check(cfg, W.make_hidden(cfg, s), W.make_lmhead_weight(cfg, s), rows=np.sort(rows))
+
+
+def test_workspace_is_reusable_across_shapes_and_calls():
+    ws = ob.alloc_workspace(8 << 20, DEV)
+    for (R, Hd, V, seed) in [(64, 512, 3000, 1), (200, 256, 1500, 2), (64, 512, 3000, 1)]:
+        cfg = W.scaled(W.CONFIGS[2], B=1, Hq=Hd // 64, Hkv=Hd // 64, D=64, V=V)
+        hidden, w = W.make_hidden(cfg, seed, rows=R), W.make_lmhead_weight(cfg, seed)
+        ref = O.lmhead_argmax(hidden, w)
+        h_d = torch.from_numpy(hidden).to(DEV).to(torch.bfloat16)
+        w_d = torch.from_numpy(w).to(DEV).to(torch.bfloat16)
+        assert ob.ouro_lmhead_argmax_workspace(h_d, w_d) <= ws.numel()
+        for _ in range(2):
+            arg = ob.ouro_lmhead_argmax(h_d, w_d, workspace=ws).cpu().numpy()
+            bad = [r for r in range(R) if arg[r] != ref["argmax"][r] and ref["margin"][r] >= MARGIN]
+            assert not bad
+        assert int(ws[:256].view(torch.int32).abs().sum()) == 0
