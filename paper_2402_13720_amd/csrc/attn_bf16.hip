@@ -367,42 +367,53 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
   // ---- several chunks: leave a partial, the last workgroup of the group merges ----
   {
     const size_t pbase = (static_cast<size_t>(group) * a.nch + chunk) * C::kRows;
-    for (int p = tid; p < C::kRows * 32; p += 256) {
-      const int row = p >> 5, c = p & 31;
-      *reinterpret_cast<f32x4*>(a.part_o + (pbase + row) * kD + 4 * c) =
-          *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 4 * c);
+    for (int p = tid; p < C::kRows * 64; p += 256) {
+      const int row = p >> 6, c = p & 63;
+      const float* src = stage_o + row * kStageRow + 2 * c;
+      st_agent_f2(a.part_o + (pbase + row) * kD + 2 * c, src[0], src[1]);
     }
-    for (int p = tid; p < C::kRows * 2; p += 256) a.part_ml[pbase * 2 + p] = stage_ml[p];
+    for (int p = tid; p < C::kRows; p += 256) st_agent_f2(a.part_ml + (pbase + p) * 2, stage_ml[2 * p], stage_ml[2 * p + 1]);
   }
-  __threadfence();                                  // partial visible device-wide before the ticket is taken
+  partials_written();
   __syncthreads();
-  if (tid == 0) s_ticket = __hip_atomic_fetch_add(a.counters + group, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid == 0) s_ticket = take_ticket(a.counters + group);
   __syncthreads();
   if (s_ticket != static_cast<unsigned>(nchb - 1)) return;
-  __threadfence();                                  // acquire: the other workgroups' partials
   {
+    // Device-coherent loads have a long round trip: issue them in batches of 4 chunks (20 loads in
+    // flight per thread) and fold each batch into a running (max, sum, O) in ascending chunk order.
     const size_t gbase = static_cast<size_t>(group) * a.nch * C::kRows;
     for (int p = tid; p < C::kRows * 16; p += 256) {
       const int row = p >> 4, c = p & 15;
       const int r = row0 + row;
       if (r >= M) continue;
-      float m_star = -INFINITY;
-      for (int ch = 0; ch < nchb; ++ch)
-        m_star = fmaxf(m_star, a.part_ml[(gbase + static_cast<size_t>(ch) * C::kRows + row) * 2]);
-      float lsum = 0.f;
+      float m_star = -INFINITY, lsum = 0.f;
       f32x8 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      for (int ch = 0; ch < nchb; ++ch) {
-        const size_t prow = gbase + static_cast<size_t>(ch) * C::kRows + row;
-        const float m_c = a.part_ml[prow * 2];
-        const float l_c = a.part_ml[prow * 2 + 1];
-        const float wgt = exp2f(m_c - m_star);
-        lsum += wgt * l_c;
-        const f32x4 x0 = *reinterpret_cast<const f32x4*>(a.part_o + prow * kD + 8 * c);
-        const f32x4 x1 = *reinterpret_cast<const f32x4*>(a.part_o + prow * kD + 8 * c + 4);
+      for (int ch0 = 0; ch0 < nchb; ch0 += 4) {
+        float m_c[4], l_c[4];
+        f32x8 x[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          acc[e] += wgt * x0[e];
-          acc[4 + e] += wgt * x1[e];
+        for (int u = 0; u < 4; ++u) {
+          const int ch = min(ch0 + u, nchb - 1);          // clamped duplicates are skipped below
+          const size_t prow = gbase + static_cast<size_t>(ch) * C::kRows + row;
+          ld_agent_f2(a.part_ml + prow * 2, m_c[u], l_c[u]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float x0, x1;
+            ld_agent_f2(a.part_o + prow * kD + 8 * c + 2 * e, x0, x1);
+            x[u][2 * e] = x0;
+            x[u][2 * e + 1] = x1;
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (ch0 + u >= nchb) continue;
+          const float m_new = fmaxf(m_star, m_c[u]);
+          const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+          const float fa = exp2f(m_star - m_safe), fb = exp2f(m_c[u] - m_safe);
+          m_star = m_new;
+          lsum = lsum * fa + l_c[u] * fb;
+          acc = acc * fa + x[u] * fb;
         }
       }
       const float inv = 1.0f / lsum;
@@ -413,7 +424,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
         a.lse[(static_cast<size_t>(b) * Hq + g * G + hh) * T + t] = (m_star + log2f(lsum)) * kLn2;
     }
   }
-  if (tid == 0) __hip_atomic_store(a.counters + group, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+  if (tid == 0) reset_ticket(a.counters + group);   // ready for the next call
 }
 
 template <int QT>

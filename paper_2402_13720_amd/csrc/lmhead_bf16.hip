@@ -191,28 +191,35 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
       const int i2 = besti[mt * C::kHRows + rl];
       if (better(v2, i2, bv, bi)) { bv = v2; bi = i2; }
     }
-    a.part[static_cast<size_t>(blockIdx.x) * R + r0 + rl] = make_float2(bv, __int_as_float(bi));
+    st_agent_f2(reinterpret_cast<float*>(a.part + static_cast<size_t>(blockIdx.x) * R + r0 + rl), bv, __int_as_float(bi));
   }
 
   // ---- the workgroup that finishes last for this row slice reduces over the slabs ----
   __shared__ unsigned s_ticket;
-  __threadfence();                                  // this slab's pairs visible device-wide before the ticket
+  partials_written();
   __syncthreads();
-  if (threadIdx.x == 0)
-    s_ticket = __hip_atomic_fetch_add(a.counters + blockIdx.y, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+  if (threadIdx.x == 0) s_ticket = take_ticket(a.counters + blockIdx.y);
   __syncthreads();
   if (s_ticket != gridDim.x - 1) return;
-  __threadfence();
   constexpr int kSlices = 256 / C::kHRows;          // threads per row, each scanning every kSlices-th slab
   const int rl = threadIdx.x % C::kHRows, slice = threadIdx.x / C::kHRows;
   const int nslab = gridDim.x;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
   if (r0 + rl < R) {
-    for (int s = slice; s < nslab; s += kSlices) {
-      const float2 p = a.part[static_cast<size_t>(s) * R + r0 + rl];
-      const int i = __float_as_int(p.y);
-      if (better(p.x, i, bv, bi)) { bv = p.x; bi = i; }
+    // device-coherent loads have a long round trip: keep 16 of them in flight per thread
+    for (int s0 = slice; s0 < nslab; s0 += 16 * kSlices) {
+      float pv[16], pi[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int s = min(s0 + u * kSlices, nslab - 1);     // clamped duplicates cannot change the result
+        ld_agent_f2(reinterpret_cast<const float*>(a.part + static_cast<size_t>(s) * R + r0 + rl), pv[u], pi[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int i = __float_as_int(pi[u]);
+        if (better(pv[u], i, bv, bi)) { bv = pv[u]; bi = i; }
+      }
     }
   }
   bestv[slice * C::kHRows + rl] = bv;               // kSlices <= MT for both variants: the area is large enough
@@ -228,7 +235,7 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
     a.argmax_out[r0 + rl] = bi;
     if (a.max_out) a.max_out[r0 + rl] = bv;
   }
-  if (threadIdx.x == 0) __hip_atomic_store(a.counters + blockIdx.y, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (threadIdx.x == 0) reset_ticket(a.counters + blockIdx.y);
 }
 
 template <int MT, int NT>

@@ -19,6 +19,38 @@ inline int check_launch() {
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// ---- cross-workgroup hand-over without cache flushes ------------------------------------
+// Partials that one workgroup writes and another (on any XCD) reads are moved with relaxed
+// agent-scope atomic 64-bit accesses: each is a single store/load that is coherent at device
+// level, so no L2 write-back or invalidate (which would evict the streamed operands of every
+// other workgroup) is needed.  Order: writers store, wait for completion (workgroup-scope
+// release = wait on the memory counter), barrier, one relaxed agent-scope ticket increment;
+// the workgroup that draws the last ticket then reads with the same kind of loads.
+#if defined(__HIPCC__)
+__device__ __forceinline__ void st_agent_u64(void* p, unsigned long long v) {
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_agent_u64(const void* p) {
+  return __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent_f2(float* p, float x, float y) {
+  st_agent_u64(p, (static_cast<unsigned long long>(__float_as_uint(y)) << 32) | __float_as_uint(x));
+}
+__device__ __forceinline__ void ld_agent_f2(const float* p, float& x, float& y) {
+  const unsigned long long v = ld_agent_u64(p);
+  x = __uint_as_float(static_cast<unsigned>(v));
+  y = __uint_as_float(static_cast<unsigned>(v >> 32));
+}
+// Called by every thread after its partial stores and before the workgroup barrier that precedes the ticket.
+__device__ __forceinline__ void partials_written() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+__device__ __forceinline__ unsigned take_ticket(unsigned* counter) {
+  return __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void reset_ticket(unsigned* counter) {
+  __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+#endif
+
 // ---- attention ------------------------------------------------------------------------
 // Launch plan of the bf16 split-KV kernel, derived on the host from shapes only.
 struct AttnPlan {
