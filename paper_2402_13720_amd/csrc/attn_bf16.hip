@@ -6,7 +6,7 @@
 // key tiles that overlap the block (the last T keys) pay for it, cache tiles are mask-free.
 //
 // Work decomposition.  Query rows of one (sequence, KV head) are the T*G rows of the G query
-// heads sharing that KV head (row = t*G + head_in_group), cut into row blocks of 32*QT rows.
+// heads sharing that KV head (row = t*G + head_in_group), cut into row blocks of 32 rows.
 // The key axis [cache | block] is cut into chunks.  One workgroup (4 waves) owns one
 // (sequence, KV head, chunk, row block); its waves take the chunk's 32-key tiles round-robin,
 // so together they stream one contiguous window of K and V.  Each wave runs a flash-style
@@ -15,7 +15,9 @@
 //   global --coalesced 16B loads--> registers --> wave-private LDS (K row-major swizzled,
 //   V transposed with in-register byte-permutes) --> MFMA operands
 //
-//   S^T[key, q]  = K . Q^T          v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q (registers)
+//   S^T[key, q]  = K . Q^T          v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q rows from a
+//                                    workgroup-shared LDS tile (keeps the kernel under 256 registers:
+//                                    two waves per SIMD, no spills between a prefetch and its use)
 //   online softmax in the exp2 domain, one query per lane column, keys along registers
 //   O^T[d, q]   += V^T . P^T        A = V^T from LDS, B = P^T = the S^T accumulator registers
 //                                    rounded to bf16 (no shuffle: the accumulator layout of
@@ -25,9 +27,10 @@
 // The next tile's global loads are issued before the current tile's math.  After the loop
 // the 4 wave states (O, running max, running sum) are merged pairwise through LDS, staged
 // row-major in LDS and written with coalesced 16-byte stores.  A sequence that spans several
-// chunks leaves one fp32 partial per workgroup; the workgroup that finishes last for a
-// (sequence, KV head, row block) -- found with a ticket counter in the workspace -- merges
-// the partials in ascending chunk order (deterministic) and writes bf16.  One launch.
+// chunks leaves one fp32 partial per workgroup, and a second small kernel merges the partials
+// of a row in ascending chunk order (deterministic) and writes bf16.  (A single-launch variant
+// in which the last workgroup of a row block merged the partials was measured slower: the
+// device-scope store/ticket/load round trips stall every workgroup for several microseconds.)
 //
 // Workgroup ids are mapped so that workgroups reading the same K/V window (different row
 // blocks) are congruent modulo 8, i.e. land on the same XCD and share its L2.
@@ -62,7 +65,6 @@ struct AttnArgs {
   const ouro_tok_meta* meta;
   __bf16* out;
   float* lse;
-  unsigned* counters;  // [groups], zero on entry, zero on exit
   float* part_ml;      // [group][chunk][rows_wg][2]
   float* part_o;       // [group][chunk][rows_wg][128]
   int n_x;             // B * Hkv * nch
@@ -73,14 +75,12 @@ struct AttnArgs {
 
 constexpr int cmax(int x, int y) { return x > y ? x : y; }
 
-template <int QT>
-struct AttnCfg {
-  static constexpr int kRows = 32 * QT;
-  static constexpr int kStateBytes = QT * 16 * 64 * 16;                 // O accumulators of one wave, lane-major
-  static constexpr int kMergeBytes = 2 * kStateBytes + 2 * QT * 64 * 8;  // two slots + their (max, sum) pairs
-  static constexpr int kStageBytes = kRows * kStageRow * 4 + kRows * 8;
-  static constexpr int kLdsBytes = cmax(cmax(4 * kWaveLds, kMergeBytes), kStageBytes);
-};
+constexpr int kRows = 32;                                  // query rows per workgroup
+constexpr int kQBytes = kRows * 256;                       // Q tile shared by the 4 waves, same swizzle as the K tile
+constexpr int kStateBytes = 16 * 64 * 16;                  // O accumulators of one wave, lane-major
+constexpr int kMergeBytes = 2 * kStateBytes + 2 * 64 * 8;  // two slots + their (max, sum) pairs
+constexpr int kStageBytes = kRows * kStageRow * 4 + kRows * 8;
+constexpr int kLdsBytes = kQBytes + cmax(cmax(4 * kWaveLds, kMergeBytes), kStageBytes);   // 72 KB: two workgroups per CU
 
 // Slot (16 bytes = 8 keys of one head-dim element d) of the transposed V tile.
 // d = 8*a + j, c = key group (0..3).  Writers (fixed j, c; a = 0..15) and readers
@@ -100,13 +100,10 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int QT>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
-  using C = AttnCfg<QT>;
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  __shared__ unsigned s_ticket;
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
 
   // ---- workgroup id -> (x = (sequence, KV head, chunk), row block); same x => same id modulo 8 ----
   const int per = 8 * a.nrb;
@@ -126,27 +123,26 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
   const int k_end = min(n, k_begin + a.chunk);
   const int nchb = (n + a.chunk - 1) / a.chunk;   // chunks this sequence really has
 
-  unsigned char* kl = lds + wave * kWaveLds;
+  unsigned char* ql = lds;                        // Q tile, shared
+  unsigned char* kl = lds + kQBytes + wave * kWaveLds;
   unsigned char* vl = kl + kKBytes;
   const int col = lane & 31, half = lane >> 5;
   const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
+  const int row0 = rb * kRows;
 
-  // ---- query fragments (B operand of S^T = K . Q^T) and the row's metadata ----
-  bf16x8 qf[QT][8];
-  int tq[QT], pidq[QT], boffq[QT];
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    const int r = rb * C::kRows + qt * 32 + col;
-    const int rr = min(r, M - 1);                 // rows past M are computed on a duplicate and never stored
+  // ---- Q tile -> LDS (coalesced: 16 lanes per 256-byte row), read back as the B operand of S^T = K . Q^T ----
+  for (int p = tid; p < kRows * 16; p += 256) {
+    const int row = p >> 4, c = p & 15;
+    const int rr = min(row0 + row, M - 1);        // rows past M are computed on a duplicate and never stored
     const int t = rr / G, hh = rr - t * G;
     const __bf16* qp = a.q + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) qf[qt][s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s + 8 * half);
-    const ouro_tok_meta mq = a.meta[static_cast<size_t>(b) * T + t];
-    tq[qt] = t;
-    pidq[qt] = mq.phrase_id;
-    boffq[qt] = mq.branch_off;
+    *reinterpret_cast<u32x4*>(ql + k_slot(row, c) * 16) = *reinterpret_cast<const u32x4*>(qp + 8 * c);
   }
+  // this lane's query row (its column of S^T) and that row's metadata
+  const int rq = min(row0 + col, M - 1);
+  const int tq = rq / G;
+  const ouro_tok_meta mq = a.meta[static_cast<size_t>(b) * T + tq];
+  const int pidq = mq.phrase_id, boffq = mq.branch_off;
 
   // ---- staging: lane (kq = lane/16, c16 = lane%16) loads 16 B of 8 key rows per tile ----
   // Row order inside the tile is chosen so that the 8 rows of a lane are exactly one key
@@ -154,33 +150,43 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
   const int kq = lane >> 4, c16 = lane & 15;
   const int row_base = 16 * (kq >> 1) + 4 * (kq & 1);
   u32x4 kr[8], vr[8];
-#define OURO_ATTN_ISSUE_LOADS(TILE)                                                                              \
-  {                                                                                                              \
-    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                              \
-      const int kidx = min((TILE) + row_base + 8 * (i >> 2) + (i & 3), n - 1); /* clamp: finite data, masked */  \
-      const bool in_cache = kidx < L;                                                                            \
-      const size_t row = in_cache ? static_cast<size_t>(cu0 + kidx) : static_cast<size_t>(b) * T + (kidx - L);   \
-      const size_t off = (row * Hkv + g) * kD + 8 * c16;                                                         \
-      kr[i] = *reinterpret_cast<const u32x4*>((in_cache ? a.k_cache : a.k_blk) + off);                           \
-      vr[i] = *reinterpret_cast<const u32x4*>((in_cache ? a.v_cache : a.v_blk) + off);                           \
-    }                                                                                                            \
+  // Element offset of this lane's first row from the first row of a tile; its other rows follow at
+  // fixed multiples of the key stride (tile wholly inside the cache: one wave-uniform base pointer
+  // plus these, no per-row address arithmetic in the loop).
+  const unsigned kstride = static_cast<unsigned>(Hkv) * kD;
+  const unsigned loff0 = static_cast<unsigned>(row_base) * kstride + 8 * c16;
+#define OURO_ATTN_ISSUE_LOADS(TILE)                                                                                \
+  if ((TILE) + 32 <= L) {                                                                                          \
+    const size_t base = (static_cast<size_t>(cu0 + (TILE)) * Hkv + g) * kD;                                        \
+    const __bf16* kt = a.k_cache + base;                                                                           \
+    const __bf16* vt = a.v_cache + base;                                                                           \
+    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
+      const unsigned off = loff0 + static_cast<unsigned>(8 * (i >> 2) + (i & 3)) * kstride;                        \
+      kr[i] = *reinterpret_cast<const u32x4*>(kt + off);                                                           \
+      vr[i] = *reinterpret_cast<const u32x4*>(vt + off);                                                           \
+    }                                                                                                              \
+  } else {                                                                                                         \
+    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
+      const int kidx = min((TILE) + row_base + 8 * (i >> 2) + (i & 3), n - 1); /* clamp: finite data, masked */    \
+      const bool in_cache = kidx < L;                                                                              \
+      const size_t row = in_cache ? static_cast<size_t>(cu0 + kidx) : static_cast<size_t>(b) * T + (kidx - L);     \
+      const size_t off = (row * Hkv + g) * kD + 8 * c16;                                                           \
+      kr[i] = *reinterpret_cast<const u32x4*>((in_cache ? a.k_cache : a.k_blk) + off);                             \
+      vr[i] = *reinterpret_cast<const u32x4*>((in_cache ? a.v_cache : a.v_blk) + off);                             \
+    }                                                                                                              \
   }
 
-  f32x16 o[QT][4];
-  float m_run[QT], l_run[QT];
+  f32x16 o[4];
+  float m_run = -INFINITY, l_run = 0.f;
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    m_run[qt] = -INFINITY;
-    l_run[qt] = 0.f;
+  for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[qt][dt][i] = 0.f;
-  }
+    for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
 
   // this wave's tiles: k_begin + 32*(wave + 4*i)
   int tile = k_begin + 32 * wave;
-  if (tile < k_end) OURO_ATTN_ISSUE_LOADS(tile)
+  if (tile < k_end) { OURO_ATTN_ISSUE_LOADS(tile) }
+  __syncthreads();                                // Q tile complete
   for (; tile < k_end; tile += 128) {
     // ---- registers -> LDS ----
 #pragma unroll
@@ -197,156 +203,143 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
       t4.w = __builtin_amdgcn_perm(dword_of(vr[7], j >> 1), dword_of(vr[6], j >> 1), sel);
       *reinterpret_cast<u32x4*>(vl + vt_slot(c16, j, kq) * 16) = t4;
     }
-    if (tile + 128 < k_end) OURO_ATTN_ISSUE_LOADS(tile + 128)
+    if (tile + 128 < k_end) { OURO_ATTN_ISSUE_LOADS(tile + 128) }
     wave_lds_fence();
 
-    // ---- mask data for this tile.  Register i of a lane is key 8*(i/4) + 4*half + i%4 ----
-    const bool need_mask = tile + 32 > L;          // tile touches block keys or runs past n (wave-uniform)
-    int pidk[16];
-    if (need_mask) {
+    // ---- S^T = K . Q^T ----
+    f32x16 sacc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kl + k_slot(col, 2 * s + half) * 16);
+      const bf16x8 qf = *reinterpret_cast<const bf16x8*>(ql + k_slot(col, 2 * s + half) * 16);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf, sacc, 0, 0, 0);
+    }
+
+    // ---- mask (only tiles that touch block keys or run past n; wave-uniform branch) ----
+    // Register i of a lane is key 8*(i/4) + 4*half + i%4 of the tile.
+    if (tile + 32 > L) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int kb = tile + 8 * (i >> 2) + 4 * half + (i & 3) - L;
-        pidk[i] = (kb >= 0 && kb < T) ? a.meta[static_cast<size_t>(b) * T + kb].phrase_id : 0;
+        bool vis = kb < 0;
+        if (kb >= 0 && kb < T) {
+          const int pidk = a.meta[static_cast<size_t>(b) * T + kb].phrase_id;
+          vis = pidk == 0 ? kb <= boffq : (pidk == pidq && kb <= tq);
+        }
+        sacc[i] = vis ? sacc[i] : -INFINITY;
       }
     }
 
-    bf16x8 pf[QT][2];
+    // ---- online softmax (log2 domain) ----
+    // The running reference m_run is only raised when a score exceeds it by more than 8 (a factor
+    // 256, harmless in fp32 and for the bf16 rounding of P, which is relative); O and the sum stay
+    // consistent with whatever reference is in use, so the result is unchanged, and the 64-register
+    // rescale of O is skipped on almost every tile.
+    float tmax = sacc[0];
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-      // ---- S^T = K . Q^T ----
-      f32x16 sacc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kl + k_slot(col, 2 * s + half) * 16);
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][s], sacc, 0, 0, 0);
-      }
-      // ---- mask + online softmax (log2 domain) ----
-      float tmax = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float s = sacc[i] * a.scale_log2;
-        if (need_mask) {
-          const int kb = tile + 8 * (i >> 2) + 4 * half + (i & 3) - L;
-          const bool vis = kb < 0 || (kb < T && (pidk[i] == 0 ? kb <= boffq[qt] : (pidk[i] == pidq[qt] && kb <= tq[qt])));
-          s = vis ? s : -INFINITY;
-        }
-        sacc[i] = s;
-        tmax = fmaxf(tmax, s);
-      }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-      const float m_new = fmaxf(m_run[qt], tmax);
-      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = exp2f(m_run[qt] - m_safe);
-      m_run[qt] = m_new;
-      float psum = 0.f;
-      f32x8 p0, p1;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        p0[i] = exp2f(sacc[i] - m_safe);
-        p1[i] = exp2f(sacc[8 + i] - m_safe);
-        psum += p0[i] + p1[i];
-      }
-      l_run[qt] = l_run[qt] * alpha + psum;         // per-half partial sum; halves are added at the end
-      pf[qt][0] = __builtin_convertvector(p0, bf16x8);
-      pf[qt][1] = __builtin_convertvector(p1, bf16x8);
+    for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sacc[i]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * a.scale_log2;
+    if (__any(tmax > m_run + 8.0f)) {
+      const float m_new = fmaxf(m_run, tmax);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));
+      m_run = m_new;
+      l_run *= alpha;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) o[qt][dt][i] *= alpha;
+        for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;
     }
+    const float neg_m = m_run == -INFINITY ? 0.f : -m_run;
+    float psum = 0.f;
+    f32x8 p0, p1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      p0[i] = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.scale_log2, neg_m));
+      p1[i] = __builtin_amdgcn_exp2f(fmaf(sacc[8 + i], a.scale_log2, neg_m));
+      psum += p0[i] + p1[i];
+    }
+    l_run += psum;                                  // per-half partial sum; halves are added at the end
+    const bf16x8 pf0 = __builtin_convertvector(p0, bf16x8);
+    const bf16x8 pf1 = __builtin_convertvector(p1, bf16x8);
 
     // ---- O^T += V^T . P^T ----
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        const bf16x8 vf =
-            *reinterpret_cast<const bf16x8*>(vl + vt_slot(4 * dt + (col >> 3), col & 7, 2 * s + half) * 16);
-#pragma unroll
-        for (int qt = 0; qt < QT; ++qt) o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][s], o[qt][dt], 0, 0, 0);
-      }
+      const bf16x8 vf0 = *reinterpret_cast<const bf16x8*>(vl + vt_slot(4 * dt + (col >> 3), col & 7, half) * 16);
+      const bf16x8 vf1 = *reinterpret_cast<const bf16x8*>(vl + vt_slot(4 * dt + (col >> 3), col & 7, 2 + half) * 16);
+      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0, pf0, o[dt], 0, 0, 0);
+      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf1, pf1, o[dt], 0, 0, 0);
     }
     wave_lds_fence();                               // reads of this tile precede the next tile's LDS writes
   }
 #undef OURO_ATTN_ISSUE_LOADS
 
   // ---- merge the 4 wave states pairwise through LDS: (2,3) -> (0,1), then 1 -> 0 ----
-  f32x4* slot_o = reinterpret_cast<f32x4*>(lds);
-  float* slot_ml = reinterpret_cast<float*>(lds + 2 * C::kStateBytes);
+  unsigned char* scratch = lds + kQBytes;
+  f32x4* slot_o = reinterpret_cast<f32x4*>(scratch);
+  float* slot_ml = reinterpret_cast<float*>(scratch + 2 * kStateBytes);
 #pragma unroll
   for (int sft = 2; sft >= 1; sft >>= 1) {
     __syncthreads();
     if (wave >= sft && wave < 2 * sft) {
       const int slot = wave - sft;
 #pragma unroll
-      for (int qt = 0; qt < QT; ++qt) {
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-          for (int ig = 0; ig < 4; ++ig) {
-            f32x4 v4 = {o[qt][dt][4 * ig + 0], o[qt][dt][4 * ig + 1], o[qt][dt][4 * ig + 2], o[qt][dt][4 * ig + 3]};
-            slot_o[(slot * QT * 16 + (qt * 4 + dt) * 4 + ig) * 64 + lane] = v4;
-          }
-        slot_ml[((slot * QT + qt) * 64 + lane) * 2 + 0] = m_run[qt];
-        slot_ml[((slot * QT + qt) * 64 + lane) * 2 + 1] = l_run[qt];
-      }
+        for (int ig = 0; ig < 4; ++ig) {
+          f32x4 v4 = {o[dt][4 * ig + 0], o[dt][4 * ig + 1], o[dt][4 * ig + 2], o[dt][4 * ig + 3]};
+          slot_o[(slot * 16 + dt * 4 + ig) * 64 + lane] = v4;
+        }
+      slot_ml[(slot * 64 + lane) * 2 + 0] = m_run;
+      slot_ml[(slot * 64 + lane) * 2 + 1] = l_run;
     }
     __syncthreads();
     if (wave < sft) {
       const int slot = wave;
+      const float m_b = slot_ml[(slot * 64 + lane) * 2 + 0];
+      const float l_b = slot_ml[(slot * 64 + lane) * 2 + 1];
+      const float m_new = fmaxf(m_run, m_b);
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      const float fa = exp2f(m_run - m_safe), fb = exp2f(m_b - m_safe);
+      m_run = m_new;
+      l_run = l_run * fa + l_b * fb;
 #pragma unroll
-      for (int qt = 0; qt < QT; ++qt) {
-        const float m_b = slot_ml[((slot * QT + qt) * 64 + lane) * 2 + 0];
-        const float l_b = slot_ml[((slot * QT + qt) * 64 + lane) * 2 + 1];
-        const float m_new = fmaxf(m_run[qt], m_b);
-        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-        const float fa = exp2f(m_run[qt] - m_safe), fb = exp2f(m_b - m_safe);
-        m_run[qt] = m_new;
-        l_run[qt] = l_run[qt] * fa + l_b * fb;
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+        for (int ig = 0; ig < 4; ++ig) {
+          const f32x4 ob = slot_o[(slot * 16 + dt * 4 + ig) * 64 + lane];
 #pragma unroll
-          for (int ig = 0; ig < 4; ++ig) {
-            const f32x4 ob = slot_o[(slot * QT * 16 + (qt * 4 + dt) * 4 + ig) * 64 + lane];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[qt][dt][4 * ig + e] = o[qt][dt][4 * ig + e] * fa + ob[e] * fb;
-          }
-      }
+          for (int e = 0; e < 4; ++e) o[dt][4 * ig + e] = o[dt][4 * ig + e] * fa + ob[e] * fb;
+        }
     }
   }
   __syncthreads();
 
   // ---- wave 0 stages the workgroup's state row-major: stage_o[row][132], stage_ml[row][2] ----
-  float* stage_o = reinterpret_cast<float*>(lds);
-  float* stage_ml = stage_o + C::kRows * kStageRow;
+  float* stage_o = reinterpret_cast<float*>(scratch);
+  float* stage_ml = stage_o + kRows * kStageRow;
   if (wave == 0) {
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-      const float l_tot = l_run[qt] + __shfl_xor(l_run[qt], 32);
-      const int row = qt * 32 + col;
+    for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int ig = 0; ig < 4; ++ig) {
-          f32x4 v4 = {o[qt][dt][4 * ig + 0], o[qt][dt][4 * ig + 1], o[qt][dt][4 * ig + 2], o[qt][dt][4 * ig + 3]};
-          *reinterpret_cast<f32x4*>(stage_o + row * kStageRow + 32 * dt + 8 * ig + 4 * half) = v4;
-        }
-      if (half == 0) {
-        stage_ml[row * 2 + 0] = m_run[qt];
-        stage_ml[row * 2 + 1] = l_tot;
+      for (int ig = 0; ig < 4; ++ig) {
+        f32x4 v4 = {o[dt][4 * ig + 0], o[dt][4 * ig + 1], o[dt][4 * ig + 2], o[dt][4 * ig + 3]};
+        *reinterpret_cast<f32x4*>(stage_o + col * kStageRow + 32 * dt + 8 * ig + 4 * half) = v4;
       }
+    if (half == 0) {
+      stage_ml[col * 2 + 0] = m_run;
+      stage_ml[col * 2 + 1] = l_tot;
     }
   }
   __syncthreads();
 
   const int group = bg * a.nrb + rb;
-  const int row0 = rb * C::kRows;
   if (nchb == 1) {
     // ---- the workgroup saw every key of the sequence: normalise and write bf16, 16 B per thread ----
-    for (int p = tid; p < C::kRows * 16; p += 256) {
+    for (int p = tid; p < kRows * 16; p += 256) {
       const int row = p >> 4, c = p & 15;
       const int r = row0 + row;
       if (r >= M) continue;
@@ -364,81 +357,72 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     return;
   }
 
-  // ---- several chunks: leave a partial, the last workgroup of the group merges ----
-  {
-    const size_t pbase = (static_cast<size_t>(group) * a.nch + chunk) * C::kRows;
-    for (int p = tid; p < C::kRows * 64; p += 256) {
-      const int row = p >> 6, c = p & 63;
-      const float* src = stage_o + row * kStageRow + 2 * c;
-      st_agent_f2(a.part_o + (pbase + row) * kD + 2 * c, src[0], src[1]);
-    }
-    for (int p = tid; p < C::kRows; p += 256) st_agent_f2(a.part_ml + (pbase + p) * 2, stage_ml[2 * p], stage_ml[2 * p + 1]);
+  // ---- several chunks: leave a partial for the combine kernel (plain coalesced stores, no waiting) ----
+  const size_t pbase = (static_cast<size_t>(group) * a.nch + chunk) * kRows;
+  for (int p = tid; p < kRows * 32; p += 256) {
+    const int row = p >> 5, c = p & 31;
+    *reinterpret_cast<f32x4*>(a.part_o + (pbase + row) * kD + 4 * c) =
+        *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 4 * c);
   }
-  partials_written();
-  __syncthreads();
-  if (tid == 0) s_ticket = take_ticket(a.counters + group);
-  __syncthreads();
-  if (s_ticket != static_cast<unsigned>(nchb - 1)) return;
-  {
-    // Device-coherent loads have a long round trip: issue them in batches of 4 chunks (20 loads in
-    // flight per thread) and fold each batch into a running (max, sum, O) in ascending chunk order.
-    const size_t gbase = static_cast<size_t>(group) * a.nch * C::kRows;
-    for (int p = tid; p < C::kRows * 16; p += 256) {
-      const int row = p >> 4, c = p & 15;
-      const int r = row0 + row;
-      if (r >= M) continue;
-      float m_star = -INFINITY, lsum = 0.f;
-      f32x8 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      for (int ch0 = 0; ch0 < nchb; ch0 += 4) {
-        float m_c[4], l_c[4];
-        f32x8 x[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int ch = min(ch0 + u, nchb - 1);          // clamped duplicates are skipped below
-          const size_t prow = gbase + static_cast<size_t>(ch) * C::kRows + row;
-          ld_agent_f2(a.part_ml + prow * 2, m_c[u], l_c[u]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float x0, x1;
-            ld_agent_f2(a.part_o + prow * kD + 8 * c + 2 * e, x0, x1);
-            x[u][2 * e] = x0;
-            x[u][2 * e + 1] = x1;
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (ch0 + u >= nchb) continue;
-          const float m_new = fmaxf(m_star, m_c[u]);
-          const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-          const float fa = exp2f(m_star - m_safe), fb = exp2f(m_c[u] - m_safe);
-          m_star = m_new;
-          lsum = lsum * fa + l_c[u] * fb;
-          acc = acc * fa + x[u] * fb;
-        }
-      }
-      const float inv = 1.0f / lsum;
-      const int t = r / G, hh = r - t * G;
-      __bf16* op = a.out + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
-      *reinterpret_cast<bf16x8*>(op + 8 * c) = __builtin_convertvector(acc * inv, bf16x8);
-      if (a.lse && c == 0)
-        a.lse[(static_cast<size_t>(b) * Hq + g * G + hh) * T + t] = (m_star + log2f(lsum)) * kLn2;
-    }
-  }
-  if (tid == 0) reset_ticket(a.counters + group);   // ready for the next call
+  for (int p = tid; p < kRows * 2; p += 256) a.part_ml[pbase * 2 + p] = stage_ml[p];
 }
 
-template <int QT>
-int launch_qt(const AttnArgs& a, unsigned grid, hipStream_t stream) {
-  using C = AttnCfg<QT>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<QT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-    if (e != hipSuccess) return hip_failed(e);
-    attr_set = true;
+// Merge the chunk partials of every query row of the sequences that span several chunks:
+// out = sum_c 2^(m_c - m*) O_c / sum_c 2^(m_c - m*) l_c, chunks folded in ascending order
+// (deterministic).  One thread per (row, 8 head-dim elements); loads are issued four chunks
+// at a time so that their latencies overlap.
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
+  constexpr int rows_wg = kRows;
+  const long p = static_cast<long>(blockIdx.x) * 256 + threadIdx.x;
+  const int c = static_cast<int>(p & 15);
+  const long rowg = p >> 4;
+  const int row = static_cast<int>(rowg % rows_wg);
+  const long group = rowg / rows_wg;
+  if (group >= static_cast<long>(a.n_x / a.nch) * a.nrb) return;
+  const int rb = static_cast<int>(group % a.nrb);
+  const int bg = static_cast<int>(group / a.nrb);
+  const int b = bg / a.Hkv, g = bg - b * a.Hkv;
+  const int r = rb * rows_wg + row;
+  if (r >= a.M) return;
+  const int n = static_cast<int>(a.cu[b + 1] - a.cu[b]) + a.T;
+  const int nchb = (n + a.chunk - 1) / a.chunk;
+  if (nchb == 1) return;                            // written directly by the main kernel
+  const size_t gbase = static_cast<size_t>(group) * a.nch * rows_wg;
+  float m_star = -INFINITY, lsum = 0.f;
+  f32x8 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int ch0 = 0; ch0 < nchb; ch0 += 4) {
+    float m_c[4], l_c[4];
+    f32x4 x0[4], x1[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int ch = min(ch0 + u, nchb - 1);          // clamped duplicates are skipped below
+      const size_t prow = gbase + static_cast<size_t>(ch) * rows_wg + row;
+      m_c[u] = a.part_ml[prow * 2];
+      l_c[u] = a.part_ml[prow * 2 + 1];
+      x0[u] = *reinterpret_cast<const f32x4*>(a.part_o + prow * kD + 8 * c);
+      x1[u] = *reinterpret_cast<const f32x4*>(a.part_o + prow * kD + 8 * c + 4);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (ch0 + u >= nchb) continue;
+      const float m_new = fmaxf(m_star, m_c[u]);
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      const float fa = exp2f(m_star - m_safe), fb = exp2f(m_c[u] - m_safe);
+      m_star = m_new;
+      lsum = lsum * fa + l_c[u] * fb;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[e] = acc[e] * fa + x0[u][e] * fb;
+        acc[4 + e] = acc[4 + e] * fa + x1[u][e] * fb;
+      }
+    }
   }
-  hipLaunchKernelGGL(attn_bf16_kernel<QT>, dim3(grid), dim3(256), C::kLdsBytes, stream, a);
-  return check_launch();
+  const float inv = 1.0f / lsum;
+  const int t = r / a.G, hh = r - t * a.G;
+  __bf16* op = a.out + ((static_cast<size_t>(b) * a.T + t) * a.Hq + g * a.G + hh) * kD;
+  *reinterpret_cast<bf16x8*>(op + 8 * c) = __builtin_convertvector(acc * inv, bf16x8);
+  if (a.lse && c == 0)
+    a.lse[(static_cast<size_t>(b) * a.Hq + g * a.G + hh) * a.T + t] = (m_star + log2f(lsum)) * kLn2;
 }
 
 }  // namespace
@@ -455,7 +439,6 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
   a.out = static_cast<__bf16*>(d.out);
   a.lse = d.lse;
   unsigned char* ws = static_cast<unsigned char*>(d.workspace);
-  a.counters = reinterpret_cast<unsigned*>(ws);
   a.part_ml = reinterpret_cast<float*>(ws + plan.counter_bytes);
   a.part_o = reinterpret_cast<float*>(ws + plan.counter_bytes + plan.part_ml_bytes);
   a.T = d.T;
@@ -469,7 +452,19 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
   a.n_x = d.B * d.Hkv * plan.nch;
   a.scale_log2 = scale * 1.4426950408889634f;
   const unsigned grid = static_cast<unsigned>((a.n_x + 7) / 8) * 8u * plan.nrb;
-  return plan.qt == 2 ? launch_qt<2>(a, grid, stream) : launch_qt<1>(a, grid, stream);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return hip_failed(e);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(attn_bf16_kernel, dim3(grid), dim3(256), kLdsBytes, stream, a);
+  int st = check_launch();
+  if (st != OURO_OK || plan.nch == 1) return st;
+  const long threads = static_cast<long>(d.B) * d.Hkv * plan.nrb * kRows * 16;
+  hipLaunchKernelGGL(attn_combine_kernel, dim3(static_cast<unsigned>((threads + 255) / 256)), dim3(256), 0, stream, a);
+  return check_launch();
 }
 
 }  // namespace ouro

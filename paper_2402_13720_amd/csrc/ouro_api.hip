@@ -24,14 +24,13 @@ static long env_long(const char* name, long dflt) {
 // KV head) for its query rows and, when the sequence spans several chunks, leaves one fp32
 // partial.  Small chunks fill the 256 compute units; large chunks keep the partial traffic
 // (rows * 512 bytes per workgroup) small against the K/V bytes of a chunk (chunk * 512 bytes).
-// The default aims at about three workgroups per compute unit.  OURO_ATTN_CHUNK (keys) and
-// OURO_ATTN_QT (1 or 2) override the heuristic for tuning runs.
+// The default aims at about three workgroups per compute unit.  OURO_ATTN_CHUNK (keys)
+// overrides the heuristic for tuning runs.
 AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
   AttnPlan p{};
   const int G = d.Hq / d.Hkv;
   const int M = d.T * G;
-  const long qt_env = env_long("OURO_ATTN_QT", 0);
-  p.qt = qt_env == 1 || qt_env == 2 ? static_cast<int>(qt_env) : (M > 64 ? 2 : 1);
+  p.qt = 1;
   p.rows_wg = 32 * p.qt;
   p.nrb = (M + p.rows_wg - 1) / p.rows_wg;
   const long maxn = static_cast<long>(d.max_seqlen) + d.T;
