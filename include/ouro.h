@@ -19,16 +19,8 @@
  *     Descriptors themselves are HOST memory, read during the call only.
  *   - Calls only enqueue work on the given HIP stream (a hipStream_t passed as
  *     void*; NULL = the default stream).  They never allocate, free or
- *     synchronise, keep no host state between calls, and may be called from several
+ *     synchronise, keep no state between calls, and may be called from several
  *     threads on different streams with disjoint outputs and workspaces.
- *   - Workspaces.  The kernels that split their work over workgroups find the
- *     workgroup that finishes last with ticket counters kept at the start of the
- *     workspace.  A workspace must therefore be zero-filled once after it is
- *     allocated (ouro_workspace_init, or any zero fill of at least its first MiB);
- *     every call that completes leaves the counters zero again, so the same
- *     workspace can be reused by any later call of any shape, one call at a time.
- *     After a call that did not complete (device fault, aborted stream) zero it
- *     again.  The rest of the workspace may hold anything.
  *   - Return value: OURO_OK (0) or a negative OURO_E_* code.  On an error nothing
  *     has been enqueued, except OURO_E_HIP which reports a failed launch (the
  *     hipError_t is kept per thread for ouro_last_hip_error()).
@@ -114,7 +106,7 @@ typedef struct {
   float softmax_scale;         /* <= 0: 1/sqrt(D) */
   void* out;                   /* [B, T, Hq, D], same dtype as q */
   float* lse;                  /* optional [B, Hq, T]: natural-log softmax denominator; NULL to skip */
-  void* workspace;             /* >= ouro_verify_attn_workspace() bytes, 16-byte aligned, counters zero (see above) */
+  void* workspace;             /* >= ouro_verify_attn_workspace() bytes, 16-byte aligned; contents arbitrary */
   size_t workspace_bytes;
 } ouro_attn_desc;
 
@@ -140,7 +132,7 @@ typedef struct {
   const void* w;               /* [V, Hd] row-major: row v is the output embedding of token v */
   int32_t* argmax_out;         /* [R] */
   float* max_out;              /* optional [R]: the winning logit (fp32); NULL to skip */
-  void* workspace;             /* >= ouro_lmhead_argmax_workspace() bytes, 16-byte aligned, counters zero (see above) */
+  void* workspace;             /* >= ouro_lmhead_argmax_workspace() bytes, 16-byte aligned; contents arbitrary */
   size_t workspace_bytes;
 } ouro_lmhead_desc;
 
@@ -186,10 +178,6 @@ OURO_API int ouro_accept(const ouro_accept_desc* desc, void* hip_stream);
 /* ------------------------------------------------------------------------------------ */
 /* Host-side helpers                                                                     */
 /* ------------------------------------------------------------------------------------ */
-/* Enqueue a zero fill of the counter area (the first min(bytes, 1 MiB) bytes) of a DEVICE
- * workspace.  A kernel, not a memset, so that it may be recorded into a HIP graph. */
-OURO_API int ouro_workspace_init(void* workspace, size_t bytes, void* hip_stream);
-
 /* Debug check of a HOST copy of one sequence's metadata against the layout rules above
  * (main tokens first with branch_off = index, phrases contiguous and ascending with ids
  * 1..K, -1 <= b_j < gamma).  Returns OURO_OK or OURO_E_BAD_META / OURO_E_NULLPTR /

@@ -66,8 +66,6 @@ def _load() -> C.CDLL:
     lib.ouro_lmhead_argmax.argtypes = [C.POINTER(ouro_lmhead_desc), C.c_void_p]
     lib.ouro_accept.restype = C.c_int
     lib.ouro_accept.argtypes = [C.POINTER(ouro_accept_desc), C.c_void_p]
-    lib.ouro_workspace_init.restype = C.c_int
-    lib.ouro_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
     lib.ouro_validate_meta_host.restype = C.c_int
     lib.ouro_validate_meta_host.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.ouro_status_string.restype = C.c_char_p
@@ -119,14 +117,8 @@ def pack_meta(pid, boff) -> torch.Tensor:
 
 
 def alloc_workspace(nbytes: int, device) -> torch.Tensor:
-    """A zero-filled workspace (the library keeps ticket counters at its start; they must start at zero)."""
-    return torch.zeros(max(int(nbytes), 256), dtype=torch.uint8, device=device)
-
-
-def ouro_workspace_init(workspace: torch.Tensor, stream=None) -> None:
-    """Re-zero the counter area of a workspace (needed only after a call that did not complete)."""
-    _check(lib.ouro_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
-           "ouro_workspace_init")
+    """Scratch for partial results; contents never matter."""
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
 def make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen,

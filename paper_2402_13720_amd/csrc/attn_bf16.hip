@@ -439,8 +439,8 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
   a.out = static_cast<__bf16*>(d.out);
   a.lse = d.lse;
   unsigned char* ws = static_cast<unsigned char*>(d.workspace);
-  a.part_ml = reinterpret_cast<float*>(ws + plan.counter_bytes);
-  a.part_o = reinterpret_cast<float*>(ws + plan.counter_bytes + plan.part_ml_bytes);
+  a.part_ml = reinterpret_cast<float*>(ws);
+  a.part_o = reinterpret_cast<float*>(ws + plan.part_ml_bytes);
   a.T = d.T;
   a.Hq = d.Hq;
   a.Hkv = d.Hkv;

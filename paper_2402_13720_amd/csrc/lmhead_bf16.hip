@@ -16,9 +16,11 @@
 //   * after the loop the 4 partial accumulator sets are summed through LDS (fixed order),
 //     and the arg-max epilogue reduces lane -> wave -> workgroup; one (value, index) pair
 //     per (slab, row) goes to the workspace, the logits never leave the chip;
-//   * the workgroup that finishes last (ticket counter in the workspace) reduces the pairs
-//     over the slabs and writes the result: one launch, no float atomics, order-independent
-//     because (larger value, then smaller index) is a total order.
+//   * a second tiny kernel reduces the pairs over the slabs (no float atomics; the result is
+//     order-independent because (larger value, then smaller index) is a total order).  A
+//     single-launch variant in which the last workgroup did this reduction was measured
+//     slower: store acknowledgement, ticket and reload are three device-scope round trips
+//     that every workgroup pays at the very end, when nothing is left to overlap them with.
 #include <math.h>
 
 #include "ouro_internal.hpp"
@@ -36,9 +38,6 @@ struct LmArgs {
   const __bf16* hidden;
   const __bf16* w;
   float2* part;        // [nslab][R]
-  unsigned* counters;  // [gridDim.y], zero on entry, zero on exit
-  int32_t* argmax_out;
-  float* max_out;
   int R, Hd, V;
 };
 
@@ -191,51 +190,8 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
       const int i2 = besti[mt * C::kHRows + rl];
       if (better(v2, i2, bv, bi)) { bv = v2; bi = i2; }
     }
-    st_agent_f2(reinterpret_cast<float*>(a.part + static_cast<size_t>(blockIdx.x) * R + r0 + rl), bv, __int_as_float(bi));
+    a.part[static_cast<size_t>(blockIdx.x) * R + r0 + rl] = make_float2(bv, __int_as_float(bi));
   }
-
-  // ---- the workgroup that finishes last for this row slice reduces over the slabs ----
-  __shared__ unsigned s_ticket;
-  partials_written();
-  __syncthreads();
-  if (threadIdx.x == 0) s_ticket = take_ticket(a.counters + blockIdx.y);
-  __syncthreads();
-  if (s_ticket != gridDim.x - 1) return;
-  constexpr int kSlices = 256 / C::kHRows;          // threads per row, each scanning every kSlices-th slab
-  const int rl = threadIdx.x % C::kHRows, slice = threadIdx.x / C::kHRows;
-  const int nslab = gridDim.x;
-  float bv = -INFINITY;
-  int bi = 0x7fffffff;
-  if (r0 + rl < R) {
-    // device-coherent loads have a long round trip: keep 16 of them in flight per thread
-    for (int s0 = slice; s0 < nslab; s0 += 16 * kSlices) {
-      float pv[16], pi[16];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const int s = min(s0 + u * kSlices, nslab - 1);     // clamped duplicates cannot change the result
-        ld_agent_f2(reinterpret_cast<const float*>(a.part + static_cast<size_t>(s) * R + r0 + rl), pv[u], pi[u]);
-      }
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const int i = __float_as_int(pi[u]);
-        if (better(pv[u], i, bv, bi)) { bv = pv[u]; bi = i; }
-      }
-    }
-  }
-  bestv[slice * C::kHRows + rl] = bv;               // kSlices <= MT for both variants: the area is large enough
-  besti[slice * C::kHRows + rl] = bi;
-  __syncthreads();
-  if (slice == 0 && r0 + rl < R) {
-#pragma unroll
-    for (int sl = 1; sl < kSlices; ++sl) {
-      const float v2 = bestv[sl * C::kHRows + rl];
-      const int i2 = besti[sl * C::kHRows + rl];
-      if (better(v2, i2, bv, bi)) { bv = v2; bi = i2; }
-    }
-    a.argmax_out[r0 + rl] = bi;
-    if (a.max_out) a.max_out[r0 + rl] = bv;
-  }
-  if (threadIdx.x == 0) reset_ticket(a.counters + blockIdx.y);
 }
 
 template <int MT, int NT>
@@ -258,10 +214,7 @@ int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_
   LmArgs a{};
   a.hidden = static_cast<const __bf16*>(d.hidden);
   a.w = static_cast<const __bf16*>(d.w);
-  a.counters = static_cast<unsigned*>(d.workspace);
-  a.part = reinterpret_cast<float2*>(static_cast<unsigned char*>(d.workspace) + plan.counter_bytes);
-  a.argmax_out = d.argmax_out;
-  a.max_out = d.max_out;
+  a.part = static_cast<float2*>(d.workspace);
   a.R = d.R;
   a.Hd = d.Hd;
   a.V = d.V;

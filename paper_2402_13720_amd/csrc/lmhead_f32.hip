@@ -9,8 +9,6 @@
 // reduces over slabs.
 #include <math.h>
 
-#include <algorithm>
-
 #include "ouro_internal.hpp"
 
 namespace ouro {
@@ -86,33 +84,20 @@ __global__ __launch_bounds__(256) void lmhead_final_kernel(const float2* part, i
   }
 }
 
-// Zero fill with 16-byte stores (a kernel rather than a memset node, so that callers may capture it).
-__global__ __launch_bounds__(256) void zero_fill_kernel(uint4* p, size_t n16) {
-  for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += static_cast<size_t>(gridDim.x) * 256)
-    p[i] = make_uint4(0u, 0u, 0u, 0u);
-}
-
 }  // namespace
 
 int launch_lmhead_f32(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream) {
   dim3 grid(plan.nslab, plan.nrtile);
   const size_t smem = static_cast<size_t>(plan.rtile) * 4 * 2 * sizeof(float);
   hipLaunchKernelGGL(lmhead_f32_kernel, grid, dim3(256), smem, stream, d, plan.slab, plan.rtile,
-                     reinterpret_cast<float2*>(static_cast<unsigned char*>(d.workspace) + plan.counter_bytes));
+                     static_cast<float2*>(d.workspace));
   return check_launch();
 }
 
 int launch_lmhead_final(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream) {
   hipLaunchKernelGGL(lmhead_final_kernel, dim3((d.R + 3) / 4), dim3(256), 0, stream,
-                     reinterpret_cast<const float2*>(static_cast<unsigned char*>(d.workspace) + plan.counter_bytes),
+                     static_cast<const float2*>(d.workspace),
                      plan.nslab, d.R, d.argmax_out, d.max_out);
-  return check_launch();
-}
-
-int launch_zero_fill(void* p, size_t bytes, hipStream_t stream) {
-  const size_t n16 = bytes / 16;
-  const unsigned grid = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 256));
-  hipLaunchKernelGGL(zero_fill_kernel, dim3(grid), dim3(256), 0, stream, static_cast<uint4*>(p), n16);
   return check_launch();
 }
 

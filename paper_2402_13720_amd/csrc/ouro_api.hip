@@ -24,7 +24,8 @@ static long env_long(const char* name, long dflt) {
 // KV head) for its query rows and, when the sequence spans several chunks, leaves one fp32
 // partial.  Small chunks fill the 256 compute units; large chunks keep the partial traffic
 // (rows * 512 bytes per workgroup) small against the K/V bytes of a chunk (chunk * 512 bytes).
-// The default aims at about three workgroups per compute unit.  OURO_ATTN_CHUNK (keys)
+// The default aims at about 1.5 workgroups per compute unit (two are resident at a time; measured
+// best on the 7B/13B/70B-shaped workloads, where per-workgroup prologue/epilogue latency dominates).  OURO_ATTN_CHUNK (keys)
 // overrides the heuristic for tuning runs.
 AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
   AttnPlan p{};
@@ -36,7 +37,7 @@ AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
   const long maxn = static_cast<long>(d.max_seqlen) + d.T;
   const long tiles = (maxn + 31) / 32;
   const long groups = std::max<long>(1, static_cast<long>(d.B) * d.Hkv * p.nrb);
-  long want = (768 + groups - 1) / groups;           // chunk slots per sequence
+  long want = (384 + groups - 1) / groups;           // chunk slots per sequence
   want = std::max<long>(1, std::min(want, (tiles + 3) / 4));
   long tiles_per_chunk = ((tiles + want - 1) / want + 3) / 4 * 4;
   const long chunk_env = env_long("OURO_ATTN_CHUNK", 0);
@@ -45,7 +46,6 @@ AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
   p.nch = static_cast<int>((maxn + p.chunk - 1) / p.chunk);
   if (p.nch > 1) {
     const size_t slots = static_cast<size_t>(groups) * p.nch;
-    p.counter_bytes = round_up(static_cast<size_t>(groups) * sizeof(unsigned), 256);
     p.part_ml_bytes = round_up(slots * p.rows_wg * 2 * sizeof(float), 256);
     p.part_o_bytes = round_up(slots * p.rows_wg * d.D * sizeof(float), 256);
   }
@@ -69,7 +69,6 @@ LmPlan plan_lmhead(const ouro_lmhead_desc& d) {
   }
   p.nslab = (d.V + p.slab - 1) / p.slab;
   p.nrtile = (d.R + p.rtile - 1) / p.rtile;
-  p.counter_bytes = round_up(static_cast<size_t>(p.nrtile) * sizeof(unsigned), 256);
   p.part_bytes = round_up(static_cast<size_t>(p.nslab) * std::max(d.R, 1) * 8, 256);
   return p;
 }
@@ -82,8 +81,6 @@ static int validate_attn(const ouro_attn_desc* d, bool need_pointers) {
   if (d->max_seqlen < 0) return OURO_E_BAD_SHAPE;
   if (d->dtype == OURO_BF16 ? d->D != 128 : (d->D != 64 && d->D != 128)) return OURO_E_BAD_SHAPE;
   if (static_cast<long>(d->T) * (d->Hq / d->Hkv) > 32768) return OURO_E_BAD_SHAPE;
-  if (static_cast<long>(d->B) * d->Hkv * (d->T * (d->Hq / d->Hkv) / 32 + 1) * 4 > static_cast<long>(kMaxCounterBytes))
-    return OURO_E_BAD_SHAPE;
   if (!need_pointers || d->B == 0) return OURO_OK;
   if (!d->q || !d->cu_seqlens || !d->k_blk || !d->v_blk || !d->meta || !d->out) return OURO_E_NULLPTR;
   if (d->max_seqlen > 0 && (!d->k_cache || !d->v_cache)) return OURO_E_NULLPTR;
@@ -157,8 +154,7 @@ int ouro_lmhead_argmax(const ouro_lmhead_desc* desc, void* hip_stream) {
   if (!desc->workspace) return OURO_E_NULLPTR;
   if (desc->workspace_bytes < p.total()) return OURO_E_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (desc->dtype == OURO_BF16) return launch_lmhead_bf16(*desc, p, stream);
-  st = launch_lmhead_f32(*desc, p, stream);
+  st = desc->dtype == OURO_BF16 ? launch_lmhead_bf16(*desc, p, stream) : launch_lmhead_f32(*desc, p, stream);
   if (st != OURO_OK) return st;
   return launch_lmhead_final(*desc, p, stream);
 }
@@ -168,14 +164,6 @@ int ouro_accept(const ouro_accept_desc* desc, void* hip_stream) {
   if (st != OURO_OK) return st;
   if (desc->B == 0) return OURO_OK;
   return launch_accept(*desc, static_cast<hipStream_t>(hip_stream));
-}
-
-int ouro_workspace_init(void* workspace, size_t bytes, void* hip_stream) {
-  if (!workspace) return bytes == 0 ? OURO_OK : OURO_E_NULLPTR;
-  if (!aligned16(workspace)) return OURO_E_MISALIGNED;
-  const size_t n = std::min(bytes, kMaxCounterBytes) / 16 * 16;
-  if (n == 0) return OURO_OK;
-  return launch_zero_fill(workspace, n, static_cast<hipStream_t>(hip_stream));
 }
 
 int ouro_validate_meta_host(const ouro_tok_meta* m, int32_t T, int32_t gamma, int32_t K, int32_t beta) {

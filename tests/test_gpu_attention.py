@@ -119,10 +119,10 @@ def test_full_size_config5_sampled_heads():
 
 
 def test_workspace_is_reusable_across_shapes_and_calls():
-    """The ticket counters at the start of the workspace are left zero by every call."""
+    """A workspace may hold anything on entry and can be shared by calls of different shapes."""
     from paper_2402_13720_amd import binding as ob
     from gpu_util import upload_attention
-    ws = ob.alloc_workspace(64 << 20, DEV)
+    ws = torch.full((64 << 20,), 0xA5, dtype=torch.uint8, device=DEV)
     for kw, seed in [(dict(B=2, Hq=4, Hkv=2, L=(700, 3000)), 1), (dict(B=1, Hq=8, Hkv=8, L=5000), 2),
                      (dict(B=2, Hq=4, Hkv=2, L=(700, 3000)), 1)]:
         cfg = W.scaled(W.CONFIGS[2], **kw)
@@ -135,12 +135,3 @@ def test_workspace_is_reusable_across_shapes_and_calls():
                                       t["meta"], t["max_seqlen"], workspace=ws)
             torch.cuda.synchronize()
             assert np.abs(to_np64(out) - ref).max() <= 2e-2
-        assert int(ws[:256].view(torch.int32).abs().sum()) == 0
-
-
-def test_workspace_init_clears_dirty_counters():
-    from paper_2402_13720_amd import binding as ob
-    ws = torch.full((1 << 21,), 255, dtype=torch.uint8, device=DEV)
-    ob.ouro_workspace_init(ws)
-    torch.cuda.synchronize()
-    assert int(ws[: 1 << 20].sum()) == 0 and int(ws[1 << 20:].min()) == 255

@@ -100,7 +100,7 @@ def test_full_size_config5_sampled_rows():
 
 
 def test_workspace_is_reusable_across_shapes_and_calls():
-    ws = ob.alloc_workspace(8 << 20, DEV)
+    ws = torch.full((8 << 20,), 0xA5, dtype=torch.uint8, device=DEV)
     for (R, Hd, V, seed) in [(64, 512, 3000, 1), (200, 256, 1500, 2), (64, 512, 3000, 1)]:
         cfg = W.scaled(W.CONFIGS[2], B=1, Hq=Hd // 64, Hkv=Hd // 64, D=64, V=V)
         hidden, w = W.make_hidden(cfg, seed, rows=R), W.make_lmhead_weight(cfg, seed)
@@ -112,4 +112,3 @@ def test_workspace_is_reusable_across_shapes_and_calls():
             arg = ob.ouro_lmhead_argmax(h_d, w_d, workspace=ws).cpu().numpy()
             bad = [r for r in range(R) if arg[r] != ref["argmax"][r] and ref["margin"][r] >= MARGIN]
             assert not bad
-        assert int(ws[:256].view(torch.int32).abs().sum()) == 0
