@@ -109,8 +109,9 @@ def cpu_baseline(cfg, inp, w, draws, budget_s):
 
 
 def load_traffic(workload_key):
-    """HBM bytes per launch of the dominant kernel from committed rocprofv3 --pmc summaries, if present."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, each scaled by the plain-copy calibration) of the
+    main kernels, from the committed rocprofv3 --pmc summary for this workload, if present."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     try:
         with open(path) as f:
             return json.load(f).get(workload_key)
@@ -196,8 +197,30 @@ def main():
     d_acc = ob.make_accept_desc(tok, arg.view(cfg.B, cfg.T), meta, root, cfg.gamma, cfg.K, cfg.beta_p, acc_out)
     f_attn, f_lm, f_acc = ob.lib.ouro_verify_attn, ob.lib.ouro_lmhead_argmax, ob.lib.ouro_accept
 
-    def step(i, ev=None):
+    # raw HIP events handed to the library: it records them right around the main kernel of a call,
+    # on the launch stream, so that kernel's duration is measured inside the timed region
+    hip = C.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+
+    def new_event():
+        e = C.c_void_p()
+        if hip.hipEventCreate(C.byref(e)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        return e
+
+    def elapsed_us(e0, e1):
+        ms = C.c_float()
+        if hip.hipEventElapsedTime(C.byref(ms), e0, e1) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return ms.value * 1e3
+
+    kev = [[new_event() for _ in range(4)] for _ in range(args.steps)]
+
+    def step(i, ev=None, kv=None):
         r = i % nrot
+        d_attn[r].ev_start, d_attn[r].ev_stop = (kv[0], kv[1]) if kv else (None, None)
+        d_lm[r].ev_start, d_lm[r].ev_stop = (kv[2], kv[3]) if kv else (None, None)
         if ev is not None:
             ev[0].record(stream)
         st = f_attn(C.byref(d_attn[r]), hs)
@@ -218,7 +241,7 @@ def main():
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, events[i])
+        step(args.warmup + i, events[i], kev[i])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
@@ -226,22 +249,28 @@ def main():
     seg = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(3)] for ev in events])   # ms
     t_attn, t_lm, t_acc = (float(x) for x in seg.mean(axis=0))
     tokens = cfg.R
+    # main-kernel durations (ms): attention split-KV kernel, LM-head weight-streaming kernel
+    k_attn = float(np.mean([elapsed_us(k[0], k[1]) for k in kev])) * 1e-3
+    k_lm = float(np.mean([elapsed_us(k[2], k[3]) for k in kev])) * 1e-3
 
     lm_bytes = lmhead_algorithmic_bytes(cfg)
     at_bytes = attn_algorithmic_bytes(cfg, total_rows)
-    lm_gbs = lm_bytes / (t_lm * 1e-3) / 1e9
-    at_gbs = at_bytes / (t_attn * 1e-3) / 1e9
-    lm_tflops = lmhead_flops(cfg) / (t_lm * 1e-3) / 1e12
-    at_tflops = attn_flops(cfg, seqlens) / (t_attn * 1e-3) / 1e12
+    lm_gbs = lm_bytes / (k_lm * 1e-3) / 1e9
+    at_gbs = at_bytes / (k_attn * 1e-3) / 1e9
+    lm_tflops = lmhead_flops(cfg) / (k_lm * 1e-3) / 1e12
+    at_tflops = attn_flops(cfg, seqlens) / (k_attn * 1e-3) / 1e12
     workload = "cfg%d:%s" % (cfg.cfg_id, cfg.name)
     lm_mfma_bound = cfg.R >= 312          # arithmetic intensity ~R flop/B against a machine balance of ~312
+    traffic = load_traffic(workload) or {}
     if lm_mfma_bound:
-        roofline = {"kernel": "ouro_lmhead_argmax", "bound": "mfma", "achieved": lm_tflops,
-                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": lm_tflops / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": load_traffic(workload)}
+        roofline = {"kernel": "lmhead_bf16_kernel (main kernel of ouro_lmhead_argmax)", "bound": "mfma",
+                    "achieved": lm_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": lm_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic.get("lmhead_bytes"),
+                    "kernel_us": k_lm * 1e3, "algorithmic_bytes": lm_bytes}
     else:
-        roofline = {"kernel": "ouro_lmhead_argmax", "bound": "hbm", "achieved": lm_gbs, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": lm_gbs / HBM_PEAK_GBS, "traffic": load_traffic(workload)}
+        roofline = {"kernel": "lmhead_bf16_kernel (main kernel of ouro_lmhead_argmax)", "bound": "hbm",
+                    "achieved": lm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": lm_gbs / HBM_PEAK_GBS,
+                    "traffic": traffic.get("lmhead_bytes"), "kernel_us": k_lm * 1e3, "algorithmic_bytes": lm_bytes}
     result = {
         "metric": "draft tokens verified per second (one verification step: attention + LM head/argmax + accept)",
         "value": tokens / (ms_step * 1e-3),
@@ -254,10 +283,12 @@ def main():
         "config": {"workload": workload, "B": cfg.B, "T": cfg.T, "gamma": cfg.gamma, "K": cfg.K, "beta": cfg.beta_p,
                    "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D, "cache_rows": total_rows, "V": cfg.V,
                    "branch": args.branch, "rotated_copies": nrot},
-        "kernel_us": {"ouro_verify_attn": t_attn * 1e3, "ouro_lmhead_argmax": t_lm * 1e3, "ouro_accept": t_acc * 1e3},
+        "call_us": {"ouro_verify_attn": t_attn * 1e3, "ouro_lmhead_argmax": t_lm * 1e3, "ouro_accept": t_acc * 1e3},
         "roofline": roofline,
-        "roofline_attn": {"kernel": "ouro_verify_attn", "bound": "hbm", "achieved": at_gbs, "peak": HBM_PEAK_GBS,
-                          "unit": "GB/s", "frac": at_gbs / HBM_PEAK_GBS, "mfma_tflops": at_tflops},
+        "roofline_attn": {"kernel": "attn_bf16_kernel (main kernel of ouro_verify_attn)", "bound": "hbm",
+                          "achieved": at_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": at_gbs / HBM_PEAK_GBS,
+                          "traffic": traffic.get("attn_bytes"), "kernel_us": k_attn * 1e3,
+                          "algorithmic_bytes": at_bytes, "mfma_tflops": at_tflops},
         "lmhead_mfma_frac": lm_tflops / MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else None,
         "cpu_baseline": cpu,
         "accepted_per_sequence": acc_out["n_accept"].cpu().tolist()[:16],

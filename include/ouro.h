@@ -108,6 +108,8 @@ typedef struct {
   float* lse;                  /* optional [B, Hq, T]: natural-log softmax denominator; NULL to skip */
   void* workspace;             /* >= ouro_verify_attn_workspace() bytes, 16-byte aligned; contents arbitrary */
   size_t workspace_bytes;
+  void* ev_start;              /* optional hipEvent_t pair (NULL to skip), recorded on the stream right before and */
+  void* ev_stop;               /* right after the call's main kernel, so that a profiler can time that kernel alone */
 } ouro_attn_desc;
 
 /* Host-only: bytes of workspace the call will need for this descriptor (data pointers are
@@ -134,6 +136,8 @@ typedef struct {
   float* max_out;              /* optional [R]: the winning logit (fp32); NULL to skip */
   void* workspace;             /* >= ouro_lmhead_argmax_workspace() bytes, 16-byte aligned; contents arbitrary */
   size_t workspace_bytes;
+  void* ev_start;              /* optional hipEvent_t pair around the main (weight-streaming) kernel, as above */
+  void* ev_stop;
 } ouro_lmhead_desc;
 
 OURO_API size_t ouro_lmhead_argmax_workspace(const ouro_lmhead_desc* desc);

@@ -28,6 +28,7 @@ class ouro_attn_desc(C.Structure):
         ("softmax_scale", C.c_float),
         ("out", C.c_void_p), ("lse", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+        ("ev_start", C.c_void_p), ("ev_stop", C.c_void_p),
     ]
 
 
@@ -37,6 +38,7 @@ class ouro_lmhead_desc(C.Structure):
         ("R", C.c_int32), ("Hd", C.c_int32), ("V", C.c_int32), ("reserved", C.c_int32),
         ("hidden", C.c_void_p), ("w", C.c_void_p), ("argmax_out", C.c_void_p), ("max_out", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+        ("ev_start", C.c_void_p), ("ev_stop", C.c_void_p),
     ]
 
 

@@ -459,8 +459,11 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
     if (e != hipSuccess) return hip_failed(e);
     attr_set = true;
   }
+  if (d.ev_start && hipEventRecord(static_cast<hipEvent_t>(d.ev_start), stream) != hipSuccess) return hip_failed(hipGetLastError());
   hipLaunchKernelGGL(attn_bf16_kernel, dim3(grid), dim3(256), kLdsBytes, stream, a);
   int st = check_launch();
+  if (st == OURO_OK && d.ev_stop && hipEventRecord(static_cast<hipEvent_t>(d.ev_stop), stream) != hipSuccess)
+    return hip_failed(hipGetLastError());
   if (st != OURO_OK || plan.nch == 1) return st;
   const long threads = static_cast<long>(d.B) * d.Hkv * plan.nrb * kRows * 16;
   hipLaunchKernelGGL(attn_combine_kernel, dim3(static_cast<unsigned>((threads + 255) / 256)), dim3(256), 0, stream, a);

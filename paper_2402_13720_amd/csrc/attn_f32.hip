@@ -108,9 +108,13 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(ouro_attn_desc d, float sc
 
 int launch_attn_f32(const ouro_attn_desc& d, float scale, hipStream_t stream) {
   dim3 grid(d.T, d.Hq, d.B);
+  if (d.ev_start && hipEventRecord(static_cast<hipEvent_t>(d.ev_start), stream) != hipSuccess) return hip_failed(hipGetLastError());
   if (d.D == 64) hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(64), 0, stream, d, scale);
   else hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(64), 0, stream, d, scale);
-  return check_launch();
+  const int st = check_launch();
+  if (st == OURO_OK && d.ev_stop && hipEventRecord(static_cast<hipEvent_t>(d.ev_stop), stream) != hipSuccess)
+    return hip_failed(hipGetLastError());
+  return st;
 }
 
 }  // namespace ouro

@@ -154,8 +154,12 @@ int ouro_lmhead_argmax(const ouro_lmhead_desc* desc, void* hip_stream) {
   if (!desc->workspace) return OURO_E_NULLPTR;
   if (desc->workspace_bytes < p.total()) return OURO_E_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (desc->ev_start && hipEventRecord(static_cast<hipEvent_t>(desc->ev_start), stream) != hipSuccess)
+    return hip_failed(hipGetLastError());
   st = desc->dtype == OURO_BF16 ? launch_lmhead_bf16(*desc, p, stream) : launch_lmhead_f32(*desc, p, stream);
   if (st != OURO_OK) return st;
+  if (desc->ev_stop && hipEventRecord(static_cast<hipEvent_t>(desc->ev_stop), stream) != hipSuccess)
+    return hip_failed(hipGetLastError());
   return launch_lmhead_final(*desc, p, stream);
 }
 

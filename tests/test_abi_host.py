@@ -37,8 +37,8 @@ def test_version_and_status_strings():
 
 def test_struct_sizes_match_the_header_layout():
     # 8 int32 + 7 pointers + float(+pad) + 4 pointers/size_t
-    assert C.sizeof(ob.ouro_attn_desc) == 32 + 7 * 8 + 8 + 4 * 8
-    assert C.sizeof(ob.ouro_lmhead_desc) == 24 + 6 * 8
+    assert C.sizeof(ob.ouro_attn_desc) == 32 + 7 * 8 + 8 + 6 * 8
+    assert C.sizeof(ob.ouro_lmhead_desc) == 24 + 8 * 8
     assert C.sizeof(ob.ouro_accept_desc) == 24 + 11 * 8
 
 
