@@ -145,8 +145,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int pidq = mq.phrase_id, boffq = mq.branch_off;
 
   // ---- staging: lane (kq = lane/16, c16 = lane%16) loads 16 B of 8 key rows per tile ----
-  // Row order inside the tile is chosen so that the 8 rows of a lane are exactly one key
-  // group of the P.V contraction: rows 16*(kq/2) + 8*jj + 4*(kq%2) + r, i = 4*jj + r.
+  // Load i of a lane fetches key 4*i + kq of the tile, so one load instruction covers 4 adjacent
+  // key rows.  The 8 keys of a lane must be one key group of the P.V contraction, and the S^T
+  // accumulator fixes which accumulator rows form a group (rows 16*(kq/2) + 8*jj + 4*(kq%2) + r,
+  // i = 4*jj + r); so key 4*i + kq is simply stored in that row of the K tile: the rows of S^T are a
+  // permutation of the tile's keys, which only the mask has to know about (key_of_reg below).
   const int kq = lane >> 4, c16 = lane & 15;
   const int row_base = 16 * (kq >> 1) + 4 * (kq & 1);
   u32x4 kr[8], vr[8];
@@ -154,20 +157,20 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   // fixed multiples of the key stride (tile wholly inside the cache: one wave-uniform base pointer
   // plus these, no per-row address arithmetic in the loop).
   const unsigned kstride = static_cast<unsigned>(Hkv) * kD;
-  const unsigned loff0 = static_cast<unsigned>(row_base) * kstride + 8 * c16;
+  const unsigned loff0 = static_cast<unsigned>(kq) * kstride + 8 * c16;
 #define OURO_ATTN_ISSUE_LOADS(TILE)                                                                                \
   if ((TILE) + 32 <= L) {                                                                                          \
     const size_t base = (static_cast<size_t>(cu0 + (TILE)) * Hkv + g) * kD;                                        \
     const __bf16* kt = a.k_cache + base;                                                                           \
     const __bf16* vt = a.v_cache + base;                                                                           \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
-      const unsigned off = loff0 + static_cast<unsigned>(8 * (i >> 2) + (i & 3)) * kstride;                        \
+      const unsigned off = loff0 + static_cast<unsigned>(4 * i) * kstride;                                         \
       kr[i] = *reinterpret_cast<const u32x4*>(kt + off);                                                           \
       vr[i] = *reinterpret_cast<const u32x4*>(vt + off);                                                           \
     }                                                                                                              \
   } else {                                                                                                         \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
-      const int kidx = min((TILE) + row_base + 8 * (i >> 2) + (i & 3), n - 1); /* clamp: finite data, masked */    \
+      const int kidx = min((TILE) + 4 * i + kq, n - 1); /* clamp: finite data, masked later */                     \
       const bool in_cache = kidx < L;                                                                              \
       const size_t row = in_cache ? static_cast<size_t>(cu0 + kidx) : static_cast<size_t>(b) * T + (kidx - L);     \
       const size_t off = (row * Hkv + g) * kD + 8 * c16;                                                           \
@@ -218,11 +221,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     }
 
     // ---- mask (only tiles that touch block keys or run past n; wave-uniform branch) ----
-    // Register i of a lane is key 8*(i/4) + 4*half + i%4 of the tile.
+    // Accumulator register i of a lane (half h) is S^T row 8*(i/4) + 4*h + i%4, which holds
+    // key 16*((i/4)%2) + 4*(i%4) + 2*(i/8) + h of the tile.
     if (tile + 32 > L) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int kb = tile + 8 * (i >> 2) + 4 * half + (i & 3) - L;
+        const int kb = tile + 16 * ((i >> 2) & 1) + 4 * (i & 3) + 2 * (i >> 3) + half - L;
         bool vis = kb < 0;
         if (kb >= 0 && kb < T) {
           const int pidk = a.meta[static_cast<size_t>(b) * T + kb].phrase_id;

@@ -218,6 +218,7 @@ int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_
   a.R = d.R;
   a.Hd = d.Hd;
   a.V = d.V;
+  if (plan.variant == 3) return launch_lmhead_bf16_tile(d, plan, stream);
   if (plan.variant == 1) return launch_variant<4, 2>(a, plan, stream);
   return launch_variant<4, 4>(a, plan, stream);
 }

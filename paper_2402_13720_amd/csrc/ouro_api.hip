@@ -62,10 +62,14 @@ LmPlan plan_lmhead(const ouro_lmhead_desc& d) {
     p.variant = 1;
     p.slab = 128;
     p.rtile = 64;
-  } else {
+  } else if (d.R <= 128) {
     p.variant = 2;
     p.slab = 128;
     p.rtile = 128;
+  } else {
+    p.variant = 3;                                   // MFMA-bound: 256 x 256 workgroup tiles
+    p.slab = 256;
+    p.rtile = 256;
   }
   p.nslab = (d.V + p.slab - 1) / p.slab;
   p.nrtile = (d.R + p.rtile - 1) / p.rtile;

@@ -38,7 +38,7 @@ int launch_attn_f32(const ouro_attn_desc& d, float scale, hipStream_t stream);
 
 // ---- LM head --------------------------------------------------------------------------
 struct LmPlan {
-  int variant;     // 0: fp32 VALU, 1: bf16 skinny (R tile 64), 2: bf16 skinny (R tile 128)
+  int variant;     // 0: fp32 VALU, 1: bf16 streaming (R tile 64), 2: bf16 streaming (R tile 128), 3: bf16 large tile
   int slab;        // vocabulary rows per workgroup
   int nslab;       // ceil(V / slab)
   int rtile;       // rows per grid.y slice
@@ -49,6 +49,7 @@ struct LmPlan {
 
 LmPlan plan_lmhead(const ouro_lmhead_desc& d);
 int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
+int launch_lmhead_bf16_tile(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
 int launch_lmhead_f32(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
 int launch_lmhead_final(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
 
