@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU-oracle baseline leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--branch", default="uniform", choices=["uniform", "last"])
+    ap.add_argument("--w-layout", default="tiled", choices=["tiled", "row"],
+                    help="LM-head weight layout: re-blocked once at set-up into contiguous 128x64 tiles "
+                         "(ouro_lmhead_pack_w; default) or the row-major [V, hidden] matrix as is")
     return ap.parse_args()
 
 
@@ -158,6 +161,10 @@ def main():
     kcs = [kc0] + [kc0.clone() for _ in range(nrot - 1)]
     vcs = [vc0] + [vc0.clone() for _ in range(nrot - 1)]
     ws = [w0] + [w0.clone() for _ in range(nrot - 1)]
+    if args.w_layout == "tiled" and cfg.dtype == "bf16":
+        ws = [ob.ouro_lmhead_pack_w(x) for x in ws]       # load-time step, outside the timed region
+        torch.cuda.synchronize()
+        del w0
     cu = torch.from_numpy(inp["cu_seqlens"]).to(dev)
     meta = ob.pack_meta(inp["pid"], inp["boff"]).to(dev)
     root = torch.from_numpy(draws["root_pred"]).to(dev)
@@ -166,7 +173,7 @@ def main():
     hidden = out.view(cfg.R, cfg.hidden)
     arg = torch.empty(cfg.R, dtype=torch.int32, device=dev)
     ws_attn = ob.alloc_workspace(ob.ouro_verify_attn_workspace(q, k_blk, max_seqlen), dev)
-    ws_lm = ob.alloc_workspace(ob.ouro_lmhead_argmax_workspace(hidden, w0), dev)
+    ws_lm = ob.alloc_workspace(ob.ouro_lmhead_argmax_workspace(hidden, ws[0]), dev)
     acc_out = ob.alloc_accept_outputs(cfg.B, cfg.gamma, cfg.K, cfg.beta_p, dev)
 
     # draft ids: half of the block positions carry the token they will be compared with (the greedy
@@ -282,7 +289,8 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": workload, "B": cfg.B, "T": cfg.T, "gamma": cfg.gamma, "K": cfg.K, "beta": cfg.beta_p,
                    "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D, "cache_rows": total_rows, "V": cfg.V,
-                   "branch": args.branch, "rotated_copies": nrot},
+                   "branch": args.branch, "rotated_copies": nrot,
+                   "w_layout": args.w_layout if cfg.dtype == "bf16" else "row"},
         "call_us": {"ouro_verify_attn": t_attn * 1e3, "ouro_lmhead_argmax": t_lm * 1e3, "ouro_accept": t_acc * 1e3},
         "roofline": roofline,
         "roofline_attn": {"kernel": "attn_bf16_kernel (main kernel of ouro_verify_attn)", "bound": "hbm",

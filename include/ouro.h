@@ -129,9 +129,13 @@ typedef struct {
   int32_t R;                   /* rows (B*T block tokens), >= 0 */
   int32_t Hd;                  /* hidden size, multiple of 64 (bf16) / 4 (f32) */
   int32_t V;                   /* vocabulary, >= 1 */
-  int32_t reserved;
+  int32_t w_layout;            /* OURO_W_ROW_MAJOR or OURO_W_TILED (bf16 only) */
   const void* hidden;          /* [R, Hd] row-major (the attention output viewed as [B*T, Hq*D]) */
-  const void* w;               /* [V, Hd] row-major: row v is the output embedding of token v */
+  const void* w;               /* OURO_W_ROW_MAJOR: [V, Hd], row v is the output embedding of token v.
+                                  OURO_W_TILED: the same matrix re-blocked once by ouro_lmhead_pack_w into
+                                  contiguous 16 KB tiles [ceil(V/128)][Hd/64][128 rows][64 columns] (rows past V
+                                  zero): every wave then streams whole contiguous tiles, which is what HBM
+                                  delivers fastest.  Weights are static, so the packing is a load-time step. */
   int32_t* argmax_out;         /* [R] */
   float* max_out;              /* optional [R]: the winning logit (fp32); NULL to skip */
   void* workspace;             /* >= ouro_lmhead_argmax_workspace() bytes, 16-byte aligned; contents arbitrary */
@@ -140,8 +144,16 @@ typedef struct {
   void* ev_stop;
 } ouro_lmhead_desc;
 
+enum { OURO_W_ROW_MAJOR = 0, OURO_W_TILED = 1 };
+
 OURO_API size_t ouro_lmhead_argmax_workspace(const ouro_lmhead_desc* desc);
 OURO_API int ouro_lmhead_argmax(const ouro_lmhead_desc* desc, void* hip_stream);
+
+/* Bytes of the OURO_W_TILED form of a bf16 [V, Hd] weight (Hd a multiple of 64); 0 if the shape is invalid. */
+OURO_API size_t ouro_lmhead_packed_w_bytes(int32_t V, int32_t Hd);
+/* Enqueue the re-blocking of a bf16 row-major DEVICE weight [V, Hd] into w_tiled (DEVICE, 16-byte aligned,
+ * >= ouro_lmhead_packed_w_bytes bytes, not overlapping w_row_major). */
+OURO_API int ouro_lmhead_pack_w(const void* w_row_major, void* w_tiled, int32_t V, int32_t Hd, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------ */
 /* Acceptance (Eq. (3) for the main draft, Eq. (9) for each phrase, and the rule after    */

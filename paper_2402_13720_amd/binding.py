@@ -35,7 +35,7 @@ class ouro_attn_desc(C.Structure):
 class ouro_lmhead_desc(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32), ("dtype", C.c_int32),
-        ("R", C.c_int32), ("Hd", C.c_int32), ("V", C.c_int32), ("reserved", C.c_int32),
+        ("R", C.c_int32), ("Hd", C.c_int32), ("V", C.c_int32), ("w_layout", C.c_int32),
         ("hidden", C.c_void_p), ("w", C.c_void_p), ("argmax_out", C.c_void_p), ("max_out", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
         ("ev_start", C.c_void_p), ("ev_stop", C.c_void_p),
@@ -66,6 +66,10 @@ def _load() -> C.CDLL:
     lib.ouro_lmhead_argmax_workspace.argtypes = [C.POINTER(ouro_lmhead_desc)]
     lib.ouro_lmhead_argmax.restype = C.c_int
     lib.ouro_lmhead_argmax.argtypes = [C.POINTER(ouro_lmhead_desc), C.c_void_p]
+    lib.ouro_lmhead_packed_w_bytes.restype = C.c_size_t
+    lib.ouro_lmhead_packed_w_bytes.argtypes = [C.c_int32, C.c_int32]
+    lib.ouro_lmhead_pack_w.restype = C.c_int
+    lib.ouro_lmhead_pack_w.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     lib.ouro_accept.restype = C.c_int
     lib.ouro_accept.argtypes = [C.POINTER(ouro_accept_desc), C.c_void_p]
     lib.ouro_validate_meta_host.restype = C.c_int
@@ -169,10 +173,41 @@ def ouro_verify_attn(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, max_se
     return out
 
 
+OURO_W_ROW_MAJOR, OURO_W_TILED = 0, 1
+
+
+class TiledWeight:
+    """A bf16 LM-head weight re-blocked by ouro_lmhead_pack_w (contiguous 128 x 64 tiles)."""
+
+    def __init__(self, data: torch.Tensor, V: int, Hd: int):
+        self.data, self.V, self.Hd = data, V, Hd
+        self.shape = (V, Hd)
+        self.dtype = torch.bfloat16
+
+    def data_ptr(self):
+        return self.data.data_ptr()
+
+    def is_contiguous(self):
+        return True
+
+
+def ouro_lmhead_pack_w(w: torch.Tensor, stream=None) -> TiledWeight:
+    """Re-block a row-major bf16 weight [V, Hd] once, at load time, into the tiled layout."""
+    assert w.dtype == torch.bfloat16 and w.is_contiguous()
+    V, Hd = w.shape
+    nbytes = int(lib.ouro_lmhead_packed_w_bytes(V, Hd))
+    if nbytes == 0:
+        raise OuroError(-2, "ouro_lmhead_packed_w_bytes")
+    out = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=w.device)
+    _check(lib.ouro_lmhead_pack_w(_ptr(w), _ptr(out), V, Hd, _stream(stream)), "ouro_lmhead_pack_w")
+    return TiledWeight(out, V, Hd)
+
+
 def make_lmhead_desc(hidden, w, argmax_out, max_out=None, workspace=None) -> ouro_lmhead_desc:
     d = ouro_lmhead_desc()
     d.struct_size = C.sizeof(ouro_lmhead_desc)
     d.dtype = _dtype_code(hidden)
+    d.w_layout = OURO_W_TILED if isinstance(w, TiledWeight) else OURO_W_ROW_MAJOR
     d.R, d.Hd, d.V = hidden.shape[0], hidden.shape[1], w.shape[0]
     d.hidden, d.w, d.argmax_out, d.max_out = _ptr(hidden), _ptr(w), _ptr(argmax_out), _ptr(max_out)
     d.workspace = _ptr(workspace)

@@ -39,6 +39,7 @@ struct LmArgs {
   const __bf16* w;
   float2* part;        // [nslab][R]
   int R, Hd, V;
+  int tiled;        // W given as contiguous [slab][k-tile][128][64] tiles
 };
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
@@ -82,9 +83,13 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   // Row pointers of this lane are fixed for the whole kernel; only the k offset moves.
   const __bf16* wrow[MT * 4];
   const __bf16* hrow[NT * 4];
+  // Row-major W: row pointers, k-tile kt at +64*kt.  Tiled W: the slab's tiles are contiguous 16 KB blocks,
+  // row r of k-tile kt at (kt*128 + r)*64, so one load instruction of the wave reads 1 KB contiguous.
+  const size_t wstep = a.tiled ? 128 * 64 : 64;
 #pragma unroll
   for (int p = 0; p < MT * 4; ++p)
-    wrow[p] = a.w + static_cast<size_t>(min(slab0 + 8 * p + lr, V - 1)) * Hd + 8 * lc;   // rows past V: duplicate, masked later
+    wrow[p] = a.tiled ? a.w + (static_cast<size_t>(blockIdx.x) * (Hd / 64) * 128 + 8 * p + lr) * 64 + 8 * lc
+                      : a.w + static_cast<size_t>(min(slab0 + 8 * p + lr, V - 1)) * Hd + 8 * lc;   // rows past V: duplicate, masked later
 #pragma unroll
   for (int p = 0; p < NT * 4; ++p)
     hrow[p] = a.hidden + static_cast<size_t>(min(r0 + 8 * p + lr, R - 1)) * Hd + 8 * lc;
@@ -92,7 +97,7 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   {                                                                                        \
     const size_t koff = static_cast<size_t>(KT) * 64;                                      \
     _Pragma("unroll") for (int p = 0; p < MT * 4; ++p)                                     \
-        wreg[p] = *reinterpret_cast<const u32x4*>(wrow[p] + koff);                         \
+        wreg[p] = *reinterpret_cast<const u32x4*>(wrow[p] + static_cast<size_t>(KT) * wstep); \
     _Pragma("unroll") for (int p = 0; p < NT * 4; ++p)                                     \
         hreg[p] = *reinterpret_cast<const u32x4*>(hrow[p] + koff);                         \
   }
@@ -109,11 +114,23 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   int kt = wave;
   if (kt < nkt) OURO_LM_ISSUE_LOADS(kt)
   for (; kt < nkt; kt += 4) {
+    // Each staging register is copied to LDS and immediately re-armed with its load of the wave's next
+    // k-tile, so the memory queue of the wave is never empty while the tile is being written (the last
+    // iteration harmlessly re-reads its own tile).
+    const size_t ktn = static_cast<size_t>(kt + 4 < nkt ? kt + 4 : kt);
+    const size_t knext = ktn * 64, wnext = ktn * wstep;
 #pragma unroll
-    for (int p = 0; p < MT * 4; ++p) *reinterpret_cast<u32x4*>(wl + tile_slot(8 * p + lr, lc) * 16) = wreg[p];
+    for (int p = 0; p < MT * 4; ++p) {
+      *reinterpret_cast<u32x4*>(wl + tile_slot(8 * p + lr, lc) * 16) = wreg[p];
+      wreg[p] = *reinterpret_cast<const u32x4*>(wrow[p] + wnext);
+      __builtin_amdgcn_sched_barrier(0);
+    }
 #pragma unroll
-    for (int p = 0; p < NT * 4; ++p) *reinterpret_cast<u32x4*>(hl + tile_slot(8 * p + lr, lc) * 16) = hreg[p];
-    if (kt + 4 < nkt) OURO_LM_ISSUE_LOADS(kt + 4)
+    for (int p = 0; p < NT * 4; ++p) {
+      *reinterpret_cast<u32x4*>(hl + tile_slot(8 * p + lr, lc) * 16) = hreg[p];
+      hreg[p] = *reinterpret_cast<const u32x4*>(hrow[p] + knext);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     wave_lds_fence();
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -194,6 +211,23 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   }
 }
 
+// Row-major bf16 [V, Hd] -> [ceil(V/128)][Hd/64][128][64] tiles, 16 bytes per thread; rows past V become zero.
+__global__ __launch_bounds__(256) void pack_w_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int V, int Hd,
+                                                     size_t n16) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= n16) return;
+  const int c = static_cast<int>(i & 7);                 // 16-byte chunk within a 64-column row
+  const int r = static_cast<int>((i >> 3) & 127);        // row within the tile
+  const size_t tile = i >> 10;
+  const int nkt = Hd / 64;
+  const int kt = static_cast<int>(tile % nkt);
+  const size_t slab = tile / nkt;
+  const size_t v = slab * 128 + r;
+  u32x4 x = {0u, 0u, 0u, 0u};
+  if (v < static_cast<size_t>(V)) x = src[(v * Hd + static_cast<size_t>(kt) * 64) / 8 + c];
+  dst[i] = x;
+}
+
 template <int MT, int NT>
 int launch_variant(const LmArgs& a, const LmPlan& plan, hipStream_t stream) {
   using C = LmCfg<MT, NT>;
@@ -210,6 +244,13 @@ int launch_variant(const LmArgs& a, const LmPlan& plan, hipStream_t stream) {
 
 }  // namespace
 
+int launch_pack_w(const void* src, void* dst, int V, int Hd, hipStream_t stream) {
+  const size_t n16 = static_cast<size_t>((V + 127) / 128) * 128 * static_cast<size_t>(Hd) / 8;
+  hipLaunchKernelGGL(pack_w_kernel, dim3(static_cast<unsigned>((n16 + 255) / 256)), dim3(256), 0, stream,
+                     static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), V, Hd, n16);
+  return check_launch();
+}
+
 int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream) {
   LmArgs a{};
   a.hidden = static_cast<const __bf16*>(d.hidden);
@@ -218,6 +259,7 @@ int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_
   a.R = d.R;
   a.Hd = d.Hd;
   a.V = d.V;
+  a.tiled = d.w_layout == OURO_W_TILED;
   if (plan.variant == 3) return launch_lmhead_bf16_tile(d, plan, stream);
   if (plan.variant == 1) return launch_variant<4, 2>(a, plan, stream);
   return launch_variant<4, 4>(a, plan, stream);

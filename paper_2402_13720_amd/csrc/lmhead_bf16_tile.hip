@@ -45,6 +45,7 @@ struct TileArgs {
   float2* part;     // [nslab][R]
   int R, Hd, V;
   int nslab, nrtile;
+  int tiled;        // W given as contiguous [V/128][k-tile][128][64] tiles
 };
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
@@ -74,14 +75,19 @@ __global__ __launch_bounds__(kThreads) void lmhead_bf16_tile_kernel(TileArgs a) 
   const __bf16* hp[4];
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
-    wp[p] = a.w + static_cast<size_t>(min(v0 + 64 * p + lr, V - 1)) * Hd + 8 * lc;   // rows past V: duplicate, masked later
+    const int row = 64 * p + lr;                       // row of the 256-row tile = two 128-row tiled slabs
+    const int slab128 = min(2 * slab + (row >> 7), (V + 127) / 128 - 1);
+    wp[p] = a.tiled ? a.w + (static_cast<size_t>(slab128) * (Hd / 64) * 128 + (row & 127)) * 64 + 8 * lc
+                    : a.w + static_cast<size_t>(min(v0 + row, V - 1)) * Hd + 8 * lc;   // rows past V: duplicate, masked later
     hp[p] = a.hidden + static_cast<size_t>(min(r0 + 64 * p + lr, R - 1)) * Hd + 8 * lc;
   }
+  const size_t wstep = a.tiled ? 128 * 64 : kBK;
   u32x4 wreg[4], hreg[4];
 #define OURO_TILE_GLOAD(KT)                                                                                    \
   {                                                                                                            \
     const size_t koff = static_cast<size_t>(KT) * kBK;                                                         \
-    _Pragma("unroll") for (int p = 0; p < 4; ++p) wreg[p] = *reinterpret_cast<const u32x4*>(wp[p] + koff);     \
+    _Pragma("unroll") for (int p = 0; p < 4; ++p)                                                              \
+        wreg[p] = *reinterpret_cast<const u32x4*>(wp[p] + static_cast<size_t>(KT) * wstep);                    \
     _Pragma("unroll") for (int p = 0; p < 4; ++p) hreg[p] = *reinterpret_cast<const u32x4*>(hp[p] + koff);     \
   }
 #define OURO_TILE_LDS_STORE(BUF)                                                                               \
@@ -189,6 +195,7 @@ int launch_lmhead_bf16_tile(const ouro_lmhead_desc& d, const LmPlan& plan, hipSt
   a.V = d.V;
   a.nslab = plan.nslab;
   a.nrtile = plan.nrtile;
+  a.tiled = d.w_layout == OURO_W_TILED;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_bf16_tile_kernel),

@@ -100,6 +100,7 @@ static int validate_lmhead(const ouro_lmhead_desc* d, bool need_pointers) {
   if (d->dtype != OURO_F32 && d->dtype != OURO_BF16) return OURO_E_UNSUPPORTED_DTYPE;
   if (d->R < 0 || d->V < 1 || d->Hd < 1) return OURO_E_BAD_SHAPE;
   if (d->Hd % (d->dtype == OURO_BF16 ? 64 : 4) != 0) return OURO_E_BAD_SHAPE;
+  if (d->w_layout != OURO_W_ROW_MAJOR && !(d->w_layout == OURO_W_TILED && d->dtype == OURO_BF16)) return OURO_E_BAD_SHAPE;
   if (!need_pointers || d->R == 0) return OURO_OK;
   if (!d->hidden || !d->w || !d->argmax_out) return OURO_E_NULLPTR;
   if (!aligned16(d->hidden) || !aligned16(d->w) || !aligned16(d->workspace)) return OURO_E_MISALIGNED;
@@ -165,6 +166,18 @@ int ouro_lmhead_argmax(const ouro_lmhead_desc* desc, void* hip_stream) {
   if (desc->ev_stop && hipEventRecord(static_cast<hipEvent_t>(desc->ev_stop), stream) != hipSuccess)
     return hip_failed(hipGetLastError());
   return launch_lmhead_final(*desc, p, stream);
+}
+
+size_t ouro_lmhead_packed_w_bytes(int32_t V, int32_t Hd) {
+  if (V < 1 || Hd < 64 || Hd % 64 != 0) return 0;
+  return static_cast<size_t>((V + 127) / 128) * 128 * static_cast<size_t>(Hd) * 2;
+}
+
+int ouro_lmhead_pack_w(const void* w_row_major, void* w_tiled, int32_t V, int32_t Hd, void* hip_stream) {
+  if (!w_row_major || !w_tiled) return OURO_E_NULLPTR;
+  if (ouro_lmhead_packed_w_bytes(V, Hd) == 0) return OURO_E_BAD_SHAPE;
+  if (!aligned16(w_row_major) || !aligned16(w_tiled)) return OURO_E_MISALIGNED;
+  return launch_pack_w(w_row_major, w_tiled, V, Hd, static_cast<hipStream_t>(hip_stream));
 }
 
 int ouro_accept(const ouro_accept_desc* desc, void* hip_stream) {

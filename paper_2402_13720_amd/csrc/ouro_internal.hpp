@@ -51,6 +51,7 @@ LmPlan plan_lmhead(const ouro_lmhead_desc& d);
 int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
 int launch_lmhead_bf16_tile(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
 int launch_lmhead_f32(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
+int launch_pack_w(const void* src, void* dst, int V, int Hd, hipStream_t stream);
 int launch_lmhead_final(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
 
 // ---- acceptance -----------------------------------------------------------------------

@@ -21,7 +21,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
     assert {"ouro_verify_attn", "ouro_lmhead_argmax", "ouro_accept", "ouro_verify_attn_workspace",
-            "ouro_lmhead_argmax_workspace", "ouro_validate_meta_host", "ouro_status_string",
+            "ouro_lmhead_argmax_workspace", "ouro_lmhead_packed_w_bytes", "ouro_lmhead_pack_w", "ouro_validate_meta_host", "ouro_status_string",
             "ouro_last_hip_error", "ouro_version"} <= set(names)
     for n in names:
         assert hasattr(ob.lib, n), n
@@ -104,6 +104,20 @@ def test_lmhead_descriptor_validation():
     assert f(C.byref(_lm_desc(**ok, workspace=512, workspace_bytes=8)), None) == -4
     need = ob.lib.ouro_lmhead_argmax_workspace(C.byref(_lm_desc()))
     assert need >= 250 * 64 * 8
+
+
+def test_packed_weight_helpers():
+    f = ob.lib.ouro_lmhead_packed_w_bytes
+    assert f(32000, 4096) == 32000 * 4096 * 2
+    assert f(1000, 256) == 1024 * 256 * 2            # rows padded to a multiple of 128
+    assert f(0, 64) == 0 and f(10, 100) == 0
+    g = ob.lib.ouro_lmhead_pack_w
+    assert g(None, 256, 10, 64, None) == -1
+    assert g(256, 512, 10, 100, None) == -2
+    assert g(260, 512, 10, 64, None) == -5
+    lm = ob.lib.ouro_lmhead_argmax
+    assert lm(C.byref(_lm_desc(w_layout=7)), None) == -2
+    assert lm(C.byref(_lm_desc(w_layout=1, dtype=ob.OURO_F32)), None) == -2
 
 
 def _acc_desc(**kw):

@@ -13,18 +13,20 @@ pytestmark = pytest.mark.gpu
 MARGIN = 1e-3
 
 
-def _run(cfg, hidden, w):
+def _run(cfg, hidden, w, tiled=False):
     dt = torch_dtype(cfg)
     h_d = torch.from_numpy(hidden).to(DEV).to(dt).contiguous()
     w_d = torch.from_numpy(w).to(DEV).to(dt).contiguous()
+    if tiled:
+        w_d = ob.ouro_lmhead_pack_w(w_d)
     mx = torch.empty(hidden.shape[0], dtype=torch.float32, device=DEV)
     arg = ob.ouro_lmhead_argmax(h_d, w_d, max_out=mx)
     torch.cuda.synchronize()
     return arg.cpu().numpy(), mx.cpu().numpy()
 
 
-def _check(cfg, hidden, w, rows=None):
-    arg, mx = _run(cfg, hidden, w)
+def _check(cfg, hidden, w, rows=None, tiled=False):
+    arg, mx = _run(cfg, hidden, w, tiled)
     sel = np.arange(hidden.shape[0]) if rows is None else np.asarray(rows)
     ref = O.lmhead_argmax(hidden[sel], w)
     bad = [(int(r), int(arg[r]), int(ref["argmax"][i]), float(ref["margin"][i]))
@@ -47,10 +49,26 @@ def test_config1_fp32():
 
 @pytest.mark.parametrize("R,Hd,V", [(1, 64, 1), (5, 256, 300), (64, 512, 1000), (37, 1024, 129), (100, 256, 777),
                                     (128, 320, 1025), (200, 192, 500), (512, 128, 260)])
-def test_bf16_shapes(R, Hd, V):
+@pytest.mark.parametrize("tiled", [False, True])
+def test_bf16_shapes(R, Hd, V, tiled):
     cfg = W.scaled(W.CONFIGS[2], B=1, Hq=Hd // 64, Hkv=Hd // 64, D=64, V=V)
     assert cfg.hidden == Hd
-    _check(cfg, W.make_hidden(cfg, 3, rows=R), W.make_lmhead_weight(cfg, 3))
+    _check(cfg, W.make_hidden(cfg, 3, rows=R), W.make_lmhead_weight(cfg, 3), tiled=tiled)
+
+
+@pytest.mark.parametrize("V,Hd", [(1, 64), (128, 64), (129, 192), (1000, 256), (32000, 4096)])
+def test_pack_w_is_the_documented_reblocking(V, Hd):
+    """[V, Hd] -> [ceil(V/128)][Hd/64][128][64], rows past V zero: a pure index permutation, bit-exact."""
+    rng = np.random.default_rng(V)
+    w = torch.from_numpy(rng.integers(-30000, 30000, size=(V, Hd)).astype(np.int16)).to(DEV).view(torch.bfloat16)
+    packed = ob.ouro_lmhead_pack_w(w)
+    torch.cuda.synchronize()
+    got = packed.data.view(torch.int16).cpu().numpy()
+    ns = (V + 127) // 128
+    pad = np.zeros((ns * 128, Hd), np.int16)
+    pad[:V] = w.view(torch.int16).cpu().numpy()
+    want = pad.reshape(ns, 128, Hd // 64, 64).transpose(0, 2, 1, 3).reshape(-1)
+    assert got.shape == want.shape and np.array_equal(got, want)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -85,18 +103,20 @@ def test_planted_winners_bf16():
     assert np.array_equal(arg, plant)
 
 
+@pytest.mark.parametrize("tiled", [False, True])
 @pytest.mark.parametrize("cfg_id", [2, 3, 4])
-def test_full_size_configs(cfg_id):
+def test_full_size_configs(cfg_id, tiled):
     cfg = W.CONFIGS[cfg_id]
     s = W.seed_for(cfg_id)
-    _check(cfg, W.make_hidden(cfg, s), W.make_lmhead_weight(cfg, s))
+    _check(cfg, W.make_hidden(cfg, s), W.make_lmhead_weight(cfg, s), tiled=tiled)
 
 
-def test_full_size_config5_sampled_rows():
+@pytest.mark.parametrize("tiled", [False, True])
+def test_full_size_config5_sampled_rows(tiled):
     cfg = W.CONFIGS[5]
     s = W.seed_for(5)
     rows = np.random.default_rng(0).choice(cfg.R, size=96, replace=False)
-    _check(cfg, W.make_hidden(cfg, s), W.make_lmhead_weight(cfg, s), rows=np.sort(rows))
+    _check(cfg, W.make_hidden(cfg, s), W.make_lmhead_weight(cfg, s), rows=np.sort(rows), tiled=tiled)
 
 
 def test_workspace_is_reusable_across_shapes_and_calls():
