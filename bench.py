@@ -252,6 +252,38 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    # ---- extra: the same steps replayed from a HIP graph (launch gaps removed); not the headline value ----
+    graph_us = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            hs_side = side.cuda_stream
+
+            def gstep(r):
+                d_attn[r].ev_start = d_attn[r].ev_stop = d_lm[r].ev_start = d_lm[r].ev_stop = None
+                return (f_attn(C.byref(d_attn[r]), hs_side) | f_lm(C.byref(d_lm[r]), hs_side)
+                        | f_acc(C.byref(d_acc), hs_side))
+
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                st = 0
+                for r in range(nrot):
+                    st |= gstep(r)
+            if st == 0:
+                reps = max(1, args.steps // nrot)
+                graph.replay()
+                torch.cuda.synchronize()
+                g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                g0.record(side)
+                for _ in range(reps):
+                    graph.replay()
+                g1.record(side)
+                torch.cuda.synchronize()
+                graph_us = g0.elapsed_time(g1) * 1e3 / (reps * nrot)
+    except Exception as exc:      # graph capture is optional; report why it was skipped
+        graph_us = "unavailable: %s" % type(exc).__name__
+
     ms_step = elapsed * 1e3 / args.steps
     seg = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(3)] for ev in events])   # ms
     t_attn, t_lm, t_acc = (float(x) for x in seg.mean(axis=0))
@@ -285,6 +317,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step,
         "verify_step_latency_us": ms_step * 1e3,
+        "graph_replay_step_latency_us": graph_us,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": workload, "B": cfg.B, "T": cfg.T, "gamma": cfg.gamma, "K": cfg.K, "beta": cfg.beta_p,
