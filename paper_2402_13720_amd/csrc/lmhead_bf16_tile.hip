@@ -5,14 +5,17 @@
 // exceeds the machine balance, so the product is bound by the matrix cores and organised as
 // a classic LDS-tiled GEMM:
 //
-//   * workgroup tile 256 vocabulary rows x 256 hidden rows, k-tiles of 64; 8 waves in a 4x2
-//     grid, each owning 64 x 128 = 2x4 accumulator tiles of v_mfma_f32_32x32x16_bf16 (128
-//     accumulator registers per lane), so that two waves share a SIMD and one wave's LDS
-//     reads and waits hide behind the other's MFMAs; 6 operand fragments feed 8 MFMAs per
-//     16-wide k step;
-//   * global -> registers -> LDS (XOR-swizzled 128-byte rows, conflict-free fragment reads),
-//     two LDS buffers: the k-tile after next is in flight in registers while the next one is
-//     already in LDS; one barrier per k-tile;
+//   * workgroup tile 256 vocabulary rows x 256 hidden rows, k-tiles of 64; 4 waves in a 2x2 grid, one per
+//     SIMD, each owning 128 x 128 = 4x4 accumulator tiles of v_mfma_f32_32x32x16_bf16 (all 256 accumulator
+//     registers of the lane), so that 8 operand fragments feed 16 MFMAs per 16-wide k step;
+//   * with one wave per SIMD nothing else hides latency, so the loop is software-pipelined by hand and the
+//     order is pinned with scheduling barriers: the fragments of k step s+1 are read from LDS between the
+//     MFMAs of step s (two fragment register sets), and the staging work of the next k-tile (registers ->
+//     the other LDS buffer, each staging register re-armed at once with the k-tile after next from global
+//     memory) sits between the MFMAs of steps 1 and 2; one barrier per k-tile, before step 3 prefetches the
+//     first fragments of the next k-tile;
+//   * LDS tiles have 128-byte rows with XOR-swizzled 16-byte chunks (conflict-free fragment reads and
+//     staging writes);
 //   * epilogue: arg-max lane -> wave -> workgroup with the total order (larger value, then
 //     smaller id); one (value, id) pair per (vocabulary slab, row) goes to the workspace and
 //     the cross-slab kernel finishes.  The logits never reach memory.
@@ -34,10 +37,9 @@ typedef unsigned __attribute__((ext_vector_type(4))) u32x4;
 constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kTileBytes = 256 * 128;                    // one operand tile: 256 rows x 64 bf16
 constexpr int kBufBytes = 2 * kTileBytes;                // W tile + hidden tile
-constexpr int kThreads = 512;
-constexpr int kMT = 2, kNT = 4;                          // accumulator tiles per wave
-constexpr int kBestOff = 2 * kBufBytes;                  // [4 wave rows][256] (value, id)
-constexpr int kLdsBytes = kBestOff + 4 * kBN * 8;
+constexpr int kThreads = 256;
+constexpr int kMT = 4, kNT = 4;                          // accumulator tiles per wave
+constexpr int kLdsBytes = 2 * kBufBytes;                 // 128 KB; the arg-max exchange reuses buffer 0
 
 struct TileArgs {
   const __bf16* hidden;
@@ -50,15 +52,12 @@ struct TileArgs {
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
-// 16-byte slot of chunk c (0..7) of row `row` in a tile with 128-byte rows (see lmhead_bf16.hip).
-__device__ __forceinline__ int tile_slot(int row, int c) { return row * 8 + (c ^ ((row >> 1) & 7)); }
-
 __global__ __launch_bounds__(kThreads) void lmhead_bf16_tile_kernel(TileArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int col = lane & 31, half = lane >> 5;
-  const int wm = wave >> 1, wn = wave & 1;             // wave's 64 x 128 block: vocabulary rows 64*wm.., hidden rows 128*wn..
+  const int wm = wave >> 1, wn = wave & 1;             // wave's 128 x 128 block: vocabulary rows 128*wm.., hidden rows 128*wn..
 
   // workgroup id -> (slab, row tile): the row tiles of one slab sit 8 ids apart
   const int per = 8 * a.nrtile;
@@ -69,37 +68,43 @@ __global__ __launch_bounds__(kThreads) void lmhead_bf16_tile_kernel(TileArgs a) 
   const int v0 = slab * kBM, r0 = rt * kBN;
   const int R = a.R, Hd = a.Hd, V = a.V;
 
-  // staging: thread (lr = tid/8, lc = tid%8) moves chunk lc of rows 64*p + lr, p = 0..3, of both tiles
+  // ---- staging: thread (lr = tid/8, lc = tid%8) moves 16-byte chunk lc of rows 32*p + lr, p = 0..7, of both
+  // tiles.  Addresses = workgroup-uniform base + per-thread 32-bit byte offset + uniform k-tile step.
   const int lr = tid >> 3, lc = tid & 7;
-  const __bf16* wp[4];
-  const __bf16* hp[4];
+  const unsigned char* wbase;
+  const unsigned char* hbase = reinterpret_cast<const unsigned char*>(a.hidden);
+  unsigned woff[8], hoff[8];
+  unsigned wstep, w_second = 0;
+  if (a.tiled) {
+    const int n128 = (V + 127) / 128;
+    const size_t slab_bytes = static_cast<size_t>(Hd / 64) * 128 * 128;       // one 128-row slab, all k-tiles
+    wbase = reinterpret_cast<const unsigned char*>(a.w) + static_cast<size_t>(2 * slab) * slab_bytes;
+    w_second = (2 * slab + 1 < n128) ? static_cast<unsigned>(slab_bytes) : 0u;   // no second slab: duplicate, masked later
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int row = 64 * p + lr;                       // row of the 256-row tile = two 128-row tiled slabs
-    const int slab128 = min(2 * slab + (row >> 7), (V + 127) / 128 - 1);
-    wp[p] = a.tiled ? a.w + (static_cast<size_t>(slab128) * (Hd / 64) * 128 + (row & 127)) * 64 + 8 * lc
-                    : a.w + static_cast<size_t>(min(v0 + row, V - 1)) * Hd + 8 * lc;   // rows past V: duplicate, masked later
-    hp[p] = a.hidden + static_cast<size_t>(min(r0 + 64 * p + lr, R - 1)) * Hd + 8 * lc;
+    for (int p = 0; p < 8; ++p) woff[p] = (p >= 4 ? w_second : 0u) + static_cast<unsigned>(((32 * p + lr) & 127) * 128 + 16 * lc);
+    wstep = 128 * 128;
+  } else {
+    wbase = reinterpret_cast<const unsigned char*>(a.w) + static_cast<size_t>(v0) * Hd * 2;
+#pragma unroll
+    for (int p = 0; p < 8; ++p)                        // rows past V: duplicate of the last row, masked later
+      woff[p] = static_cast<unsigned>(min(32 * p + lr, V - 1 - v0)) * static_cast<unsigned>(Hd * 2) + 16 * lc;
+    wstep = kBK * 2;
   }
-  const size_t wstep = a.tiled ? 128 * 64 : kBK;
-  u32x4 wreg[4], hreg[4];
-#define OURO_TILE_GLOAD(KT)                                                                                    \
-  {                                                                                                            \
-    const size_t koff = static_cast<size_t>(KT) * kBK;                                                         \
-    _Pragma("unroll") for (int p = 0; p < 4; ++p)                                                              \
-        wreg[p] = *reinterpret_cast<const u32x4*>(wp[p] + static_cast<size_t>(KT) * wstep);                    \
-    _Pragma("unroll") for (int p = 0; p < 4; ++p) hreg[p] = *reinterpret_cast<const u32x4*>(hp[p] + koff);     \
-  }
-#define OURO_TILE_LDS_STORE(BUF)                                                                               \
-  {                                                                                                            \
-    unsigned char* wl_ = lds + (BUF) * kBufBytes;                                                              \
-    unsigned char* hl_ = wl_ + kTileBytes;                                                                     \
-    _Pragma("unroll") for (int p = 0; p < 4; ++p)                                                              \
-        *reinterpret_cast<u32x4*>(wl_ + tile_slot(64 * p + lr, lc) * 16) = wreg[p];                            \
-    _Pragma("unroll") for (int p = 0; p < 4; ++p)                                                              \
-        *reinterpret_cast<u32x4*>(hl_ + tile_slot(64 * p + lr, lc) * 16) = hreg[p];                            \
-  }
+  hbase += static_cast<size_t>(r0) * Hd * 2;
+#pragma unroll
+  for (int p = 0; p < 8; ++p) hoff[p] = static_cast<unsigned>(min(32 * p + lr, R - 1 - r0)) * static_cast<unsigned>(Hd * 2) + 16 * lc;
 
+  // LDS tiles: 128-byte rows, the 16-byte chunk index XORed with (row/2)%8 (conflict-free fragment reads
+  // and staging writes).  Writer slot of (row 32p + lr, chunk lc); reader slot of (row 32t + col, chunk 2s + half).
+  const unsigned wr0 = static_cast<unsigned>(lr * 128 + ((lc ^ ((lr >> 1) & 7)) * 16));
+  unsigned rd[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) rd[s] = static_cast<unsigned>(col * 128 + (((2 * s + half) ^ ((col >> 1) & 7)) * 16));
+  const unsigned wave_w = static_cast<unsigned>(wm * 128 * 128);
+  const unsigned wave_h = static_cast<unsigned>(kTileBytes + wn * 128 * 128);
+
+  u32x4 wreg[8], hreg[8];
+  bf16x8 fa[2][kMT], fb[2][kNT];
   f32x16 acc[kMT][kNT];
 #pragma unroll
   for (int mt = 0; mt < kMT; ++mt)
@@ -108,46 +113,78 @@ __global__ __launch_bounds__(kThreads) void lmhead_bf16_tile_kernel(TileArgs a) 
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.f;
 
+#define OURO_GLOAD_W(P, KT) wreg[P] = *reinterpret_cast<const u32x4*>(wbase + static_cast<size_t>(KT) * wstep + woff[P]);
+#define OURO_GLOAD_H(P, KT) hreg[P] = *reinterpret_cast<const u32x4*>(hbase + static_cast<size_t>(KT) * (kBK * 2) + hoff[P]);
+#define OURO_STORE_W(P, BUF) *reinterpret_cast<u32x4*>(lds + (BUF) * kBufBytes + (P) * 4096 + wr0) = wreg[P];
+#define OURO_STORE_H(P, BUF) *reinterpret_cast<u32x4*>(lds + (BUF) * kBufBytes + kTileBytes + (P) * 4096 + wr0) = hreg[P];
+// fragment Q (0..3: W rows 32Q.., 4..7: hidden rows 32(Q-4)..) of k step S from buffer BUF into register set SET
+#define OURO_FRAG(Q, S, BUF, SET)                                                                              \
+  if ((Q) < 4)                                                                                                 \
+    fa[SET][(Q) & 3] = *reinterpret_cast<const bf16x8*>(lds + (BUF) * kBufBytes + wave_w + ((Q) & 3) * 4096 + rd[S]); \
+  else                                                                                                         \
+    fb[SET][(Q) & 3] = *reinterpret_cast<const bf16x8*>(lds + (BUF) * kBufBytes + wave_h + ((Q) & 3) * 4096 + rd[S]);
+// One 16-wide k step: 16 MFMAs on register set SET; between them, the 8 fragment reads of the next k step
+// (step NS of buffer NBUF, into the other register set) and, when STAGE is 1 / 2, the W / hidden half of the
+// staging work (registers -> other LDS buffer, then the same register is re-armed with the k-tile after next).
+// The scheduling barriers pin this interleaving: one wave per SIMD, so all latency hiding is in this order.
+#define OURO_KSTEP(SET, NS, NBUF, STAGE)                                                                       \
+  _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                             \
+    acc[j >> 2][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[SET][j >> 2], fb[SET][j & 3], acc[j >> 2][j & 3], 0, 0, 0); \
+    if (j < 8) {                                                                                               \
+      const int q_ = j == 0 ? 0 : j < 5 ? j + 3 : j - 4;   /* order: W0, H0..H3, W1..W3 */                     \
+      OURO_FRAG(q_, NS, NBUF, (SET) ^ 1)                                                                       \
+    } else if ((STAGE) == 1) {                                                                                 \
+      OURO_STORE_W(j - 8, cur ^ 1)                                                                             \
+      OURO_GLOAD_W(j - 8, ktl)                                                                                 \
+    } else if ((STAGE) == 2) {                                                                                 \
+      OURO_STORE_H(j - 8, cur ^ 1)                                                                             \
+      OURO_GLOAD_H(j - 8, ktl)                                                                                 \
+    }                                                                                                          \
+    __builtin_amdgcn_sched_barrier(0);                                                                         \
+  }
+
   const int nkt = Hd / kBK;
-  OURO_TILE_GLOAD(0)
-  OURO_TILE_LDS_STORE(0)
-  if (nkt > 1) OURO_TILE_GLOAD(1)
+  // prologue: k-tile 0 -> LDS buffer 0, k-tile 1 -> registers, first fragments -> register set 0
+  // (loads in the order the loop re-arms them, so that its counted waits are exact from the first iteration)
+#pragma unroll
+  for (int p = 0; p < 8; ++p) { OURO_GLOAD_W(p, 0) }
+#pragma unroll
+  for (int p = 0; p < 8; ++p) { OURO_GLOAD_H(p, 0) }
+  {
+    const int kt1 = min(1, nkt - 1);
+#pragma unroll
+    for (int p = 0; p < 8; ++p) { OURO_STORE_W(p, 0) OURO_GLOAD_W(p, kt1) __builtin_amdgcn_sched_barrier(0); }
+#pragma unroll
+    for (int p = 0; p < 8; ++p) { OURO_STORE_H(p, 0) OURO_GLOAD_H(p, kt1) __builtin_amdgcn_sched_barrier(0); }
+  }
   __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 8; ++q) { OURO_FRAG(q, 0, 0, 0) }
 
   for (int kt = 0; kt < nkt; ++kt) {
     const int cur = kt & 1;
-    // k-tile kt+1 (in registers since the previous iteration) -> the other LDS buffer, whose readers
-    // all passed the barrier that ended the previous iteration; then put k-tile kt+2 in flight.
-    // (Spreading this staging work over the four k steps was measured slower.)
-    if (kt + 1 < nkt) OURO_TILE_LDS_STORE(cur ^ 1)
-    if (kt + 2 < nkt) OURO_TILE_GLOAD(kt + 2)
-
-    const unsigned char* wl = lds + cur * kBufBytes + (wm * 64) * 128;
-    const unsigned char* hl = lds + cur * kBufBytes + kTileBytes + (wn * 128) * 128;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      bf16x8 af[kMT], bf[kNT];
-#pragma unroll
-      for (int mt = 0; mt < kMT; ++mt)
-        af[mt] = *reinterpret_cast<const bf16x8*>(wl + tile_slot(32 * mt + col, 2 * s + half) * 16);
-#pragma unroll
-      for (int nt = 0; nt < kNT; ++nt)
-        bf[nt] = *reinterpret_cast<const bf16x8*>(hl + tile_slot(32 * nt + col, 2 * s + half) * 16);
-#pragma unroll
-      for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < kNT; ++nt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bf[nt], acc[mt][nt], 0, 0, 0);
-    }
+    const int ktl = min(kt + 2, nkt - 1);     // past the end: a harmless reload of the last k-tile
+    OURO_KSTEP(0, 1, cur, 0)
+    OURO_KSTEP(1, 2, cur, 1)
+    OURO_KSTEP(0, 3, cur, 2)
+    // every wave has read the last fragments of buffer cur^1's previous contents before the previous
+    // barrier and has now written its share of k-tile kt+1 there
     __syncthreads();
+    OURO_KSTEP(1, 0, cur ^ 1, 0)
   }
-#undef OURO_TILE_GLOAD
-#undef OURO_TILE_LDS_STORE
+#undef OURO_GLOAD_W
+#undef OURO_GLOAD_H
+#undef OURO_STORE_W
+#undef OURO_STORE_H
+#undef OURO_FRAG
+#undef OURO_KSTEP
 
   // ---- arg-max epilogue.  Lane (col, half) of wave (wm, wn) holds, for hidden row r0 + 128*wn + 32*nt + col,
-  // the logits of vocabulary rows v0 + 64*wm + 32*mt + 8*(i/4) + 4*half + i%4.
-  float* bestv = reinterpret_cast<float*>(lds + kBestOff);
-  int* besti = reinterpret_cast<int*>(lds + kBestOff + 4 * kBN * 4);
+  // the logits of vocabulary rows v0 + 128*wm + 32*mt + 8*(i/4) + 4*half + i%4.
+  __syncthreads();                                          // all fragment reads done: buffer 0 is free
+  const bool full_slab = v0 + kBM <= V;                     // workgroup-uniform: no row to mask
+  float* bestv = reinterpret_cast<float*>(lds);             // [2 wave rows][256]
+  int* besti = reinterpret_cast<int*>(lds + 2 * kBN * 4);
 #pragma unroll
   for (int nt = 0; nt < kNT; ++nt) {
     float bv = -INFINITY;
@@ -156,8 +193,8 @@ __global__ __launch_bounds__(kThreads) void lmhead_bf16_tile_kernel(TileArgs a) 
     for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int v = v0 + 64 * wm + 32 * mt + 8 * (i >> 2) + 4 * half + (i & 3);
-        const float x = v < V ? acc[mt][nt][i] : -INFINITY;
+        const int v = v0 + 128 * wm + 32 * mt + 8 * (i >> 2) + 4 * half + (i & 3);
+        const float x = (full_slab || v < V) ? acc[mt][nt][i] : -INFINITY;
         if (x > bv) { bv = x; bi = v; }                    // v ascending within the lane
       }
     const float ov = __shfl_xor(bv, 32);
@@ -173,12 +210,9 @@ __global__ __launch_bounds__(kThreads) void lmhead_bf16_tile_kernel(TileArgs a) 
     const int rl = tid;
     float bv = bestv[rl];
     int bi = besti[rl];
-#pragma unroll
-    for (int q = 1; q < 4; ++q) {                           // the four wave rows, ascending vocabulary
-      const float v2 = bestv[q * kBN + rl];
-      const int i2 = besti[q * kBN + rl];
-      if (better(v2, i2, bv, bi)) { bv = v2; bi = i2; }
-    }
+    const float v2 = bestv[kBN + rl];                       // the second wave row: larger vocabulary ids
+    const int i2 = besti[kBN + rl];
+    if (better(v2, i2, bv, bi)) { bv = v2; bi = i2; }
     a.part[static_cast<size_t>(slab) * R + r0 + rl] = make_float2(bv, __int_as_float(bi));
   }
 }
