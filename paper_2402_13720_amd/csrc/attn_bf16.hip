@@ -70,6 +70,7 @@ struct AttnArgs {
   int n_x;             // B * Hkv * nch
   int T, Hq, Hkv, G, M;
   int nrb, nch, chunk;
+  int rows_wg;         // query rows per workgroup (32 x row blocks per workgroup)
   float scale_log2;
 };
 
@@ -80,7 +81,9 @@ constexpr int kQBytes = kRows * 256;                       // Q tile shared by t
 constexpr int kStateBytes = 16 * 64 * 16;                  // O accumulators of one wave, lane-major
 constexpr int kMergeBytes = 2 * kStateBytes + 2 * 64 * 8;  // two slots + their (max, sum) pairs
 constexpr int kStageBytes = kRows * kStageRow * 4 + kRows * 8;
-constexpr int kLdsBytes = kQBytes + cmax(cmax(4 * kWaveLds, kMergeBytes), kStageBytes);   // 72 KB: two workgroups per CU
+constexpr int kPidBytes = 128 * 2;                         // phrase ids of the block keys (T <= 128)
+constexpr int kMainLds = kQBytes + cmax(cmax(4 * kWaveLds, kMergeBytes), kStageBytes);
+constexpr int kLdsBytes = kMainLds + kPidBytes;            // 72 KB: two workgroups per CU
 
 // Slot (16 bytes = 8 keys of one head-dim element d) of the transposed V tile.
 // d = 8*a + j, c = key group (0..3).  Writers (fixed j, c; a = 0..15) and readers
@@ -99,6 +102,110 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
+
+// ---- building blocks shared by the two kernels (macros rather than functions: the register arrays they
+// ---- work on must stay in registers) ---------------------------------------------------------------------
+// Names they expect in scope: a, b, g, T, L, k_end, fast_end, cu0, Hkv, kq, c16, row_base, loff0, kstride (staging);
+// col, half, tq, pidq, boffq, o, m_run, l_run (the wave's flash state); kpid (phrase ids of the block keys, in LDS).
+
+// Issue the global loads of the 32-key tile that starts at key TILE of the sequence's [cache | block] axis into
+// the staging registers (8 K loads, then 8 V loads: always, so that counted waits stay exact); a tile wholly
+// inside the cache part of the workgroup's window takes the fast path, any other has its keys clamped into the window.
+#define OURO_ATTN_ISSUE_HALF(TILE, REG, CACHE, BLK)                                                                 \
+  if ((TILE) + 32 <= fast_end) {                                                                                   \
+    const __bf16* src = (CACHE) + (static_cast<size_t>(cu0 + (TILE)) * Hkv + g) * kD;                              \
+    _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                                  \
+        REG[i] = *reinterpret_cast<const u32x4*>(src + loff0 + static_cast<unsigned>(4 * i) * kstride);            \
+  } else {                                                                                                         \
+    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
+      const int kidx = min((TILE) + 4 * i + kq, k_end - 1); /* clamp: finite data, masked or unused later */       \
+      const bool in_cache = kidx < L;                                                                              \
+      const size_t row = in_cache ? static_cast<size_t>(cu0 + kidx) : static_cast<size_t>(b) * T + (kidx - L);     \
+      REG[i] = *reinterpret_cast<const u32x4*>((in_cache ? (CACHE) : (BLK)) + (row * Hkv + g) * kD + 8 * c16);     \
+    }                                                                                                              \
+  }
+#define OURO_ATTN_ISSUE_K(TILE, KR) OURO_ATTN_ISSUE_HALF(TILE, KR, a.k_cache, a.k_blk)
+#define OURO_ATTN_ISSUE_V(TILE, VR) OURO_ATTN_ISSUE_HALF(TILE, VR, a.v_cache, a.v_blk)
+#define OURO_ATTN_ISSUE_LOADS(TILE, KR, VR) OURO_ATTN_ISSUE_K(TILE, KR) OURO_ATTN_ISSUE_V(TILE, VR)
+
+// Staging registers -> one K tile (row-major, swizzled) and one V^T tile (transposed with byte permutes;
+// head-dim elements 8*c16 + j, j = J0..J1-1: 8 keys of one element are dword j/2, low or high half, of each row).
+#define OURO_ATTN_STORE_K(KL, KR)                                                                                  \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                                    \
+      *reinterpret_cast<u32x4*>((KL) + k_slot(row_base + 8 * (i >> 2) + (i & 3), c16) * 16) = KR[i];
+#define OURO_ATTN_STORE_V(VL, VR, J0, J1)                                                                          \
+  _Pragma("unroll") for (int j = (J0); j < (J1); ++j) {                                                            \
+    const unsigned sel = (j & 1) ? 0x07060302u : 0x05040100u;                                                      \
+    u32x4 t4;                                                                                                      \
+    t4.x = __builtin_amdgcn_perm(dword_of(VR[1], j >> 1), dword_of(VR[0], j >> 1), sel);                           \
+    t4.y = __builtin_amdgcn_perm(dword_of(VR[3], j >> 1), dword_of(VR[2], j >> 1), sel);                           \
+    t4.z = __builtin_amdgcn_perm(dword_of(VR[5], j >> 1), dword_of(VR[4], j >> 1), sel);                           \
+    t4.w = __builtin_amdgcn_perm(dword_of(VR[7], j >> 1), dword_of(VR[6], j >> 1), sel);                           \
+    *reinterpret_cast<u32x4*>((VL) + vt_slot(c16, j, kq) * 16) = t4;                                               \
+  }
+#define OURO_ATTN_STORE_TILE(KL, VL, KR, VR) { OURO_ATTN_STORE_K(KL, KR) OURO_ATTN_STORE_V(VL, VR, 0, 8) }
+
+// One 32-row x 32-key step of the flash loop on the tile in (KL, VL) with the query tile in QL.
+//
+// S^T = K . Q^T; then the mask, only on tiles that touch block keys or run past n (wave-uniform branch):
+// accumulator register i of a lane (half h) is S^T row 8*(i/4) + 4*h + i%4, which holds key
+// 16*((i/4)%2) + 4*(i%4) + 2*(i/8) + h of the tile.  The rule is Eq. (8) on (phrase id, branch offset) pairs:
+// cache keys are visible to every row; a main-draft key up to the row's branch point; a phrase key only to
+// later rows of the same phrase.  The phrase ids of the block keys come from a small LDS table.
+//
+// Online softmax in the log2 domain.  The running reference m_run is only raised when a score exceeds it by
+// more than 8 (a factor 256, harmless in fp32 and for the bf16 rounding of P, which is relative); O and the
+// sum stay consistent with whatever reference is in use, so the result is unchanged, and the 64-register
+// rescale of O is skipped on almost every tile.  l_run is a per-half partial sum; halves are added at the end.
+//
+// O^T += V^T . P^T with P^T = the S^T accumulator registers rounded to bf16.
+#define OURO_ATTN_COMPUTE_TILE(TILE, KL, VL, QL)                                                                   \
+  {                                                                                                                \
+    f32x16 sacc;                                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < 16; ++i) sacc[i] = 0.f;                                                  \
+    _Pragma("unroll") for (int s = 0; s < 8; ++s) {                                                                \
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>((KL) + k_slot(col, 2 * s + half) * 16);                   \
+      const bf16x8 qf = *reinterpret_cast<const bf16x8*>((QL) + k_slot(col, 2 * s + half) * 16);                   \
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf, sacc, 0, 0, 0);                                       \
+    }                                                                                                              \
+    if ((TILE) + 32 > L) {                                                                                         \
+      _Pragma("unroll") for (int i = 0; i < 16; ++i) {                                                             \
+        const int kb = (TILE) + 16 * ((i >> 2) & 1) + 4 * (i & 3) + 2 * (i >> 3) + half - L;                       \
+        const int pidk = kpid[min(max(kb, 0), T - 1)];                                                             \
+        const bool blk_vis = pidk == 0 ? kb <= boffq : (pidk == pidq && kb <= tq);                                 \
+        sacc[i] = (kb < 0 || (kb < T && blk_vis)) ? sacc[i] : -INFINITY;                                           \
+      }                                                                                                            \
+    }                                                                                                              \
+    float tmax = sacc[0];                                                                                          \
+    _Pragma("unroll") for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sacc[i]);                                    \
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * a.scale_log2;                                                       \
+    if (__any(tmax > m_run + 8.0f)) {                                                                              \
+      const float m_new = fmaxf(m_run, tmax);                                                                      \
+      const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));                      \
+      m_run = m_new;                                                                                               \
+      l_run *= alpha;                                                                                              \
+      _Pragma("unroll") for (int dt = 0; dt < 4; ++dt)                                                             \
+          _Pragma("unroll") for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;                                        \
+    }                                                                                                              \
+    const float neg_m = m_run == -INFINITY ? 0.f : -m_run;                                                         \
+    float psum = 0.f;                                                                                              \
+    f32x8 p0, p1;                                                                                                  \
+    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
+      p0[i] = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.scale_log2, neg_m));                                          \
+      p1[i] = __builtin_amdgcn_exp2f(fmaf(sacc[8 + i], a.scale_log2, neg_m));                                      \
+      psum += p0[i] + p1[i];                                                                                       \
+    }                                                                                                              \
+    l_run += psum;                                                                                                 \
+    const bf16x8 pf0 = __builtin_convertvector(p0, bf16x8);                                                        \
+    const bf16x8 pf1 = __builtin_convertvector(p1, bf16x8);                                                        \
+    _Pragma("unroll") for (int dt = 0; dt < 4; ++dt) {                                                             \
+      const bf16x8 vf0 = *reinterpret_cast<const bf16x8*>((VL) + vt_slot(4 * dt + (col >> 3), col & 7, half) * 16);     \
+      const bf16x8 vf1 = *reinterpret_cast<const bf16x8*>((VL) + vt_slot(4 * dt + (col >> 3), col & 7, 2 + half) * 16); \
+      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0, pf0, o[dt], 0, 0, 0);                                   \
+      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf1, pf1, o[dt], 0, 0, 0);                                   \
+    }                                                                                                              \
+  }
+
 
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -122,10 +229,13 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   if (k_begin >= n) return;                       // chunk slot beyond this sequence (uniform for the workgroup)
   const int k_end = min(n, k_begin + a.chunk);
   const int nchb = (n + a.chunk - 1) / a.chunk;   // chunks this sequence really has
+  const int fast_end = min(L, k_end);             // tiles that end by here lie wholly in the cache part of the window
 
   unsigned char* ql = lds;                        // Q tile, shared
   unsigned char* kl = lds + kQBytes + wave * kWaveLds;
   unsigned char* vl = kl + kKBytes;
+  short* kpid = reinterpret_cast<short*>(lds + kMainLds);
+  for (int i = tid; i < T; i += 256) kpid[i] = a.meta[static_cast<size_t>(b) * T + i].phrase_id;
   const int col = lane & 31, half = lane >> 5;
   const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
   const int row0 = rb * kRows;
@@ -158,27 +268,6 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   // plus these, no per-row address arithmetic in the loop).
   const unsigned kstride = static_cast<unsigned>(Hkv) * kD;
   const unsigned loff0 = static_cast<unsigned>(kq) * kstride + 8 * c16;
-#define OURO_ATTN_ISSUE_LOADS(TILE)                                                                                \
-  if ((TILE) + 32 <= L) {                                                                                          \
-    const size_t base = (static_cast<size_t>(cu0 + (TILE)) * Hkv + g) * kD;                                        \
-    const __bf16* kt = a.k_cache + base;                                                                           \
-    const __bf16* vt = a.v_cache + base;                                                                           \
-    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
-      const unsigned off = loff0 + static_cast<unsigned>(4 * i) * kstride;                                         \
-      kr[i] = *reinterpret_cast<const u32x4*>(kt + off);                                                           \
-      vr[i] = *reinterpret_cast<const u32x4*>(vt + off);                                                           \
-    }                                                                                                              \
-  } else {                                                                                                         \
-    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
-      const int kidx = min((TILE) + 4 * i + kq, n - 1); /* clamp: finite data, masked later */                     \
-      const bool in_cache = kidx < L;                                                                              \
-      const size_t row = in_cache ? static_cast<size_t>(cu0 + kidx) : static_cast<size_t>(b) * T + (kidx - L);     \
-      const size_t off = (row * Hkv + g) * kD + 8 * c16;                                                           \
-      kr[i] = *reinterpret_cast<const u32x4*>((in_cache ? a.k_cache : a.k_blk) + off);                             \
-      vr[i] = *reinterpret_cast<const u32x4*>((in_cache ? a.v_cache : a.v_blk) + off);                             \
-    }                                                                                                              \
-  }
-
   f32x16 o[4];
   float m_run = -INFINITY, l_run = 0.f;
 #pragma unroll
@@ -188,97 +277,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 
   // this wave's tiles: k_begin + 32*(wave + 4*i)
   int tile = k_begin + 32 * wave;
-  if (tile < k_end) { OURO_ATTN_ISSUE_LOADS(tile) }
+  if (tile < k_end) { OURO_ATTN_ISSUE_LOADS(tile, kr, vr) }
   __syncthreads();                                // Q tile complete
   for (; tile < k_end; tile += 128) {
-    // ---- registers -> LDS ----
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      *reinterpret_cast<u32x4*>(kl + k_slot(row_base + 8 * (i >> 2) + (i & 3), c16) * 16) = kr[i];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      // 8 keys of head-dim element 8*c16 + j: dword j/2 of each row, low or high half
-      const unsigned sel = (j & 1) ? 0x07060302u : 0x05040100u;
-      u32x4 t4;
-      t4.x = __builtin_amdgcn_perm(dword_of(vr[1], j >> 1), dword_of(vr[0], j >> 1), sel);
-      t4.y = __builtin_amdgcn_perm(dword_of(vr[3], j >> 1), dword_of(vr[2], j >> 1), sel);
-      t4.z = __builtin_amdgcn_perm(dword_of(vr[5], j >> 1), dword_of(vr[4], j >> 1), sel);
-      t4.w = __builtin_amdgcn_perm(dword_of(vr[7], j >> 1), dword_of(vr[6], j >> 1), sel);
-      *reinterpret_cast<u32x4*>(vl + vt_slot(c16, j, kq) * 16) = t4;
-    }
-    if (tile + 128 < k_end) { OURO_ATTN_ISSUE_LOADS(tile + 128) }
+    OURO_ATTN_STORE_TILE(kl, vl, kr, vr)
+    if (tile + 128 < k_end) { OURO_ATTN_ISSUE_LOADS(tile + 128, kr, vr) }
     wave_lds_fence();
-
-    // ---- S^T = K . Q^T ----
-    f32x16 sacc;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kl + k_slot(col, 2 * s + half) * 16);
-      const bf16x8 qf = *reinterpret_cast<const bf16x8*>(ql + k_slot(col, 2 * s + half) * 16);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf, sacc, 0, 0, 0);
-    }
-
-    // ---- mask (only tiles that touch block keys or run past n; wave-uniform branch) ----
-    // Accumulator register i of a lane (half h) is S^T row 8*(i/4) + 4*h + i%4, which holds
-    // key 16*((i/4)%2) + 4*(i%4) + 2*(i/8) + h of the tile.
-    if (tile + 32 > L) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int kb = tile + 16 * ((i >> 2) & 1) + 4 * (i & 3) + 2 * (i >> 3) + half - L;
-        bool vis = kb < 0;
-        if (kb >= 0 && kb < T) {
-          const int pidk = a.meta[static_cast<size_t>(b) * T + kb].phrase_id;
-          vis = pidk == 0 ? kb <= boffq : (pidk == pidq && kb <= tq);
-        }
-        sacc[i] = vis ? sacc[i] : -INFINITY;
-      }
-    }
-
-    // ---- online softmax (log2 domain) ----
-    // The running reference m_run is only raised when a score exceeds it by more than 8 (a factor
-    // 256, harmless in fp32 and for the bf16 rounding of P, which is relative); O and the sum stay
-    // consistent with whatever reference is in use, so the result is unchanged, and the 64-register
-    // rescale of O is skipped on almost every tile.
-    float tmax = sacc[0];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sacc[i]);
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * a.scale_log2;
-    if (__any(tmax > m_run + 8.0f)) {
-      const float m_new = fmaxf(m_run, tmax);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;
-    }
-    const float neg_m = m_run == -INFINITY ? 0.f : -m_run;
-    float psum = 0.f;
-    f32x8 p0, p1;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      p0[i] = __builtin_amdgcn_exp2f(fmaf(sacc[i], a.scale_log2, neg_m));
-      p1[i] = __builtin_amdgcn_exp2f(fmaf(sacc[8 + i], a.scale_log2, neg_m));
-      psum += p0[i] + p1[i];
-    }
-    l_run += psum;                                  // per-half partial sum; halves are added at the end
-    const bf16x8 pf0 = __builtin_convertvector(p0, bf16x8);
-    const bf16x8 pf1 = __builtin_convertvector(p1, bf16x8);
-
-    // ---- O^T += V^T . P^T ----
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-      const bf16x8 vf0 = *reinterpret_cast<const bf16x8*>(vl + vt_slot(4 * dt + (col >> 3), col & 7, half) * 16);
-      const bf16x8 vf1 = *reinterpret_cast<const bf16x8*>(vl + vt_slot(4 * dt + (col >> 3), col & 7, 2 + half) * 16);
-      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0, pf0, o[dt], 0, 0, 0);
-      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf1, pf1, o[dt], 0, 0, 0);
-    }
+    OURO_ATTN_COMPUTE_TILE(tile, kl, vl, ql)
     wave_lds_fence();                               // reads of this tile precede the next tile's LDS writes
   }
-#undef OURO_ATTN_ISSUE_LOADS
 
   // ---- merge the 4 wave states pairwise through LDS: (2,3) -> (0,1), then 1 -> 0 ----
   unsigned char* scratch = lds + kQBytes;
@@ -371,12 +378,315 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   for (int p = tid; p < kRows * 2; p += 256) a.part_ml[pbase * 2 + p] = stage_ml[p];
 }
 
+// ---- row-split variant: more than 32 query rows per (sequence, KV head) -------------------------------------
+// With T*G > 32 rows (long drafts, grouped-query heads) the K/V window of a chunk is needed by several
+// 32-row blocks.  Here the workgroup keeps RW of them (RW = 2 or 4) and its waves share the staged tiles:
+// a stage is 128 keys = four 32-key tiles, one staged by each wave exactly as above, and wave (rw, kw) runs
+// its row block rw over the tiles kw, kw + KW, ... of the stage (KW = 4 / RW key groups).  Staging work, K/V
+// global loads and LDS writes per query row drop by RW.
+//
+// One wave per SIMD (the whole register file: Q fragments, K and V fragments, two score accumulators stay in
+// registers), so nothing but the instruction order hides latency; it is pipelined by hand and pinned with
+// scheduling barriers.  Two LDS stage buffers; while the waves compute on stage s,
+//   * the staging registers (stage s+1, loaded during stage s-1) go to the other buffer, a piece per tile slot,
+//   * each staging register is re-armed with stage s+2 as soon as it has been stored (the 64 KB of loads of a
+//     stage would otherwise block every wave for the ~1000 cycles they need to pass the address pipeline),
+// and one barrier ends the stage.  Inside a stage, per tile u:
+//
+//   staging piece | read V fragments(u) | mask, running maximum(u) | the S^T MFMAs of tile u+1 interleaved
+//                 with the exponentials of tile u | read K fragments(u+2) | P.V MFMAs(u)
+//
+// Every wave issues its 16 loads per stage whether or not its tile exists (clamped addresses), so that the
+// counted waits never drain the prefetch.  At the end the KW states of a row block are merged through LDS and
+// the workgroup writes 32*RW rows.
+#define OURO_ATTN_READ_KF(TK)                                                                                      \
+  _Pragma("unroll") for (int s = 0; s < 8; ++s)                                                                    \
+      kf[s] = *reinterpret_cast<const bf16x8*>((TK) + k_slot(col, 2 * s + half) * 16);
+#define OURO_ATTN_READ_VF(TV)                                                                                      \
+  _Pragma("unroll") for (int dt = 0; dt < 4; ++dt) {                                                               \
+    vf[2 * dt] = *reinterpret_cast<const bf16x8*>((TV) + vt_slot(4 * dt + (col >> 3), col & 7, half) * 16);        \
+    vf[2 * dt + 1] = *reinterpret_cast<const bf16x8*>((TV) + vt_slot(4 * dt + (col >> 3), col & 7, 2 + half) * 16); \
+  }
+#define OURO_ATTN_QK(S)                                                                                            \
+  {                                                                                                                \
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};        \
+    S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[0], zero16, 0, 0, 0);                                    \
+    _Pragma("unroll") for (int s = 1; s < 8; ++s) S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], S, 0, 0, 0); \
+  }
+// mask + running-maximum update for the scores S of the tile at key TILE (see OURO_ATTN_COMPUTE_TILE) ...
+#define OURO_ATTN_SOFTMAX_MAX(TILE, S)                                                                             \
+  {                                                                                                                \
+    if ((TILE) + 32 > L) {                                                                                         \
+      _Pragma("unroll") for (int i = 0; i < 16; ++i) {                                                             \
+        const int kb = (TILE) + 16 * ((i >> 2) & 1) + 4 * (i & 3) + 2 * (i >> 3) + half - L;                       \
+        const int pidk = kpid[min(max(kb, 0), T - 1)];                                                             \
+        const bool blk_vis = pidk == 0 ? kb <= boffq : (pidk == pidq && kb <= tq);                                 \
+        S[i] = (kb < 0 || (kb < T && blk_vis)) ? S[i] : -INFINITY;                                                 \
+      }                                                                                                            \
+    }                                                                                                              \
+    float tmax = S[0];                                                                                             \
+    _Pragma("unroll") for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, S[i]);                                       \
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * a.scale_log2;                                                       \
+    if (__any(tmax > m_run + 8.0f)) {                                                                              \
+      const float m_new = fmaxf(m_run, tmax);                                                                      \
+      const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));                      \
+      m_run = m_new;                                                                                               \
+      l_run *= alpha;                                                                                              \
+      _Pragma("unroll") for (int dt = 0; dt < 4; ++dt)                                                             \
+          _Pragma("unroll") for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;                                        \
+    }                                                                                                              \
+  }
+// ... and the exponentials: leaves P^T (bf16) in pf0, pf1 and adds the row sums to l_run
+#define OURO_ATTN_SOFTMAX_EXP(S)                                                                                   \
+  {                                                                                                                \
+    const float neg_m = m_run == -INFINITY ? 0.f : -m_run;                                                         \
+    float psum = 0.f;                                                                                              \
+    f32x8 p0, p1;                                                                                                  \
+    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
+      p0[i] = __builtin_amdgcn_exp2f(fmaf(S[i], a.scale_log2, neg_m));                                             \
+      p1[i] = __builtin_amdgcn_exp2f(fmaf(S[8 + i], a.scale_log2, neg_m));                                         \
+      psum += p0[i] + p1[i];                                                                                       \
+    }                                                                                                              \
+    l_run += psum;                                                                                                 \
+    pf0 = __builtin_convertvector(p0, bf16x8);                                                                     \
+    pf1 = __builtin_convertvector(p1, bf16x8);                                                                     \
+  }
+#define OURO_ATTN_PV()                                                                                             \
+  _Pragma("unroll") for (int dt = 0; dt < 4; ++dt) {                                                               \
+    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[2 * dt], pf0, o[dt], 0, 0, 0);                              \
+    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[2 * dt + 1], pf1, o[dt], 0, 0, 0);                          \
+  }
+
+template <int RW>
+constexpr int rows_main_lds() {
+  // two stage buffers; the merge slots and the staged output reuse the same memory from its start
+  return cmax(2 * 4 * kWaveLds, cmax((4 / RW / 2) * RW * (kStateBytes + 64 * 8), 32 * RW * kStageRow * 4 + 32 * RW * 8));
+}
+template <int RW>
+constexpr int rows_lds_bytes() { return rows_main_lds<RW>() + kPidBytes; }
+
+template <int RW>
+__global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
+  constexpr int KW = 4 / RW;                      // key groups
+  constexpr int NT = 4 / KW;                      // tiles of a stage per wave
+  constexpr int kRowsWg = 32 * RW;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int rw = wave % RW, kw = wave / RW;
+
+  // ---- workgroup id -> (x = (sequence, KV head, chunk), row block); same x => same id modulo 8 ----
+  const int per = 8 * a.nrb;
+  const int blk = blockIdx.x / per, rem = blockIdx.x - blk * per;
+  const int rb = rem >> 3;
+  const int x = blk * 8 + (rem & 7);
+  if (x >= a.n_x) return;
+  const int chunk = x % a.nch;
+  const int bg = x / a.nch;
+  const int b = bg / a.Hkv, g = bg - b * a.Hkv;
+  const long cu0 = a.cu[b];
+  const int L = static_cast<int>(a.cu[b + 1] - cu0);
+  const int T = a.T;
+  const int n = L + T;
+  const int k_begin = chunk * a.chunk;
+  if (k_begin >= n) return;                       // chunk slot beyond this sequence (uniform for the workgroup)
+  const int k_end = min(n, k_begin + a.chunk);
+  const int nchb = (n + a.chunk - 1) / a.chunk;   // chunks this sequence really has
+  const int fast_end = min(L, k_end);             // tiles that end by here lie wholly in the cache part of the window
+
+  constexpr int kStageBytes4 = 4 * kWaveLds;      // one stage: 4 x (K tile, V^T tile)
+  short* kpid = reinterpret_cast<short*>(lds + rows_main_lds<RW>());
+  for (int i = tid; i < T; i += 256) kpid[i] = a.meta[static_cast<size_t>(b) * T + i].phrase_id;
+  const int col = lane & 31, half = lane >> 5;
+  const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
+  const int row0 = rb * kRowsWg + 32 * rw;        // first row of this wave's block (may lie past M: duplicates)
+
+  // ---- this lane's query row (its column of S^T): metadata, and its Q fragments straight into registers ----
+  const int rq = min(row0 + col, M - 1);          // rows past M are computed on a duplicate and never stored
+  const int tq = rq / G;
+  const ouro_tok_meta mq = a.meta[static_cast<size_t>(b) * T + tq];
+  const int pidq = mq.phrase_id, boffq = mq.branch_off;
+  bf16x8 qf[8], kf[8], vf[8], pf0, pf1;
+  {
+    const __bf16* qp = a.q + ((static_cast<size_t>(b) * T + tq) * Hq + g * G + (rq - tq * G)) * kD + 8 * half;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+  }
+
+  const int kq = lane >> 4, c16 = lane & 15;      // staging roles, as in the kernel above
+  const int row_base = 16 * (kq >> 1) + 4 * (kq & 1);
+  u32x4 kr[8], vr[8];
+  const unsigned kstride = static_cast<unsigned>(Hkv) * kD;
+  const unsigned loff0 = static_cast<unsigned>(kq) * kstride + 8 * c16;
+
+  f32x16 o[4], sacc[2];
+  float m_run = -INFINITY, l_run = 0.f;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+
+  // staging piece PH (0..3) of a stage: registers -> this wave's tile in the buffer at NB, re-armed with tile NEXT
+#define OURO_ATTN_STAGING(PH, NB, NEXT)                                                                            \
+  {                                                                                                                \
+    unsigned char* nk_ = (NB) + wave * kWaveLds;                                                                   \
+    if ((PH) == 0) { OURO_ATTN_STORE_K(nk_, kr) OURO_ATTN_ISSUE_K(NEXT, kr) }                                      \
+    if ((PH) == 1) { OURO_ATTN_STORE_V(nk_ + kKBytes, vr, 0, 4) }                                                  \
+    if ((PH) == 2) { OURO_ATTN_STORE_V(nk_ + kKBytes, vr, 4, 8) OURO_ATTN_ISSUE_V(NEXT, vr) }                      \
+  }
+
+  // prologue: stage 0 -> buffer 0, stage 1 in flight
+  OURO_ATTN_ISSUE_LOADS(k_begin + 32 * wave, kr, vr)
+  {
+    unsigned char* kl = lds + wave * kWaveLds;
+    OURO_ATTN_STORE_K(kl, kr)
+    OURO_ATTN_ISSUE_K(k_begin + 128 + 32 * wave, kr)
+    OURO_ATTN_STORE_V(kl + kKBytes, vr, 0, 8)
+    OURO_ATTN_ISSUE_V(k_begin + 128 + 32 * wave, vr)
+  }
+  __syncthreads();
+
+  int cur = 0;
+  for (int sb = k_begin; sb < k_end; sb += 128, cur ^= 1) {
+    const unsigned char* kv = lds + cur * kStageBytes4;         // the stage being computed
+    unsigned char* nb = lds + (cur ^ 1) * kStageBytes4;         // the stage being filled
+    const int next = sb + 256 + 32 * wave;                      // the tile this wave's registers are re-armed with
+    const int t0 = sb + 32 * kw;                  // this wave's tiles of the stage: t0 + 32*KW*u, u = 0..NT-1
+    if (t0 < k_end) {
+      OURO_ATTN_READ_KF(kv + kw * kWaveLds)
+      OURO_ATTN_QK(sacc[0])
+      if (NT > 1 && t0 + 32 * KW < k_end) { OURO_ATTN_READ_KF(kv + (kw + KW) * kWaveLds) }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      const int tile = t0 + 32 * KW * u;
+#pragma unroll
+      for (int ph = u * (4 / NT); ph < (u + 1) * (4 / NT); ++ph) { OURO_ATTN_STAGING(ph, nb, next) }
+      __builtin_amdgcn_sched_barrier(0);
+      if (tile < k_end) {
+        OURO_ATTN_READ_VF(kv + (kw + KW * u) * kWaveLds + kKBytes)
+        OURO_ATTN_SOFTMAX_MAX(tile, sacc[u & 1])
+        __builtin_amdgcn_sched_barrier(0);
+        // The S^T MFMAs of the next tile form a dependent chain; the exponentials of this tile are issued
+        // between them (one MFMA, then a group of vector-ALU instructions), or the wave would sit through the
+        // chain.  (Past the end of the chunk the fragments are stale and the scores unused.)
+        if (u + 1 < NT) { OURO_ATTN_QK(sacc[(u + 1) & 1]) }
+        OURO_ATTN_SOFTMAX_EXP(sacc[u & 1])
+        if (u + 1 < NT) {
+#pragma unroll
+          for (int r = 0; r < 8; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);   // eight VALU
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (u + 2 < NT) { OURO_ATTN_READ_KF(kv + (kw + KW * (u + 2)) * kWaveLds) }
+        OURO_ATTN_PV()
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    __syncthreads();                              // stage sb fully read, stage sb+128 fully written
+  }
+#undef OURO_ATTN_STAGING
+
+  // ---- merge the KW states of every row block through LDS ----
+  unsigned char* scratch = lds;
+  f32x4* slot_o = reinterpret_cast<f32x4*>(scratch);
+  float* slot_ml = reinterpret_cast<float*>(scratch + (KW / 2) * RW * kStateBytes);
+#pragma unroll
+  for (int sft = KW / 2; sft >= 1; sft >>= 1) {
+    if (kw >= sft && kw < 2 * sft) {
+      const int slot = (kw - sft) * RW + rw;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int ig = 0; ig < 4; ++ig) {
+          f32x4 v4 = {o[dt][4 * ig + 0], o[dt][4 * ig + 1], o[dt][4 * ig + 2], o[dt][4 * ig + 3]};
+          slot_o[(slot * 16 + dt * 4 + ig) * 64 + lane] = v4;
+        }
+      slot_ml[(slot * 64 + lane) * 2 + 0] = m_run;
+      slot_ml[(slot * 64 + lane) * 2 + 1] = l_run;
+    }
+    __syncthreads();
+    if (kw < sft) {
+      const int slot = kw * RW + rw;
+      const float m_b = slot_ml[(slot * 64 + lane) * 2 + 0];
+      const float l_b = slot_ml[(slot * 64 + lane) * 2 + 1];
+      const float m_new = fmaxf(m_run, m_b);
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      const float fa = exp2f(m_run - m_safe), fb = exp2f(m_b - m_safe);
+      m_run = m_new;
+      l_run = l_run * fa + l_b * fb;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int ig = 0; ig < 4; ++ig) {
+          const f32x4 ob = slot_o[(slot * 16 + dt * 4 + ig) * 64 + lane];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[dt][4 * ig + e] = o[dt][4 * ig + e] * fa + ob[e] * fb;
+        }
+    }
+    __syncthreads();
+  }
+
+  // ---- the kw = 0 wave of every row block stages its state row-major: stage_o[row][132], stage_ml[row][2] ----
+  float* stage_o = reinterpret_cast<float*>(scratch);
+  float* stage_ml = stage_o + kRowsWg * kStageRow;
+  if (kw == 0) {
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const int lrow = 32 * rw + col;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int ig = 0; ig < 4; ++ig) {
+        f32x4 v4 = {o[dt][4 * ig + 0], o[dt][4 * ig + 1], o[dt][4 * ig + 2], o[dt][4 * ig + 3]};
+        *reinterpret_cast<f32x4*>(stage_o + lrow * kStageRow + 32 * dt + 8 * ig + 4 * half) = v4;
+      }
+    if (half == 0) {
+      stage_ml[lrow * 2 + 0] = m_run;
+      stage_ml[lrow * 2 + 1] = l_tot;
+    }
+  }
+  __syncthreads();
+
+  const int group = bg * a.nrb + rb;
+  if (nchb == 1) {
+    // ---- the workgroup saw every key of the sequence: normalise and write bf16, 16 B per thread ----
+    for (int p = tid; p < kRowsWg * 16; p += 256) {
+      const int row = p >> 4, c = p & 15;
+      const int r = rb * kRowsWg + row;
+      if (r >= M) continue;
+      const float inv = 1.0f / stage_ml[row * 2 + 1];
+      const f32x4 x0 = *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 8 * c);
+      const f32x4 x1 = *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 8 * c + 4);
+      f32x8 v8 = {x0[0] * inv, x0[1] * inv, x0[2] * inv, x0[3] * inv, x1[0] * inv, x1[1] * inv, x1[2] * inv, x1[3] * inv};
+      const int t = r / G, hh = r - t * G;
+      __bf16* op = a.out + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
+      *reinterpret_cast<bf16x8*>(op + 8 * c) = __builtin_convertvector(v8, bf16x8);
+      if (a.lse && c == 0)
+        a.lse[(static_cast<size_t>(b) * Hq + g * G + hh) * T + t] =
+            (stage_ml[row * 2] + log2f(stage_ml[row * 2 + 1])) * kLn2;
+    }
+    return;
+  }
+
+  // ---- several chunks: leave a partial for the combine kernel (plain coalesced stores, no waiting) ----
+  const size_t pbase = (static_cast<size_t>(group) * a.nch + chunk) * kRowsWg;
+  for (int p = tid; p < kRowsWg * 32; p += 256) {
+    const int row = p >> 5, c = p & 31;
+    *reinterpret_cast<f32x4*>(a.part_o + (pbase + row) * kD + 4 * c) =
+        *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 4 * c);
+  }
+  for (int p = tid; p < kRowsWg * 2; p += 256) a.part_ml[pbase * 2 + p] = stage_ml[p];
+}
+
 // Merge the chunk partials of every query row of the sequences that span several chunks:
 // out = sum_c 2^(m_c - m*) O_c / sum_c 2^(m_c - m*) l_c, chunks folded in ascending order
 // (deterministic).  One thread per (row, 8 head-dim elements); loads are issued four chunks
 // at a time so that their latencies overlap.
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
-  constexpr int rows_wg = kRows;
+  const int rows_wg = a.rows_wg;
   const long p = static_cast<long>(blockIdx.x) * 256 + threadIdx.x;
   const int c = static_cast<int>(p & 15);
   const long rowg = p >> 4;
@@ -455,21 +765,33 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
   a.chunk = plan.chunk;
   a.n_x = d.B * d.Hkv * plan.nch;
   a.scale_log2 = scale * 1.4426950408889634f;
+  a.rows_wg = plan.rows_wg;
   const unsigned grid = static_cast<unsigned>((a.n_x + 7) / 8) * 8u * plan.nrb;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_rows_kernel<2>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds_bytes<2>());
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_rows_kernel<4>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds_bytes<4>());
     if (e != hipSuccess) return hip_failed(e);
     attr_set = true;
   }
   if (d.ev_start && hipEventRecord(static_cast<hipEvent_t>(d.ev_start), stream) != hipSuccess) return hip_failed(hipGetLastError());
-  hipLaunchKernelGGL(attn_bf16_kernel, dim3(grid), dim3(256), kLdsBytes, stream, a);
+  if (plan.rw == 4)
+    hipLaunchKernelGGL(attn_bf16_rows_kernel<4>, dim3(grid), dim3(256), rows_lds_bytes<4>(), stream, a);
+  else if (plan.rw == 2)
+    hipLaunchKernelGGL(attn_bf16_rows_kernel<2>, dim3(grid), dim3(256), rows_lds_bytes<2>(), stream, a);
+  else
+    hipLaunchKernelGGL(attn_bf16_kernel, dim3(grid), dim3(256), kLdsBytes, stream, a);
   int st = check_launch();
   if (st == OURO_OK && d.ev_stop && hipEventRecord(static_cast<hipEvent_t>(d.ev_stop), stream) != hipSuccess)
     return hip_failed(hipGetLastError());
   if (st != OURO_OK || plan.nch == 1) return st;
-  const long threads = static_cast<long>(d.B) * d.Hkv * plan.nrb * kRows * 16;
+  const long threads = static_cast<long>(d.B) * d.Hkv * plan.nrb * plan.rows_wg * 16;
   hipLaunchKernelGGL(attn_combine_kernel, dim3(static_cast<unsigned>((threads + 255) / 256)), dim3(256), 0, stream, a);
   return check_launch();
 }

@@ -24,22 +24,37 @@ static long env_long(const char* name, long dflt) {
 // KV head) for its query rows and, when the sequence spans several chunks, leaves one fp32
 // partial.  Small chunks fill the 256 compute units; large chunks keep the partial traffic
 // (rows * 512 bytes per workgroup) small against the K/V bytes of a chunk (chunk * 512 bytes).
-// The default aims at about 1.5 workgroups per compute unit (two are resident at a time; measured
-// best on the 7B/13B/70B-shaped workloads, where per-workgroup prologue/epilogue latency dominates).  OURO_ATTN_CHUNK (keys)
-// overrides the heuristic for tuning runs.
+//
+// Up to 64 query rows per (sequence, KV head): one 32-row block per workgroup, the four waves split the
+// keys; the default aims at about 1.5 workgroups per compute unit (two are resident at a time; measured
+// best where per-workgroup prologue/epilogue latency dominates).  More rows (long drafts, grouped-query
+// heads): the workgroup keeps 4 row blocks and its waves share the staged tiles; one workgroup per compute
+// unit, and the chunk count is the largest that still lets every workgroup be resident at once (no second
+// round of workgroups).  OURO_ATTN_CHUNK (keys) and OURO_ATTN_RW (1, 2, 4) override the heuristic for
+// tuning runs.
 AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
   AttnPlan p{};
   const int G = d.Hq / d.Hkv;
   const int M = d.T * G;
-  p.qt = 1;
-  p.rows_wg = 32 * p.qt;
+  p.rw = M <= 64 ? 1 : 4;                            // (2 is built as well; measured no faster than 1 at 64 rows)
+  const long rw_env = env_long("OURO_ATTN_RW", 0);
+  if (rw_env == 1 || rw_env == 2 || rw_env == 4) p.rw = static_cast<int>(rw_env);
+  p.rows_wg = 32 * p.rw;
   p.nrb = (M + p.rows_wg - 1) / p.rows_wg;
   const long maxn = static_cast<long>(d.max_seqlen) + d.T;
   const long tiles = (maxn + 31) / 32;
   const long groups = std::max<long>(1, static_cast<long>(d.B) * d.Hkv * p.nrb);
-  long want = (384 + groups - 1) / groups;           // chunk slots per sequence
-  want = std::max<long>(1, std::min(want, (tiles + 3) / 4));
-  long tiles_per_chunk = ((tiles + want - 1) / want + 3) / 4 * 4;
+  long tiles_per_chunk;
+  if (p.rw == 1) {
+    long want = (384 + groups - 1) / groups;           // chunk slots per sequence
+    want = std::max<long>(1, std::min(want, (tiles + 3) / 4));
+    tiles_per_chunk = ((tiles + want - 1) / want + 3) / 4 * 4;
+  } else {
+    const long resident = 256;                         // workgroups the chip holds at once (one per compute unit)
+    const long stages = (tiles + 3) / 4;
+    const long want = std::max<long>(1, std::min(resident / groups, stages));
+    tiles_per_chunk = (stages + want - 1) / want * 4;
+  }
   const long chunk_env = env_long("OURO_ATTN_CHUNK", 0);
   if (chunk_env >= 128) tiles_per_chunk = chunk_env / 128 * 4;
   p.chunk = static_cast<int>(tiles_per_chunk * 32);

@@ -22,10 +22,10 @@ inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ---- attention ------------------------------------------------------------------------
 // Launch plan of the bf16 split-KV kernel, derived on the host from shapes only.
 struct AttnPlan {
-  int qt;          // 32-row query tiles per wave (1 or 2)
-  int rows_wg;     // query rows per workgroup: 32 * qt
+  int rw;          // 32-row query blocks per workgroup: 1 (waves split the keys), 2 or 4 (waves split the rows)
+  int rows_wg;     // query rows per workgroup: 32 * rw
   int nrb;         // row blocks per (sequence, KV head): ceil(T * G / rows_wg)
-  int chunk;       // keys per workgroup (multiple of 128: the 4 waves take 32-key tiles round-robin)
+  int chunk;       // keys per workgroup (multiple of 128: four 32-key tiles, one per wave, at a time)
   int nch;         // chunk slots per sequence: ceil((max_seqlen + T) / chunk)
   size_t part_ml_bytes;  // fp32 (max, sum) pairs
   size_t part_o_bytes;   // fp32 partial outputs

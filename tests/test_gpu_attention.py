@@ -65,6 +65,25 @@ def test_bf16_small_shapes(kw, branch):
     _check(cfg, W.make_attention_inputs(cfg, 1234, branch=branch))
 
 
+@pytest.mark.parametrize("rw", [1, 2, 4])
+@pytest.mark.parametrize("kw, chunk", [
+    (dict(B=2, Hq=4, Hkv=2, L=(0, 300), gamma=10, K=5, beta_p=6), 0),         # 80 rows; one sequence is all block
+    (dict(B=1, Hq=8, Hkv=1, L=517, gamma=16, K=8, beta_p=6), 128),            # GQA 8: 512 rows; 5 one-stage chunks
+    (dict(B=1, Hq=2, Hkv=2, L=1000, gamma=32, K=16, beta_p=6), 384),          # T = 128; 3 stages per chunk, ragged
+    (dict(B=4, Hq=2, Hkv=1, L=(30, 2000), gamma=8, K=4, beta_p=6), 512),      # uneven lengths, empty chunk slots
+    (dict(B=1, Hq=1, Hkv=1, L=95, gamma=1, K=0, beta_p=0), 0),                # a single row
+])
+def test_bf16_every_kernel_variant(monkeypatch, kw, chunk, rw):
+    """The launch heuristic picks the row blocks per workgroup (1: waves split the keys; 2, 4: waves split the
+    rows and share staged tiles) and the chunk length; force each combination so that all three kernels see
+    several stages, several chunks and a ragged tail."""
+    monkeypatch.setenv("OURO_ATTN_RW", str(rw))
+    if chunk:
+        monkeypatch.setenv("OURO_ATTN_CHUNK", str(chunk))
+    cfg = W.scaled(W.CONFIGS[2], **kw)
+    _check(cfg, W.make_attention_inputs(cfg, 4321))
+
+
 def test_bf16_phrase_hanging_off_the_prefix():
     cfg = W.scaled(W.CONFIGS[2], B=1, Hq=2, Hkv=2, L=70, gamma=4, K=3, beta_p=5)
     inp = W.make_attention_inputs(cfg, 5)
