@@ -16,8 +16,10 @@ lengthened draft (Sec. 3.2: the masked pass replaces verifying them one by one),
 probe/closed-form cases; attention against a library SDPA on textbook cases and
 the log-sum-exp split identity; LM head against planted winners and ties;
 acceptance against hand-worked traces (tests/golden), exhaustive path
-enumeration, and the lossless replay property of Eq. (4).  No function here is
-"parity unpinned".
+enumeration, and the lossless replay property of Eq. (4); the commit of accepted
+tokens against a hand-worked example (tests/golden), a concatenation written
+with library routines, and the property that a committed cache gives the next
+step the context of the accepted draft.  No function here is "parity unpinned".
 
 Conventions (readings of points the paper leaves open):
   * Block token t carries (pid[t], boff[t]).  pid 0 = main draft, main token i
@@ -118,11 +120,14 @@ def verify_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
                      cu_seqlens: np.ndarray, k_blk: np.ndarray, v_blk: np.ndarray,
                      pid: np.ndarray, boff: np.ndarray,
                      scale: Optional[float] = None,
-                     heads: Optional[list] = None) -> Dict[str, np.ndarray]:
+                     heads: Optional[list] = None,
+                     seq_len: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
     """Attention of every block row over [its sequence's cache | visible block tokens].
 
     q [B,T,Hq,D]; k_cache/v_cache [sum L_b, Hkv, D] with sequence b at rows
     cu_seqlens[b]:cu_seqlens[b+1]; k_blk/v_blk [B,T,Hkv,D]; pid/boff [B,T].
+    With ``seq_len`` [B] only the first seq_len[b] rows of sequence b's region are
+    cached tokens (the rest of the region is room for tokens accepted later).
     Query head h reads key/value head h // (Hq // Hkv) (consecutive query heads
     share a KV head).  scale defaults to 1/sqrt(D).  ``heads`` optionally limits
     the computation to a list of (b, h) pairs (others are left NaN) so that large
@@ -140,6 +145,8 @@ def verify_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray,
     masks = {}
     for (b, h) in todo:
         lo, hi = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        if seq_len is not None:
+            hi = lo + int(seq_len[b])
         if b not in masks:
             masks[b] = dense_mask(pid[b], boff[b], hi - lo)
         g = h // group
@@ -273,6 +280,43 @@ def accept(tok: np.ndarray, argmax: np.ndarray, pid: np.ndarray, boff: np.ndarra
 # --------------------------------------------------------------------------- #
 # The whole verification step, chained
 # --------------------------------------------------------------------------- #
+# --------------------------------------------------------------------------- #
+# Keeping the accepted tokens (the sentence after Eq. (3): d_1..A are accepted and
+# the rest of the draft is discarded; after Eq. (9): d_1..gamma, p^j_2..Ahat^j)
+# --------------------------------------------------------------------------- #
+def kv_commit(k_cache: np.ndarray, v_cache: np.ndarray, cu_seqlens: np.ndarray, seq_len: np.ndarray,
+              k_blk: np.ndarray, v_blk: np.ndarray, accept_idx: np.ndarray,
+              n_accept: np.ndarray) -> Dict[str, np.ndarray]:
+    """Append the keys/values of the accepted block tokens to each sequence's cache.
+
+    Sequence b owns rows cu_seqlens[b]:cu_seqlens[b+1] of k_cache/v_cache
+    [rows, Hkv, D]; the first seq_len[b] of them are its cached tokens.  The
+    accepted block tokens accept_idx[b, 0:n_accept[b]] (block indices, in the order
+    of the accepted draft) become cached tokens seq_len[b], seq_len[b]+1, ...; all
+    other block tokens are dropped.  A sequence whose region cannot take its
+    accepted tokens is left untouched and flagged.
+    Returns new k_cache, v_cache, seq_len and overflow [B] (0/1); inputs are not modified.
+    """
+    k_new, v_new = k_cache.copy(), v_cache.copy()
+    len_new = np.array(seq_len, dtype=np.int64).copy()
+    B = k_blk.shape[0]
+    overflow = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        start = int(cu_seqlens[b])
+        room = int(cu_seqlens[b + 1]) - start
+        have = int(seq_len[b])
+        na = int(n_accept[b])
+        if have + na > room:
+            overflow[b] = 1
+            continue
+        for i in range(na):
+            t = int(accept_idx[b, i])
+            k_new[start + have + i] = k_blk[b, t]
+            v_new[start + have + i] = v_blk[b, t]
+        len_new[b] = have + na
+    return {"k_cache": k_new, "v_cache": v_new, "seq_len": len_new, "overflow": overflow}
+
+
 def verify_step(inp: Dict[str, np.ndarray], w: np.ndarray, tok: np.ndarray,
                 root_pred: Optional[np.ndarray], gamma: int, K: int, beta_p: int,
                 hidden_round=None) -> Dict[str, np.ndarray]:

@@ -63,3 +63,18 @@ def meta_from_layout(gamma, K, beta_p, branch):
         pid[lo:lo + beta_p] = j
         boff[lo:lo + beta_p] = branch[j - 1]
     return pid, boff
+
+
+def load_commit_examples(name):
+    """Paragraphs of kv_commit_example.txt as dicts of int arrays."""
+    out, cur = [], {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for ln in list(_clean(f)) + [""]:
+            if not ln.strip():
+                if cur:
+                    out.append(cur)
+                    cur = {}
+                continue
+            k, v = ln.split(":", 1)
+            cur[k.strip()] = np.array([int(x) for x in v.split()], dtype=np.int64)
+    return out
