@@ -12,6 +12,8 @@
  *   ouro_verify_attn     masked draft-block attention against the KV cache
  *   ouro_lmhead_argmax   LM-head product fused with the arg-max over the vocabulary
  *   ouro_accept          accepted-prefix decision over main draft + phrases
+ * and the step that closes the loop:
+ *   ouro_kv_commit       keeps the keys/values of the accepted tokens in the cache
  *
  * General contract
  *   - Every data pointer in a descriptor is DEVICE memory owned by the caller and
@@ -38,7 +40,7 @@
 extern "C" {
 #endif
 
-#define OURO_VERSION 100 /* major*10000 + minor*100 + patch */
+#define OURO_VERSION 200 /* major*10000 + minor*100 + patch */
 
 /* Exported from libouro.so (everything else in the library has hidden visibility). */
 #define OURO_API __attribute__((visibility("default")))
@@ -97,9 +99,10 @@ typedef struct {
   int32_t D;                   /* head dim: 128 (bf16) ; 64 or 128 (f32) */
   int32_t max_seqlen;          /* host-side upper bound on every L_b (sizes the launch; no device read-back) */
   const void* q;               /* [B, T, Hq, D] */
-  const void* k_cache;         /* [sum_b L_b, Hkv, D], sequence b at rows cu_seqlens[b] .. cu_seqlens[b+1]-1 */
+  const void* k_cache;         /* [rows, Hkv, D], sequence b in the region of rows cu_seqlens[b] .. cu_seqlens[b+1]-1 */
   const void* v_cache;         /* same layout; may be NULL only if max_seqlen == 0 */
-  const int64_t* cu_seqlens;   /* [B+1], cu[0] = 0, non-decreasing; 0 <= L_b <= max_seqlen */
+  const int64_t* cu_seqlens;   /* [B+1], cu[0] = 0, non-decreasing region offsets.  Without seq_len the regions are
+                                  packed: L_b = cu[b+1] - cu[b].  0 <= L_b <= max_seqlen */
   const void* k_blk;           /* [B, T, Hkv, D] keys of the block tokens (not yet in the cache) */
   const void* v_blk;           /* [B, T, Hkv, D] */
   const ouro_tok_meta* meta;   /* [B, T] */
@@ -110,6 +113,8 @@ typedef struct {
   size_t workspace_bytes;
   void* ev_start;              /* optional hipEvent_t pair (NULL to skip), recorded on the stream right before and */
   void* ev_stop;               /* right after the call's main kernel, so that a profiler can time that kernel alone */
+  const int32_t* seq_len;      /* optional [B]: L_b, the cached tokens at the start of region b; the rest of the region
+                                  is room for tokens accepted later (ouro_kv_commit).  NULL: packed regions */
 } ouro_attn_desc;
 
 /* Host-only: bytes of workspace the call will need for this descriptor (data pointers are
@@ -190,6 +195,41 @@ typedef struct {
 } ouro_accept_desc;
 
 OURO_API int ouro_accept(const ouro_accept_desc* desc, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------ */
+/* Keeping the accepted tokens (the sentence after Eq. (3): d_1..A are accepted, the rest  */
+/* of the draft is discarded; after Eq. (9): d_1..gamma and p^j_2..Ahat^j are accepted).   */
+/*                                                                                       */
+/* For every sequence b the keys/values of the accepted block tokens                      */
+/* accept_idx[b, 0 .. n_accept[b]-1] (block indices in accepted order, as written by        */
+/* ouro_accept) are copied from k_blk/v_blk to the cache rows                              */
+/* cu_seqlens[b] + seq_len[b] + i, and seq_len[b] grows by n_accept[b]; the other block      */
+/* tokens are dropped.  The cache is the layout ouro_verify_attn reads with its seq_len      */
+/* field: region offsets in cu_seqlens, cached tokens at the start of each region.  A        */
+/* sequence whose region cannot take its accepted tokens is left untouched (rows and         */
+/* length) and overflow[b] is set to 1, else to 0.  Copies are bit-exact.  The work is       */
+/* enqueued as two small kernels (copy, then lengths), so seq_len is updated in place.       */
+/* ------------------------------------------------------------------------------------ */
+typedef struct {
+  uint32_t struct_size;        /* sizeof(ouro_kv_commit_desc) */
+  int32_t dtype;               /* ouro_dtype of the caches and of k_blk, v_blk */
+  int32_t B;                   /* sequences, >= 0 */
+  int32_t T;                   /* block tokens per sequence, 1..128 */
+  int32_t Hkv;                 /* key/value heads */
+  int32_t D;                   /* head dim; Hkv * D * element size must be a multiple of 16 bytes */
+  int32_t max_accept;          /* row length of accept_idx (gamma + beta for ouro_accept), 1..T */
+  const void* k_blk;           /* [B, T, Hkv, D] */
+  const void* v_blk;           /* [B, T, Hkv, D] */
+  const int32_t* accept_idx;   /* [B, max_accept], entries 0 .. n_accept[b]-1 in [0, T) */
+  const int32_t* n_accept;     /* [B], 0 .. max_accept */
+  void* k_cache;               /* [rows, Hkv, D] */
+  void* v_cache;               /* [rows, Hkv, D] */
+  const int64_t* cu_seqlens;   /* [B+1] region offsets */
+  int32_t* seq_len;            /* [B] in/out */
+  int32_t* overflow;           /* [B] out */
+} ouro_kv_commit_desc;
+
+OURO_API int ouro_kv_commit(const ouro_kv_commit_desc* desc, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------ */
 /* Host-side helpers                                                                     */

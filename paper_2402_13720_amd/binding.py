@@ -29,6 +29,7 @@ class ouro_attn_desc(C.Structure):
         ("out", C.c_void_p), ("lse", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
         ("ev_start", C.c_void_p), ("ev_stop", C.c_void_p),
+        ("seq_len", C.c_void_p),
     ]
 
 
@@ -52,6 +53,16 @@ class ouro_accept_desc(C.Structure):
     ]
 
 
+class ouro_kv_commit_desc(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("dtype", C.c_int32),
+        ("B", C.c_int32), ("T", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32), ("max_accept", C.c_int32),
+        ("k_blk", C.c_void_p), ("v_blk", C.c_void_p), ("accept_idx", C.c_void_p), ("n_accept", C.c_void_p),
+        ("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("cu_seqlens", C.c_void_p),
+        ("seq_len", C.c_void_p), ("overflow", C.c_void_p),
+    ]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(
@@ -72,6 +83,8 @@ def _load() -> C.CDLL:
     lib.ouro_lmhead_pack_w.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     lib.ouro_accept.restype = C.c_int
     lib.ouro_accept.argtypes = [C.POINTER(ouro_accept_desc), C.c_void_p]
+    lib.ouro_kv_commit.restype = C.c_int
+    lib.ouro_kv_commit.argtypes = [C.POINTER(ouro_kv_commit_desc), C.c_void_p]
     lib.ouro_validate_meta_host.restype = C.c_int
     lib.ouro_validate_meta_host.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.ouro_status_string.restype = C.c_char_p
@@ -128,7 +141,7 @@ def alloc_workspace(nbytes: int, device) -> torch.Tensor:
 
 
 def make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen,
-                   lse=None, workspace=None, softmax_scale: float = 0.0) -> ouro_attn_desc:
+                   lse=None, workspace=None, softmax_scale: float = 0.0, seq_len=None) -> ouro_attn_desc:
     B, T, Hq, D = q.shape
     d = ouro_attn_desc()
     d.struct_size = C.sizeof(ouro_attn_desc)
@@ -141,6 +154,7 @@ def make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max
     d.out, d.lse = _ptr(out), _ptr(lse)
     d.workspace = _ptr(workspace)
     d.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    d.seq_len = _ptr(seq_len)
     return d
 
 
@@ -155,9 +169,10 @@ def ouro_verify_attn_workspace(q, k_blk, max_seqlen: int) -> int:
 
 
 def ouro_verify_attn(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, max_seqlen: int,
-                     out=None, lse=None, workspace=None, softmax_scale: float = 0.0, stream=None):
+                     out=None, lse=None, workspace=None, softmax_scale: float = 0.0, stream=None, seq_len=None):
     """Masked draft-block attention.  Tensors are device tensors laid out as in include/ouro.h.
     Allocates out/workspace with torch when not given; returns out."""
+    assert seq_len is None or (seq_len.dtype == torch.int32 and seq_len.is_contiguous())
     for t in (q, k_blk, v_blk):
         assert t.is_contiguous()
     assert cu_seqlens.dtype == torch.int64 and meta.dtype == torch.int16 and meta.is_contiguous()
@@ -168,7 +183,7 @@ def ouro_verify_attn(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, max_se
         if need:
             workspace = alloc_workspace(need, q.device)
     d = make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen, lse, workspace,
-                       softmax_scale)
+                       softmax_scale, seq_len)
     _check(lib.ouro_verify_attn(C.byref(d), _stream(stream)), "ouro_verify_attn")
     return out
 
@@ -265,3 +280,31 @@ def ouro_accept(draft_tok, argmax, meta, root_pred, gamma: int, K: int, beta: in
     d = make_accept_desc(draft_tok, argmax.view(B, T), meta, root_pred, gamma, K, beta, outs)
     _check(lib.ouro_accept(C.byref(d), _stream(stream)), "ouro_accept")
     return outs
+
+
+def make_kv_commit_desc(k_blk, v_blk, accept_idx, n_accept, k_cache, v_cache, cu_seqlens, seq_len,
+                        overflow) -> ouro_kv_commit_desc:
+    B, T, Hkv, D = k_blk.shape
+    d = ouro_kv_commit_desc()
+    d.struct_size = C.sizeof(ouro_kv_commit_desc)
+    d.dtype = _dtype_code(k_blk)
+    d.B, d.T, d.Hkv, d.D, d.max_accept = B, T, Hkv, D, accept_idx.shape[1]
+    d.k_blk, d.v_blk, d.accept_idx, d.n_accept = _ptr(k_blk), _ptr(v_blk), _ptr(accept_idx), _ptr(n_accept)
+    d.k_cache, d.v_cache, d.cu_seqlens = _ptr(k_cache), _ptr(v_cache), _ptr(cu_seqlens)
+    d.seq_len, d.overflow = _ptr(seq_len), _ptr(overflow)
+    return d
+
+
+def ouro_kv_commit(k_blk, v_blk, accept_idx, n_accept, k_cache, v_cache, cu_seqlens, seq_len, overflow=None,
+                   stream=None):
+    """Keep the accepted block tokens: their K/V rows go to the tail of each sequence's cached tokens and
+    seq_len (int32 [B]) grows in place.  Returns overflow (int32 [B])."""
+    assert k_blk.is_contiguous() and v_blk.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous()
+    assert accept_idx.dtype == torch.int32 and accept_idx.is_contiguous() and n_accept.dtype == torch.int32
+    assert seq_len.dtype == torch.int32 and cu_seqlens.dtype == torch.int64
+    assert k_cache.dtype == k_blk.dtype and v_cache.dtype == v_blk.dtype
+    if overflow is None:
+        overflow = torch.empty(k_blk.shape[0], dtype=torch.int32, device=k_blk.device)
+    d = make_kv_commit_desc(k_blk, v_blk, accept_idx, n_accept, k_cache, v_cache, cu_seqlens, seq_len, overflow)
+    _check(lib.ouro_kv_commit(C.byref(d), _stream(stream)), "ouro_kv_commit")
+    return overflow

@@ -62,6 +62,7 @@ struct AttnArgs {
   const __bf16* k_blk;
   const __bf16* v_blk;
   const int64_t* cu;
+  const int32_t* len;  // cached tokens per sequence, or null: the regions given by cu are packed
   const ouro_tok_meta* meta;
   __bf16* out;
   float* lse;
@@ -222,7 +223,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int bg = x / a.nch;
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
   const long cu0 = a.cu[b];
-  const int L = static_cast<int>(a.cu[b + 1] - cu0);
+  const int L = a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - cu0);
   const int T = a.T;
   const int n = L + T;
   const int k_begin = chunk * a.chunk;
@@ -485,7 +486,7 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
   const int bg = x / a.nch;
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
   const long cu0 = a.cu[b];
-  const int L = static_cast<int>(a.cu[b + 1] - cu0);
+  const int L = a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - cu0);
   const int T = a.T;
   const int n = L + T;
   const int k_begin = chunk * a.chunk;
@@ -698,7 +699,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
   const int r = rb * rows_wg + row;
   if (r >= a.M) return;
-  const int n = static_cast<int>(a.cu[b + 1] - a.cu[b]) + a.T;
+  const int n = (a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - a.cu[b])) + a.T;
   const int nchb = (n + a.chunk - 1) / a.chunk;
   if (nchb == 1) return;                            // written directly by the main kernel
   const size_t gbase = static_cast<size_t>(group) * a.nch * rows_wg;
@@ -749,6 +750,7 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
   a.k_blk = static_cast<const __bf16*>(d.k_blk);
   a.v_blk = static_cast<const __bf16*>(d.v_blk);
   a.cu = d.cu_seqlens;
+  a.len = d.seq_len;
   a.meta = d.meta;
   a.out = static_cast<__bf16*>(d.out);
   a.lse = d.lse;

@@ -134,6 +134,23 @@ static int validate_accept(const ouro_accept_desc* d) {
   return OURO_OK;
 }
 
+static int validate_kv_commit(const ouro_kv_commit_desc* d) {
+  if (!d) return OURO_E_NULLPTR;
+  if (d->struct_size != sizeof(ouro_kv_commit_desc)) return OURO_E_BAD_STRUCT;
+  if (d->dtype != OURO_F32 && d->dtype != OURO_BF16) return OURO_E_UNSUPPORTED_DTYPE;
+  if (d->B < 0 || d->B > 65535 || d->T < 1 || d->T > 128 || d->Hkv < 1 || d->D < 1) return OURO_E_BAD_SHAPE;
+  if (d->max_accept < 1 || d->max_accept > d->T) return OURO_E_BAD_SHAPE;
+  const long row_bytes = static_cast<long>(d->Hkv) * d->D * (d->dtype == OURO_BF16 ? 2 : 4);
+  if (row_bytes % 16 != 0 || row_bytes > (1L << 30)) return OURO_E_BAD_SHAPE;
+  if (d->B == 0) return OURO_OK;
+  if (!d->k_blk || !d->v_blk || !d->accept_idx || !d->n_accept || !d->k_cache || !d->v_cache || !d->cu_seqlens ||
+      !d->seq_len || !d->overflow)
+    return OURO_E_NULLPTR;
+  if (!aligned16(d->k_blk) || !aligned16(d->v_blk) || !aligned16(d->k_cache) || !aligned16(d->v_cache))
+    return OURO_E_MISALIGNED;
+  return OURO_OK;
+}
+
 }  // namespace ouro
 
 using namespace ouro;
@@ -200,6 +217,13 @@ int ouro_accept(const ouro_accept_desc* desc, void* hip_stream) {
   if (st != OURO_OK) return st;
   if (desc->B == 0) return OURO_OK;
   return launch_accept(*desc, static_cast<hipStream_t>(hip_stream));
+}
+
+int ouro_kv_commit(const ouro_kv_commit_desc* desc, void* hip_stream) {
+  int st = validate_kv_commit(desc);
+  if (st != OURO_OK) return st;
+  if (desc->B == 0) return OURO_OK;
+  return launch_kv_commit(*desc, static_cast<hipStream_t>(hip_stream));
 }
 
 int ouro_validate_meta_host(const ouro_tok_meta* m, int32_t T, int32_t gamma, int32_t K, int32_t beta) {

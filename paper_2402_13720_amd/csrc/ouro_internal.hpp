@@ -54,7 +54,8 @@ int launch_lmhead_f32(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t
 int launch_pack_w(const void* src, void* dst, int V, int Hd, hipStream_t stream);
 int launch_lmhead_final(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
 
-// ---- acceptance -----------------------------------------------------------------------
+// ---- acceptance, commit ---------------------------------------------------------------
 int launch_accept(const ouro_accept_desc& d, hipStream_t stream);
+int launch_kv_commit(const ouro_kv_commit_desc& d, hipStream_t stream);
 
 }  // namespace ouro

@@ -21,14 +21,14 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
     assert {"ouro_verify_attn", "ouro_lmhead_argmax", "ouro_accept", "ouro_verify_attn_workspace",
-            "ouro_lmhead_argmax_workspace", "ouro_lmhead_packed_w_bytes", "ouro_lmhead_pack_w", "ouro_validate_meta_host", "ouro_status_string",
-            "ouro_last_hip_error", "ouro_version"} <= set(names)
+            "ouro_lmhead_argmax_workspace", "ouro_lmhead_packed_w_bytes", "ouro_lmhead_pack_w", "ouro_kv_commit",
+            "ouro_validate_meta_host", "ouro_status_string", "ouro_last_hip_error", "ouro_version"} <= set(names)
     for n in names:
         assert hasattr(ob.lib, n), n
 
 
 def test_version_and_status_strings():
-    assert ob.lib.ouro_version() == 100
+    assert ob.lib.ouro_version() == 200
     assert ob.lib.ouro_status_string(0) == b"ok"
     for code in range(-8, 0):
         assert ob.lib.ouro_status_string(code) not in (b"ok", b"unknown status")
@@ -36,10 +36,11 @@ def test_version_and_status_strings():
 
 
 def test_struct_sizes_match_the_header_layout():
-    # 8 int32 + 7 pointers + float(+pad) + 4 pointers/size_t
-    assert C.sizeof(ob.ouro_attn_desc) == 32 + 7 * 8 + 8 + 6 * 8
+    # 8 int32 + 7 pointers + float(+pad) + 7 pointers/size_t
+    assert C.sizeof(ob.ouro_attn_desc) == 32 + 7 * 8 + 8 + 7 * 8
     assert C.sizeof(ob.ouro_lmhead_desc) == 24 + 8 * 8
     assert C.sizeof(ob.ouro_accept_desc) == 24 + 11 * 8
+    assert C.sizeof(ob.ouro_kv_commit_desc) == 32 + 9 * 8
 
 
 def _attn_desc(**kw):
@@ -138,6 +139,31 @@ def test_accept_descriptor_validation():
     assert f(C.byref(_acc_desc(K=64, beta=1, gamma=64, T=128)), None) == -2
     assert f(C.byref(_acc_desc()), None) == -1
     assert f(C.byref(_acc_desc(B=0)), None) == 0
+
+
+def _commit_desc(**kw):
+    d = ob.ouro_kv_commit_desc()
+    d.struct_size = C.sizeof(ob.ouro_kv_commit_desc)
+    d.dtype = ob.OURO_BF16
+    d.B, d.T, d.Hkv, d.D, d.max_accept = 1, 64, 32, 128, 22
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_kv_commit_descriptor_validation():
+    f = ob.lib.ouro_kv_commit
+    assert f(None, None) == -1
+    assert f(C.byref(_commit_desc(struct_size=3)), None) == -7
+    assert f(C.byref(_commit_desc(dtype=5)), None) == -3
+    assert f(C.byref(_commit_desc(max_accept=0)), None) == -2
+    assert f(C.byref(_commit_desc(max_accept=65)), None) == -2            # more slots than block tokens
+    assert f(C.byref(_commit_desc(Hkv=1, D=4)), None) == -2               # 8-byte rows: not a multiple of 16
+    assert f(C.byref(_commit_desc()), None) == -1                         # pointers missing
+    p = 4096
+    full = dict(k_blk=p, v_blk=p, accept_idx=p, n_accept=p, k_cache=p, v_cache=p, cu_seqlens=p, seq_len=p, overflow=p)
+    assert f(C.byref(_commit_desc(**{**full, "k_cache": p + 8})), None) == -5
+    assert f(C.byref(_commit_desc(B=0)), None) == 0
 
 
 def test_validate_meta_host():
