@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU-oracle baseline leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--branch", default="uniform", choices=["uniform", "last"])
+    ap.add_argument("--event-every", type=int, default=8,
+                    help="record the per-call and per-kernel HIP events on every Nth timed step (each record is a "
+                         "packet on the stream and costs launch time; 1: every step)")
     ap.add_argument("--w-layout", default="tiled", choices=["tiled", "row"],
                     help="LM-head weight layout: re-blocked once at set-up into contiguous 128x64 tiles "
                          "(ouro_lmhead_pack_w; default) or the row-major [V, hidden] matrix as is")
@@ -222,7 +225,9 @@ def main():
             raise RuntimeError("hipEventElapsedTime failed")
         return ms.value * 1e3
 
-    kev = [[new_event() for _ in range(4)] for _ in range(args.steps)]
+    every = max(1, args.event_every)
+    sampled = [i for i in range(args.steps) if i % every == 0]
+    kev = {i: [new_event() for _ in range(4)] for i in sampled}
 
     def step(i, ev=None, kv=None):
         r = i % nrot
@@ -245,10 +250,10 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    events = {i: [torch.cuda.Event(enable_timing=True) for _ in range(4)] for i in sampled}
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, events[i], kev[i])
+        step(args.warmup + i, events.get(i), kev.get(i))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
@@ -285,12 +290,12 @@ def main():
         graph_us = "unavailable: %s" % type(exc).__name__
 
     ms_step = elapsed * 1e3 / args.steps
-    seg = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(3)] for ev in events])   # ms
+    seg = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(3)] for ev in events.values()])   # ms
     t_attn, t_lm, t_acc = (float(x) for x in seg.mean(axis=0))
     tokens = cfg.R
     # main-kernel durations (ms): attention split-KV kernel, LM-head weight-streaming kernel
-    k_attn = float(np.mean([elapsed_us(k[0], k[1]) for k in kev])) * 1e-3
-    k_lm = float(np.mean([elapsed_us(k[2], k[3]) for k in kev])) * 1e-3
+    k_attn = float(np.mean([elapsed_us(k[0], k[1]) for k in kev.values()])) * 1e-3
+    k_lm = float(np.mean([elapsed_us(k[2], k[3]) for k in kev.values()])) * 1e-3
 
     lm_bytes = lmhead_algorithmic_bytes(cfg)
     at_bytes = attn_algorithmic_bytes(cfg, total_rows)
@@ -302,7 +307,7 @@ def main():
     lm_mfma_bound = cfg.R >= 312          # arithmetic intensity ~R flop/B against a machine balance of ~312
     traffic = load_traffic(workload) or {}
     if lm_mfma_bound:
-        roofline = {"kernel": "lmhead_bf16_kernel (main kernel of ouro_lmhead_argmax)", "bound": "mfma",
+        roofline = {"kernel": "lmhead_bf16_tile_kernel (main kernel of ouro_lmhead_argmax)", "bound": "mfma",
                     "achieved": lm_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": lm_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic.get("lmhead_bytes"),
                     "kernel_us": k_lm * 1e3, "algorithmic_bytes": lm_bytes}
@@ -322,11 +327,13 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": workload, "B": cfg.B, "T": cfg.T, "gamma": cfg.gamma, "K": cfg.K, "beta": cfg.beta_p,
                    "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D, "cache_rows": total_rows, "V": cfg.V,
-                   "branch": args.branch, "rotated_copies": nrot,
+                   "branch": args.branch, "rotated_copies": nrot, "events_on_every_nth_step": every,
                    "w_layout": args.w_layout if cfg.dtype == "bf16" else "row"},
         "call_us": {"ouro_verify_attn": t_attn * 1e3, "ouro_lmhead_argmax": t_lm * 1e3, "ouro_accept": t_acc * 1e3},
         "roofline": roofline,
-        "roofline_attn": {"kernel": "attn_bf16_kernel (main kernel of ouro_verify_attn)", "bound": "hbm",
+        "roofline_attn": {"kernel": "%s (main kernel of ouro_verify_attn)"
+                                    % ("attn_bf16_kernel" if cfg.T * (cfg.Hq // cfg.Hkv) <= 64 else "attn_bf16_rows_kernel"),
+                          "bound": "hbm",
                           "achieved": at_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": at_gbs / HBM_PEAK_GBS,
                           "traffic": traffic.get("attn_bytes"), "kernel_us": k_attn * 1e3,
                           "algorithmic_bytes": at_bytes, "mfma_tflops": at_tflops},
