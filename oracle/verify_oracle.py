@@ -16,7 +16,9 @@ lengthened draft (Sec. 3.2: the masked pass replaces verifying them one by one),
 probe/closed-form cases; attention against a library SDPA on textbook cases and
 the log-sum-exp split identity; LM head against planted winners and ties;
 acceptance against hand-worked traces (tests/golden), exhaustive path
-enumeration, and the lossless replay property of Eq. (4); the commit of accepted
+enumeration, and the lossless replay property of Eq. (4); the phrase-pool
+by-products against a hand-worked example, a regular-expression scan of the match
+string and the definition of Eq. (10); the commit of accepted
 tokens against a hand-worked example (tests/golden), a concatenation written
 with library routines, and the property that a committed cache gives the next
 step the context of the accepted draft.  No function here is "parity unpinned".
@@ -278,8 +280,81 @@ def accept(tok: np.ndarray, argmax: np.ndarray, pid: np.ndarray, boff: np.ndarra
 
 
 # --------------------------------------------------------------------------- #
-# The whole verification step, chained
+# What verification leaves for the phrase pool (Sec. 3.3: Eq. (10) and the two
+# paragraphs after it)
 # --------------------------------------------------------------------------- #
+def pool_byproducts_one(tok: np.ndarray, argmax: np.ndarray, pid: np.ndarray, boff: np.ndarray,
+                        root_pred: Optional[int], gamma: int, K: int, beta_p: int) -> Dict[str, object]:
+    """By-products of one sequence's verification.
+
+    match[t] = [tok[t] == v[t]] for every block position, v[t] being the target's greedy token at that
+    position (the prediction of the row of t's parent); its sum over the main draft is #Match of Eq. (10).
+    A child of the prefix with no root_pred counts as a match, as in accept_one.
+
+    Segments: the maximal runs of consecutive matching positions inside the discarded part of the main
+    draft, d_{A+1..gamma} (0-based positions >= A; position A itself is the first mismatch), as
+    (start, length) pairs in ascending order: the sub-segments of the discarded draft that agree with
+    the verification result.  Which of them are worth keeping (a minimum length) is the caller's policy.
+
+    Repaired phrases: for every phrase o, (p^o_1, v^o_2..beta): its first token, which is the main-draft
+    token at its branch point (-1 for a phrase that hangs off the prefix: that token is not in the block),
+    followed by the target's greedy tokens at the phrase's beta_p block positions.  The caller replaces
+    the phrases it did not use (o != path) with these.
+    """
+    tok = np.asarray(tok).astype(np.int64)
+    T = gamma + K * beta_p
+    v = expected_tokens(np.asarray(argmax).astype(np.int64), pid, boff, root_pred)
+    par = parents(pid, boff)
+    match = np.zeros(T, dtype=np.uint8)
+    for t in range(T):
+        match[t] = 1 if (par[t] == ROOT and root_pred is None) or tok[t] == v[t] else 0
+    A = 0
+    while A < gamma and match[A]:
+        A += 1
+    starts, lens = [], []
+    i = A
+    while i < gamma:
+        if match[i]:
+            j = i
+            while j < gamma and match[j]:
+                j += 1
+            starts.append(i)
+            lens.append(j - i)
+            i = j
+        else:
+            i += 1
+    nmax = max(1, (gamma + 1) // 2)
+    seg_start = np.full(nmax, -1, dtype=np.int32)
+    seg_len = np.zeros(nmax, dtype=np.int32)
+    seg_start[: len(starts)] = starts
+    seg_len[: len(lens)] = lens
+    repaired = np.full((K, beta_p + 1), -1, dtype=np.int32)
+    for o in range(1, K + 1):
+        lo = gamma + (o - 1) * beta_p
+        bo = int(boff[lo])
+        repaired[o - 1, 0] = tok[bo] if bo >= 0 else -1
+        for i in range(beta_p):
+            repaired[o - 1, 1 + i] = v[lo + i]
+    return {"match": match, "n_seg": len(starts), "seg_start": seg_start, "seg_len": seg_len, "repaired": repaired}
+
+
+def pool_byproducts(tok: np.ndarray, argmax: np.ndarray, pid: np.ndarray, boff: np.ndarray,
+                    root_pred: Optional[np.ndarray], gamma: int, K: int, beta_p: int) -> Dict[str, np.ndarray]:
+    """Batch form of pool_byproducts_one: match [B,T] uint8, n_seg [B], seg_start/seg_len
+    [B, ceil(gamma/2)] (-1 / 0 padded), repaired [B,K,beta_p+1]."""
+    B = tok.shape[0]
+    res = [pool_byproducts_one(tok[b], argmax[b], pid[b], boff[b],
+                               None if root_pred is None else int(root_pred[b]), gamma, K, beta_p)
+           for b in range(B)]
+    return {
+        "match": np.stack([r["match"] for r in res]),
+        "n_seg": np.array([r["n_seg"] for r in res], dtype=np.int32),
+        "seg_start": np.stack([r["seg_start"] for r in res]),
+        "seg_len": np.stack([r["seg_len"] for r in res]),
+        "repaired": np.stack([r["repaired"] for r in res]).reshape(B, K, beta_p + 1),
+    }
+
+
 # --------------------------------------------------------------------------- #
 # Keeping the accepted tokens (the sentence after Eq. (3): d_1..A are accepted and
 # the rest of the draft is discarded; after Eq. (9): d_1..gamma, p^j_2..Ahat^j)
@@ -317,6 +392,9 @@ def kv_commit(k_cache: np.ndarray, v_cache: np.ndarray, cu_seqlens: np.ndarray, 
     return {"k_cache": k_new, "v_cache": v_new, "seq_len": len_new, "overflow": overflow}
 
 
+# --------------------------------------------------------------------------- #
+# The whole verification step, chained
+# --------------------------------------------------------------------------- #
 def verify_step(inp: Dict[str, np.ndarray], w: np.ndarray, tok: np.ndarray,
                 root_pred: Optional[np.ndarray], gamma: int, K: int, beta_p: int,
                 hidden_round=None) -> Dict[str, np.ndarray]:
