@@ -192,6 +192,17 @@ typedef struct {
   int32_t* phrase_A;           /* optional [B, K] */
   int32_t* n_match;            /* optional [B]: number of main-draft positions equal to the target's
                                   prediction, accepted or not (#Match, Eq. (10)) */
+  /* Optional by-products for the phrase pool (Sec. 3.3, the two paragraphs after Eq. (10)); NULL to skip. */
+  uint8_t* match_out;          /* [B, T]: 1 where the block token equals the target's greedy token at its position
+                                  (the indicator summed by Eq. (10)); unchecked positions count as 1 */
+  int32_t* n_seg;              /* [B]: number of matching sub-segments of the discarded draft: maximal runs of
+                                  matches among main positions > A.  n_seg, seg_start, seg_len: all or none */
+  int32_t* seg_start;          /* [B, max(1, (gamma+1)/2)]: first main index of each run, ascending, -1 padded */
+  int32_t* seg_len;            /* [B, max(1, (gamma+1)/2)]: run lengths, 0 padded */
+  int32_t* repaired;           /* [B, K, beta+1]: for every phrase o, its first token (the main-draft token at its
+                                  branch point; -1 if it hangs off the prefix) followed by the target's greedy
+                                  token at each of its beta block positions: the phrase (p^o_1, v^o_2..) that
+                                  replaces p^o in the pool when o was not the phrase used */
 } ouro_accept_desc;
 
 OURO_API int ouro_accept(const ouro_accept_desc* desc, void* hip_stream);

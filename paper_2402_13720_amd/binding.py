@@ -50,6 +50,8 @@ class ouro_accept_desc(C.Structure):
         ("draft_tok", C.c_void_p), ("argmax", C.c_void_p), ("meta", C.c_void_p), ("root_pred", C.c_void_p),
         ("n_accept", C.c_void_p), ("path", C.c_void_p), ("bonus", C.c_void_p), ("accept_idx", C.c_void_p),
         ("main_A", C.c_void_p), ("phrase_A", C.c_void_p), ("n_match", C.c_void_p),
+        ("match_out", C.c_void_p), ("n_seg", C.c_void_p), ("seg_start", C.c_void_p), ("seg_len", C.c_void_p),
+        ("repaired", C.c_void_p),
     ]
 
 
@@ -257,7 +259,20 @@ def make_accept_desc(draft_tok, argmax, meta, root_pred, gamma, K, beta, outs) -
     d.n_accept, d.path, d.bonus = _ptr(outs["n_accept"]), _ptr(outs["path"]), _ptr(outs["bonus"])
     d.accept_idx = _ptr(outs["accept_idx"])
     d.main_A, d.phrase_A, d.n_match = _ptr(outs.get("main_A")), _ptr(outs.get("phrase_A")), _ptr(outs.get("n_match"))
+    d.match_out, d.repaired = _ptr(outs.get("match")), _ptr(outs.get("repaired"))
+    d.n_seg, d.seg_start, d.seg_len = _ptr(outs.get("n_seg")), _ptr(outs.get("seg_start")), _ptr(outs.get("seg_len"))
     return d
+
+
+def alloc_pool_outputs(B: int, gamma: int, K: int, beta: int, device) -> dict:
+    """Optional outputs of ouro_accept for the phrase pool; merge into the dict passed as ``outs``."""
+    i32 = dict(dtype=torch.int32, device=device)
+    nmax = max(1, (gamma + 1) // 2)
+    return {
+        "match": torch.empty(B, gamma + K * beta, dtype=torch.uint8, device=device),
+        "n_seg": torch.empty(B, **i32), "seg_start": torch.empty(B, nmax, **i32), "seg_len": torch.empty(B, nmax, **i32),
+        "repaired": torch.empty(B, K, beta + 1, **i32),
+    }
 
 
 def alloc_accept_outputs(B: int, gamma: int, K: int, beta: int, device) -> dict:

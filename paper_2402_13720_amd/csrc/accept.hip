@@ -85,6 +85,41 @@ __global__ __launch_bounds__(64) void accept_kernel(ouro_accept_desc d) {
     for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off);
     if (lane == 0) d.n_match[b] = cnt;
   }
+
+  // ---- by-products for the phrase pool (Sec. 3.3) ----
+  if (d.match_out)
+    for (int t = lane; t < T; t += 64) d.match_out[static_cast<size_t>(b) * T + t] = match[t];
+  if (d.n_seg) {
+    // maximal runs of matches in the discarded part of the main draft (positions > A; A is the first mismatch)
+    const int nmax = max(1, (gamma + 1) / 2);
+    int32_t* ss = d.seg_start + static_cast<size_t>(b) * nmax;
+    int32_t* sl = d.seg_len + static_cast<size_t>(b) * nmax;
+    int base = 0;
+    for (int i0 = 0; i0 < gamma; i0 += 64) {
+      const int i = i0 + lane;
+      const bool is_start = i < gamma && i > A && match[i] && !match[i - 1];
+      const unsigned long long starts = __ballot(is_start);
+      if (is_start) {
+        const int k = base + __popcll(starts & ((1ull << lane) - 1ull));
+        int e = i;
+        while (e < gamma && match[e]) ++e;
+        ss[k] = i;
+        sl[k] = e - i;
+      }
+      base += __popcll(starts);
+    }
+    for (int k = base + lane; k < nmax; k += 64) { ss[k] = -1; sl[k] = 0; }
+    if (lane == 0) d.n_seg[b] = base;
+  }
+  if (d.repaired && lane >= 1 && lane <= K) {
+    // phrase o = lane: its first token (the main-draft token at its branch point) and the target's greedy token
+    // at each of its block positions
+    int32_t* rp = d.repaired + (static_cast<size_t>(b) * K + (lane - 1)) * (beta + 1);
+    const int lo = gamma + (lane - 1) * beta;
+    const int bo = meta[lo].branch_off;
+    rp[0] = bo >= 0 ? tok[bo] : -1;
+    for (int i = 0; i < beta; ++i) rp[1 + i] = i == 0 ? (bo >= 0 ? arg[bo] : root) : arg[lo + i - 1];
+  }
 }
 
 }  // namespace

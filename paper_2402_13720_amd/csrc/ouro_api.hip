@@ -131,6 +131,8 @@ static int validate_accept(const ouro_accept_desc* d) {
   if (d->B == 0) return OURO_OK;
   if (!d->draft_tok || !d->argmax || !d->meta || !d->n_accept || !d->path || !d->bonus || !d->accept_idx)
     return OURO_E_NULLPTR;
+  const int nseg_ptrs = (d->n_seg != nullptr) + (d->seg_start != nullptr) + (d->seg_len != nullptr);
+  if (nseg_ptrs != 0 && nseg_ptrs != 3) return OURO_E_NULLPTR;
   return OURO_OK;
 }
 

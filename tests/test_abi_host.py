@@ -39,7 +39,7 @@ def test_struct_sizes_match_the_header_layout():
     # 8 int32 + 7 pointers + float(+pad) + 7 pointers/size_t
     assert C.sizeof(ob.ouro_attn_desc) == 32 + 7 * 8 + 8 + 7 * 8
     assert C.sizeof(ob.ouro_lmhead_desc) == 24 + 8 * 8
-    assert C.sizeof(ob.ouro_accept_desc) == 24 + 11 * 8
+    assert C.sizeof(ob.ouro_accept_desc) == 24 + 16 * 8
     assert C.sizeof(ob.ouro_kv_commit_desc) == 32 + 9 * 8
 
 
@@ -138,6 +138,9 @@ def test_accept_descriptor_validation():
     assert f(C.byref(_acc_desc(gamma=0, T=48)), None) == -2
     assert f(C.byref(_acc_desc(K=64, beta=1, gamma=64, T=128)), None) == -2
     assert f(C.byref(_acc_desc()), None) == -1
+    p = 4096
+    need = dict(draft_tok=p, argmax=p, meta=p, n_accept=p, path=p, bonus=p, accept_idx=p)
+    assert f(C.byref(_acc_desc(**need, n_seg=p)), None) == -1            # segment outputs: all three or none
     assert f(C.byref(_acc_desc(B=0)), None) == 0
 
 

@@ -10,14 +10,21 @@ from gpu_util import DEV
 
 pytestmark = pytest.mark.gpu
 KEYS = ("n_accept", "path", "bonus", "accept_idx", "main_A", "phrase_A", "n_match")
+POOL_KEYS = ("match", "n_seg", "seg_start", "seg_len", "repaired")     # phrase-pool by-products (optional outputs)
 
 
 def _gpu(tok, argmax, pid, boff, root, gamma, K, bp):
     meta = ob.pack_meta(pid, boff).to(DEV)
+    B = tok.shape[0]
+    outs = ob.alloc_accept_outputs(B, gamma, K, bp, DEV)
+    outs.update(ob.alloc_pool_outputs(B, gamma, K, bp, DEV))
+    for k in POOL_KEYS:
+        outs[k].fill_(77)                                               # padding must be written by the kernel
     got = ob.ouro_accept(torch.from_numpy(tok.astype(np.int32)).to(DEV), torch.from_numpy(argmax.astype(np.int32)).to(DEV),
-                         meta, None if root is None else torch.from_numpy(root.astype(np.int32)).to(DEV), gamma, K, bp)
+                         meta, None if root is None else torch.from_numpy(root.astype(np.int32)).to(DEV), gamma, K, bp,
+                         outs=outs)
     torch.cuda.synchronize()
-    return {k: got[k].cpu().numpy() for k in KEYS}
+    return {k: got[k].cpu().numpy() for k in KEYS + POOL_KEYS}
 
 
 def _compare(tok, argmax, pid, boff, root, gamma, K, bp):
@@ -25,6 +32,9 @@ def _compare(tok, argmax, pid, boff, root, gamma, K, bp):
     got = _gpu(tok, argmax, pid, boff, root, gamma, K, bp)
     for k in KEYS:
         assert np.array_equal(got[k], ref[k]), (k, got[k], ref[k])
+    pool = O.pool_byproducts(tok, argmax, pid, boff, root, gamma, K, bp)
+    for k in POOL_KEYS:
+        assert np.array_equal(got[k], pool[k]), (k, got[k], pool[k])
     return ref
 
 
@@ -36,6 +46,33 @@ def test_handworked_traces():
         assert got["n_accept"][0] == t["n_accept"] and got["path"][0] == t["path"] and got["bonus"][0] == t["bonus"]
         assert got["accept_idx"][0].tolist() == t["idx"].tolist()
         assert got["main_A"][0] == t["A"] and got["phrase_A"][0].tolist() == t["Ahat"].tolist()
+
+
+def test_handworked_pool_byproducts():
+    import os
+    from golden_io import GOLDEN, _clean
+    exs, cur = [], {}
+    with open(os.path.join(GOLDEN, "pool_byproducts_example.txt")) as f:
+        for ln in list(_clean(f)) + [""]:
+            if not ln.strip():
+                if cur:
+                    exs.append(cur)
+                    cur = {}
+                continue
+            k, v = ln.split(":", 1)
+            cur[k.strip()] = v.split()
+    assert len(exs) == 2
+    for ex in exs:
+        gamma, K, bp = int(ex["gamma"][0]), int(ex["K"][0]), int(ex["beta_p"][0])
+        pid, boff = meta_from_layout(gamma, K, bp, [int(x) for x in ex["branch"]])
+        root = None if ex["root"][0] == "none" else np.array([int(ex["root"][0])])
+        ints = lambda k: np.array([int(x) for x in ex[k]])
+        got = _gpu(ints("tok")[None], ints("argmax")[None], pid[None], boff[None], root, gamma, K, bp)
+        assert got["match"][0].tolist() == ints("match").tolist()
+        assert got["n_seg"][0] == int(ex["n_seg"][0])
+        assert got["seg_start"][0].tolist() == ints("seg_start").tolist()
+        assert got["seg_len"][0].tolist() == ints("seg_len").tolist()
+        assert got["repaired"][0].ravel().tolist() == ints("repaired").tolist()
 
 
 @pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
