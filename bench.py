@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--event-every", type=int, default=8,
                     help="record the per-call and per-kernel HIP events on every Nth timed step (each record is a "
                          "packet on the stream and costs launch time; 1: every step)")
+    ap.add_argument("--kv-layout", default="head", choices=["head", "row"],
+                    help="KV-cache layout: [Hkv, rows, D] (every (sequence, KV head) stream contiguous; default) or "
+                         "[rows, Hkv, D]")
     ap.add_argument("--w-layout", default="tiled", choices=["tiled", "row"],
                     help="LM-head weight layout: re-blocked once at set-up into contiguous 128x64 tiles "
                          "(ouro_lmhead_pack_w; default) or the row-major [V, hidden] matrix as is")
@@ -161,6 +164,9 @@ def main():
     up = lambda x: torch.from_numpy(x).to(dev).to(dt).contiguous()
     q, k_blk, v_blk = up(inp["q"]), up(inp["k_blk"]), up(inp["v_blk"])
     kc0, vc0, w0 = up(inp["k_cache"]), up(inp["v_cache"]), up(w)
+    head_major = args.kv_layout == "head"
+    if head_major:                                        # a re-layout of the same values, done once at set-up
+        kc0, vc0 = kc0.permute(1, 0, 2).contiguous(), vc0.permute(1, 0, 2).contiguous()
     kcs = [kc0] + [kc0.clone() for _ in range(nrot - 1)]
     vcs = [vc0] + [vc0.clone() for _ in range(nrot - 1)]
     ws = [w0] + [w0.clone() for _ in range(nrot - 1)]
@@ -181,7 +187,8 @@ def main():
 
     # draft ids: half of the block positions carry the token they will be compared with (the greedy
     # token of their parent row); the other half are uniform.  Values do not affect timing.
-    ob.ouro_verify_attn(q, kcs[0], vcs[0], cu, k_blk, v_blk, meta, max_seqlen, out=out, workspace=ws_attn)
+    ob.ouro_verify_attn(q, kcs[0], vcs[0], cu, k_blk, v_blk, meta, max_seqlen, out=out, workspace=ws_attn,
+                        head_major=head_major)
     ob.ouro_lmhead_argmax(hidden, ws[0], argmax_out=arg, workspace=ws_lm)
     torch.cuda.synchronize()
     amax = arg.cpu().numpy().reshape(cfg.B, cfg.T)
@@ -201,7 +208,8 @@ def main():
     hs = stream.cuda_stream or None
     import ctypes as C
     # descriptors are built once per rotated copy; a step is then three C-ABI calls
-    d_attn = [ob.make_attn_desc(q, kcs[r], vcs[r], cu, k_blk, v_blk, meta, out, max_seqlen, None, ws_attn)
+    d_attn = [ob.make_attn_desc(q, kcs[r], vcs[r], cu, k_blk, v_blk, meta, out, max_seqlen, None, ws_attn,
+                                head_major=head_major)
               for r in range(nrot)]
     d_lm = [ob.make_lmhead_desc(hidden, ws[r], arg, None, ws_lm) for r in range(nrot)]
     d_acc = ob.make_accept_desc(tok, arg.view(cfg.B, cfg.T), meta, root, cfg.gamma, cfg.K, cfg.beta_p, acc_out)
@@ -328,7 +336,7 @@ def main():
         "config": {"workload": workload, "B": cfg.B, "T": cfg.T, "gamma": cfg.gamma, "K": cfg.K, "beta": cfg.beta_p,
                    "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D, "cache_rows": total_rows, "V": cfg.V,
                    "branch": args.branch, "rotated_copies": nrot, "events_on_every_nth_step": every,
-                   "w_layout": args.w_layout if cfg.dtype == "bf16" else "row"},
+                   "w_layout": args.w_layout if cfg.dtype == "bf16" else "row", "kv_layout": args.kv_layout},
         "call_us": {"ouro_verify_attn": t_attn * 1e3, "ouro_lmhead_argmax": t_lm * 1e3, "ouro_accept": t_acc * 1e3},
         "roofline": roofline,
         "roofline_attn": {"kernel": "%s (main kernel of ouro_verify_attn)"

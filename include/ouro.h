@@ -99,7 +99,8 @@ typedef struct {
   int32_t D;                   /* head dim: 128 (bf16) ; 64 or 128 (f32) */
   int32_t max_seqlen;          /* host-side upper bound on every L_b (sizes the launch; no device read-back) */
   const void* q;               /* [B, T, Hq, D] */
-  const void* k_cache;         /* [rows, Hkv, D], sequence b in the region of rows cu_seqlens[b] .. cu_seqlens[b+1]-1 */
+  const void* k_cache;         /* [rows, Hkv, D] (or head-major, see kv_layout); sequence b in the region of rows
+                                  cu_seqlens[b] .. cu_seqlens[b+1]-1 */
   const void* v_cache;         /* same layout; may be NULL only if max_seqlen == 0 */
   const int64_t* cu_seqlens;   /* [B+1], cu[0] = 0, non-decreasing region offsets.  Without seq_len the regions are
                                   packed: L_b = cu[b+1] - cu[b].  0 <= L_b <= max_seqlen */
@@ -115,7 +116,13 @@ typedef struct {
   void* ev_stop;               /* right after the call's main kernel, so that a profiler can time that kernel alone */
   const int32_t* seq_len;      /* optional [B]: L_b, the cached tokens at the start of region b; the rest of the region
                                   is room for tokens accepted later (ouro_kv_commit).  NULL: packed regions */
+  int32_t kv_layout;           /* OURO_KV_ROW_MAJOR: caches are [rows, Hkv, D].  OURO_KV_HEAD_MAJOR: [Hkv, cache_rows, D],
+                                  every (sequence, KV head) stream contiguous in memory, which HBM delivers fastest */
+  int32_t reserved0;           /* 0 */
+  int64_t cache_rows;          /* OURO_KV_HEAD_MAJOR: rows per KV head of the cache allocation (>= cu_seqlens[B]) */
 } ouro_attn_desc;
+
+enum { OURO_KV_ROW_MAJOR = 0, OURO_KV_HEAD_MAJOR = 1 };
 
 /* Host-only: bytes of workspace the call will need for this descriptor (data pointers are
  * not read).  Returns 0 if the descriptor is invalid or no workspace is needed. */
@@ -233,11 +240,14 @@ typedef struct {
   const void* v_blk;           /* [B, T, Hkv, D] */
   const int32_t* accept_idx;   /* [B, max_accept], entries 0 .. n_accept[b]-1 in [0, T) */
   const int32_t* n_accept;     /* [B], 0 .. max_accept */
-  void* k_cache;               /* [rows, Hkv, D] */
-  void* v_cache;               /* [rows, Hkv, D] */
+  void* k_cache;               /* [rows, Hkv, D] or [Hkv, cache_rows, D], see kv_layout */
+  void* v_cache;
   const int64_t* cu_seqlens;   /* [B+1] region offsets */
   int32_t* seq_len;            /* [B] in/out */
   int32_t* overflow;           /* [B] out */
+  int32_t kv_layout;           /* layout of k_cache / v_cache, as in ouro_attn_desc */
+  int32_t reserved0;           /* 0 */
+  int64_t cache_rows;          /* OURO_KV_HEAD_MAJOR: rows per KV head of the cache allocation */
 } ouro_kv_commit_desc;
 
 OURO_API int ouro_kv_commit(const ouro_kv_commit_desc* desc, void* hip_stream);

@@ -16,6 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libouro.so")
 
 OURO_F32, OURO_BF16 = 0, 1
+OURO_KV_ROW_MAJOR, OURO_KV_HEAD_MAJOR = 0, 1
 
 
 class ouro_attn_desc(C.Structure):
@@ -30,6 +31,7 @@ class ouro_attn_desc(C.Structure):
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
         ("ev_start", C.c_void_p), ("ev_stop", C.c_void_p),
         ("seq_len", C.c_void_p),
+        ("kv_layout", C.c_int32), ("reserved0", C.c_int32), ("cache_rows", C.c_int64),
     ]
 
 
@@ -62,6 +64,7 @@ class ouro_kv_commit_desc(C.Structure):
         ("k_blk", C.c_void_p), ("v_blk", C.c_void_p), ("accept_idx", C.c_void_p), ("n_accept", C.c_void_p),
         ("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("cu_seqlens", C.c_void_p),
         ("seq_len", C.c_void_p), ("overflow", C.c_void_p),
+        ("kv_layout", C.c_int32), ("reserved0", C.c_int32), ("cache_rows", C.c_int64),
     ]
 
 
@@ -143,7 +146,9 @@ def alloc_workspace(nbytes: int, device) -> torch.Tensor:
 
 
 def make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen,
-                   lse=None, workspace=None, softmax_scale: float = 0.0, seq_len=None) -> ouro_attn_desc:
+                   lse=None, workspace=None, softmax_scale: float = 0.0, seq_len=None,
+                   head_major: bool = False) -> ouro_attn_desc:
+    """head_major: k_cache / v_cache are [Hkv, cache_rows, D] tensors instead of [rows, Hkv, D]."""
     B, T, Hq, D = q.shape
     d = ouro_attn_desc()
     d.struct_size = C.sizeof(ouro_attn_desc)
@@ -157,6 +162,9 @@ def make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max
     d.workspace = _ptr(workspace)
     d.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     d.seq_len = _ptr(seq_len)
+    if head_major:
+        d.kv_layout = OURO_KV_HEAD_MAJOR
+        d.cache_rows = 0 if k_cache is None else k_cache.shape[1]
     return d
 
 
@@ -171,7 +179,8 @@ def ouro_verify_attn_workspace(q, k_blk, max_seqlen: int) -> int:
 
 
 def ouro_verify_attn(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, max_seqlen: int,
-                     out=None, lse=None, workspace=None, softmax_scale: float = 0.0, stream=None, seq_len=None):
+                     out=None, lse=None, workspace=None, softmax_scale: float = 0.0, stream=None, seq_len=None,
+                     head_major: bool = False):
     """Masked draft-block attention.  Tensors are device tensors laid out as in include/ouro.h.
     Allocates out/workspace with torch when not given; returns out."""
     assert seq_len is None or (seq_len.dtype == torch.int32 and seq_len.is_contiguous())
@@ -185,7 +194,7 @@ def ouro_verify_attn(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, max_se
         if need:
             workspace = alloc_workspace(need, q.device)
     d = make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen, lse, workspace,
-                       softmax_scale, seq_len)
+                       softmax_scale, seq_len, head_major)
     _check(lib.ouro_verify_attn(C.byref(d), _stream(stream)), "ouro_verify_attn")
     return out
 
@@ -298,7 +307,7 @@ def ouro_accept(draft_tok, argmax, meta, root_pred, gamma: int, K: int, beta: in
 
 
 def make_kv_commit_desc(k_blk, v_blk, accept_idx, n_accept, k_cache, v_cache, cu_seqlens, seq_len,
-                        overflow) -> ouro_kv_commit_desc:
+                        overflow, head_major: bool = False) -> ouro_kv_commit_desc:
     B, T, Hkv, D = k_blk.shape
     d = ouro_kv_commit_desc()
     d.struct_size = C.sizeof(ouro_kv_commit_desc)
@@ -307,11 +316,14 @@ def make_kv_commit_desc(k_blk, v_blk, accept_idx, n_accept, k_cache, v_cache, cu
     d.k_blk, d.v_blk, d.accept_idx, d.n_accept = _ptr(k_blk), _ptr(v_blk), _ptr(accept_idx), _ptr(n_accept)
     d.k_cache, d.v_cache, d.cu_seqlens = _ptr(k_cache), _ptr(v_cache), _ptr(cu_seqlens)
     d.seq_len, d.overflow = _ptr(seq_len), _ptr(overflow)
+    if head_major:
+        d.kv_layout = OURO_KV_HEAD_MAJOR
+        d.cache_rows = k_cache.shape[1]
     return d
 
 
 def ouro_kv_commit(k_blk, v_blk, accept_idx, n_accept, k_cache, v_cache, cu_seqlens, seq_len, overflow=None,
-                   stream=None):
+                   stream=None, head_major: bool = False):
     """Keep the accepted block tokens: their K/V rows go to the tail of each sequence's cached tokens and
     seq_len (int32 [B]) grows in place.  Returns overflow (int32 [B])."""
     assert k_blk.is_contiguous() and v_blk.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous()
@@ -320,6 +332,7 @@ def ouro_kv_commit(k_blk, v_blk, accept_idx, n_accept, k_cache, v_cache, cu_seql
     assert k_cache.dtype == k_blk.dtype and v_cache.dtype == v_blk.dtype
     if overflow is None:
         overflow = torch.empty(k_blk.shape[0], dtype=torch.int32, device=k_blk.device)
-    d = make_kv_commit_desc(k_blk, v_blk, accept_idx, n_accept, k_cache, v_cache, cu_seqlens, seq_len, overflow)
+    d = make_kv_commit_desc(k_blk, v_blk, accept_idx, n_accept, k_cache, v_cache, cu_seqlens, seq_len, overflow,
+                            head_major)
     _check(lib.ouro_kv_commit(C.byref(d), _stream(stream)), "ouro_kv_commit")
     return overflow

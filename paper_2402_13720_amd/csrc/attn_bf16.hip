@@ -63,6 +63,8 @@ struct AttnArgs {
   const __bf16* v_blk;
   const int64_t* cu;
   const int32_t* len;  // cached tokens per sequence, or null: the regions given by cu are packed
+  unsigned kv_row_stride;   // cache addressing, in elements: row r of KV head g starts at r * kv_row_stride +
+  size_t kv_head_stride;    // g * kv_head_stride ([rows, Hkv, D]: Hkv*D and D; [Hkv, rows, D]: D and rows*D)
   const ouro_tok_meta* meta;
   __bf16* out;
   float* lse;
@@ -114,15 +116,16 @@ __device__ __forceinline__ void wave_lds_fence() {
 // inside the cache part of the workgroup's window takes the fast path, any other has its keys clamped into the window.
 #define OURO_ATTN_ISSUE_HALF(TILE, REG, CACHE, BLK)                                                                 \
   if ((TILE) + 32 <= fast_end) {                                                                                   \
-    const __bf16* src = (CACHE) + (static_cast<size_t>(cu0 + (TILE)) * Hkv + g) * kD;                              \
+    const __bf16* src = (CACHE) + static_cast<size_t>(cu0 + (TILE)) * kstride + g * a.kv_head_stride;              \
     _Pragma("unroll") for (int i = 0; i < 8; ++i)                                                                  \
         REG[i] = *reinterpret_cast<const u32x4*>(src + loff0 + static_cast<unsigned>(4 * i) * kstride);            \
   } else {                                                                                                         \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                                \
       const int kidx = min((TILE) + 4 * i + kq, k_end - 1); /* clamp: finite data, masked or unused later */       \
       const bool in_cache = kidx < L;                                                                              \
-      const size_t row = in_cache ? static_cast<size_t>(cu0 + kidx) : static_cast<size_t>(b) * T + (kidx - L);     \
-      REG[i] = *reinterpret_cast<const u32x4*>((in_cache ? (CACHE) : (BLK)) + (row * Hkv + g) * kD + 8 * c16);     \
+      const size_t off = in_cache ? static_cast<size_t>(cu0 + kidx) * kstride + g * a.kv_head_stride               \
+                                  : ((static_cast<size_t>(b) * T + (kidx - L)) * Hkv + g) * kD;                    \
+      REG[i] = *reinterpret_cast<const u32x4*>((in_cache ? (CACHE) : (BLK)) + off + 8 * c16);                      \
     }                                                                                                              \
   }
 #define OURO_ATTN_ISSUE_K(TILE, KR) OURO_ATTN_ISSUE_HALF(TILE, KR, a.k_cache, a.k_blk)
@@ -219,8 +222,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int rb = rem >> 3;
   const int x = blk * 8 + (rem & 7);
   if (x >= a.n_x) return;
-  const int chunk = x % a.nch;
-  const int bg = x / a.nch;
+  // chunk-major: the (sequence, KV head) pairs of one chunk index are consecutive, so every XCD (id modulo 8)
+  // sees all chunk indices; pair-major order would give the rarely populated late chunks to a few XCDs
+  const int nbg = a.n_x / a.nch;
+  const int chunk = x / nbg;
+  const int bg = x - chunk * nbg;
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
   const long cu0 = a.cu[b];
   const int L = a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - cu0);
@@ -267,7 +273,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   // Element offset of this lane's first row from the first row of a tile; its other rows follow at
   // fixed multiples of the key stride (tile wholly inside the cache: one wave-uniform base pointer
   // plus these, no per-row address arithmetic in the loop).
-  const unsigned kstride = static_cast<unsigned>(Hkv) * kD;
+  const unsigned kstride = a.kv_row_stride;        // elements between consecutive cache rows of one head
   const unsigned loff0 = static_cast<unsigned>(kq) * kstride + 8 * c16;
   f32x16 o[4];
   float m_run = -INFINITY, l_run = 0.f;
@@ -482,8 +488,11 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
   const int rb = rem >> 3;
   const int x = blk * 8 + (rem & 7);
   if (x >= a.n_x) return;
-  const int chunk = x % a.nch;
-  const int bg = x / a.nch;
+  // chunk-major: the (sequence, KV head) pairs of one chunk index are consecutive, so every XCD (id modulo 8)
+  // sees all chunk indices; pair-major order would give the rarely populated late chunks to a few XCDs
+  const int nbg = a.n_x / a.nch;
+  const int chunk = x / nbg;
+  const int bg = x - chunk * nbg;
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
   const long cu0 = a.cu[b];
   const int L = a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - cu0);
@@ -517,7 +526,7 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
   const int kq = lane >> 4, c16 = lane & 15;      // staging roles, as in the kernel above
   const int row_base = 16 * (kq >> 1) + 4 * (kq & 1);
   u32x4 kr[8], vr[8];
-  const unsigned kstride = static_cast<unsigned>(Hkv) * kD;
+  const unsigned kstride = a.kv_row_stride;        // elements between consecutive cache rows of one head
   const unsigned loff0 = static_cast<unsigned>(kq) * kstride + 8 * c16;
 
   f32x16 o[4], sacc[2];
@@ -751,6 +760,8 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
   a.v_blk = static_cast<const __bf16*>(d.v_blk);
   a.cu = d.cu_seqlens;
   a.len = d.seq_len;
+  a.kv_row_stride = d.kv_layout == OURO_KV_HEAD_MAJOR ? kD : static_cast<unsigned>(d.Hkv) * kD;
+  a.kv_head_stride = d.kv_layout == OURO_KV_HEAD_MAJOR ? static_cast<size_t>(d.cache_rows) * kD : kD;
   a.meta = d.meta;
   a.out = static_cast<__bf16*>(d.out);
   a.lse = d.lse;

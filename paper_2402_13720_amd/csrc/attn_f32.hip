@@ -28,6 +28,9 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(ouro_attn_desc d, float sc
   const int L = d.seq_len ? d.seq_len[b] : static_cast<int>(d.cu_seqlens[b + 1] - cu0);
   const int n = L + T;
   const float* q = static_cast<const float*>(d.q) + ((static_cast<size_t>(b) * T + t) * Hq + h) * D;
+  // cache addressing: [rows, Hkv, D] or [Hkv, rows, D]
+  const size_t row_stride = d.kv_layout == OURO_KV_HEAD_MAJOR ? D : static_cast<size_t>(Hkv) * D;
+  const size_t head_stride = d.kv_layout == OURO_KV_HEAD_MAJOR ? static_cast<size_t>(d.cache_rows) * D : D;
   const float* kc = static_cast<const float*>(d.k_cache);
   const float* vc = static_cast<const float*>(d.v_cache);
   const float* kb = static_cast<const float*>(d.k_blk) + static_cast<size_t>(b) * T * Hkv * D;
@@ -49,7 +52,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(ouro_attn_desc d, float sc
     const float* krow = nullptr;
     if (vis) {
       if (kidx < L) {
-        krow = kc + (static_cast<size_t>(cu0 + kidx) * Hkv + g) * D;
+        krow = kc + static_cast<size_t>(cu0 + kidx) * row_stride + g * head_stride;
       } else {
         const int kk = kidx - L;
         const int pid_k = meta[kk].phrase_id;
@@ -91,7 +94,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(ouro_attn_desc d, float sc
       const float pj = p_s[j];
       if (pj == 0.f) continue;                   // wave-uniform
       const int kj = base + j;
-      const float* vrow = kj < L ? vc + (static_cast<size_t>(cu0 + kj) * Hkv + g) * D
+      const float* vrow = kj < L ? vc + static_cast<size_t>(cu0 + kj) * row_stride + g * head_stride
                                  : vb + (static_cast<size_t>(kj - L) * Hkv + g) * D;
 #pragma unroll
       for (int i = 0; i < DPL; ++i) acc[i] = fmaf(pj, vrow[lane + 64 * i], acc[i]);

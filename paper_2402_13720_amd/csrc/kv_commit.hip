@@ -26,6 +26,8 @@ struct CommitArgs {
   int32_t* overflow;
   int B, T, max_accept;
   unsigned row_bytes;          // Hkv * D * element size, multiple of 16
+  unsigned head_bytes;         // D * element size
+  size_t cache_rows;           // 0: cache is [rows, Hkv, D]; else [Hkv, cache_rows, D]
 };
 
 __device__ __forceinline__ bool fits(const CommitArgs& a, int b, int have, int na) {
@@ -41,10 +43,15 @@ __global__ __launch_bounds__(256) void kv_commit_copy_kernel(CommitArgs a) {
   const int t = a.accept_idx[b * a.max_accept + i];
   if (t < 0 || t >= a.T) return;                       // contract violation: never index outside the block
   const size_t src = (static_cast<size_t>(b) * a.T + t) * a.row_bytes;
-  const size_t dst = static_cast<size_t>(a.cu[b] + have + i) * a.row_bytes;
+  const size_t row = static_cast<size_t>(a.cu[b] + have + i);
   for (unsigned off = threadIdx.x * 16u; off < a.row_bytes; off += 256u * 16u) {
-    *reinterpret_cast<u32x4*>(a.k_cache + dst + off) = *reinterpret_cast<const u32x4*>(a.k_blk + src + off);
-    *reinterpret_cast<u32x4*>(a.v_cache + dst + off) = *reinterpret_cast<const u32x4*>(a.v_blk + src + off);
+    size_t dst = row * a.row_bytes + off;
+    if (a.cache_rows) {                                // head-major cache: head g of this row lives at [g][row]
+      const unsigned g = off / a.head_bytes;
+      dst = (g * a.cache_rows + row) * a.head_bytes + (off - g * a.head_bytes);
+    }
+    *reinterpret_cast<u32x4*>(a.k_cache + dst) = *reinterpret_cast<const u32x4*>(a.k_blk + src + off);
+    *reinterpret_cast<u32x4*>(a.v_cache + dst) = *reinterpret_cast<const u32x4*>(a.v_blk + src + off);
   }
 }
 
@@ -74,6 +81,8 @@ int launch_kv_commit(const ouro_kv_commit_desc& d, hipStream_t stream) {
   a.T = d.T;
   a.max_accept = d.max_accept;
   a.row_bytes = static_cast<unsigned>(d.Hkv) * d.D * (d.dtype == OURO_BF16 ? 2u : 4u);
+  a.head_bytes = static_cast<unsigned>(d.D) * (d.dtype == OURO_BF16 ? 2u : 4u);
+  a.cache_rows = d.kv_layout == OURO_KV_HEAD_MAJOR ? static_cast<size_t>(d.cache_rows) : 0;
   hipLaunchKernelGGL(kv_commit_copy_kernel, dim3(static_cast<unsigned>(d.B) * d.max_accept), dim3(256), 0, stream, a);
   int st = check_launch();
   if (st != OURO_OK) return st;

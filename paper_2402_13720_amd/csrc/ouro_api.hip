@@ -100,6 +100,8 @@ static int validate_attn(const ouro_attn_desc* d, bool need_pointers) {
   if (d->max_seqlen < 0) return OURO_E_BAD_SHAPE;
   if (d->dtype == OURO_BF16 ? d->D != 128 : (d->D != 64 && d->D != 128)) return OURO_E_BAD_SHAPE;
   if (static_cast<long>(d->T) * (d->Hq / d->Hkv) > 32768) return OURO_E_BAD_SHAPE;
+  if (d->kv_layout != OURO_KV_ROW_MAJOR && d->kv_layout != OURO_KV_HEAD_MAJOR) return OURO_E_BAD_SHAPE;
+  if (d->kv_layout == OURO_KV_HEAD_MAJOR && (d->cache_rows < 0 || d->cache_rows > (1LL << 40))) return OURO_E_BAD_SHAPE;
   if (!need_pointers || d->B == 0) return OURO_OK;
   if (!d->q || !d->cu_seqlens || !d->k_blk || !d->v_blk || !d->meta || !d->out) return OURO_E_NULLPTR;
   if (d->max_seqlen > 0 && (!d->k_cache || !d->v_cache)) return OURO_E_NULLPTR;
@@ -144,6 +146,10 @@ static int validate_kv_commit(const ouro_kv_commit_desc* d) {
   if (d->max_accept < 1 || d->max_accept > d->T) return OURO_E_BAD_SHAPE;
   const long row_bytes = static_cast<long>(d->Hkv) * d->D * (d->dtype == OURO_BF16 ? 2 : 4);
   if (row_bytes % 16 != 0 || row_bytes > (1L << 30)) return OURO_E_BAD_SHAPE;
+  if (d->kv_layout != OURO_KV_ROW_MAJOR && d->kv_layout != OURO_KV_HEAD_MAJOR) return OURO_E_BAD_SHAPE;
+  if (d->kv_layout == OURO_KV_HEAD_MAJOR &&
+      (d->cache_rows < 1 || d->cache_rows > (1LL << 40) || (static_cast<long>(d->D) * (d->dtype == OURO_BF16 ? 2 : 4)) % 16 != 0))
+    return OURO_E_BAD_SHAPE;
   if (d->B == 0) return OURO_OK;
   if (!d->k_blk || !d->v_blk || !d->accept_idx || !d->n_accept || !d->k_cache || !d->v_cache || !d->cu_seqlens ||
       !d->seq_len || !d->overflow)

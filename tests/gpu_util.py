@@ -11,24 +11,29 @@ def torch_dtype(cfg):
     return torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
 
 
-def upload_attention(cfg, inp):
+def upload_attention(cfg, inp, head_major=False):
+    """head_major: the caches go up as [Hkv, rows, D] (a pure re-layout of the same values)."""
     from paper_2402_13720_amd import binding as ob
     dt = torch_dtype(cfg)
     t = {}
     for k in ("q", "k_cache", "v_cache", "k_blk", "v_blk"):
         t[k] = torch.from_numpy(inp[k]).to(DEV).to(dt).contiguous()
+    if head_major:
+        for k in ("k_cache", "v_cache"):
+            t[k] = t[k].permute(1, 0, 2).contiguous()
     t["cu_seqlens"] = torch.from_numpy(inp["cu_seqlens"]).to(DEV)
     t["meta"] = ob.pack_meta(inp["pid"], inp["boff"]).to(DEV)
     t["max_seqlen"] = int(np.diff(inp["cu_seqlens"]).max()) if cfg.B else 0
     return t
 
 
-def run_attention(cfg, inp, want_lse=True, max_seqlen=None):
+def run_attention(cfg, inp, want_lse=True, max_seqlen=None, head_major=False):
     from paper_2402_13720_amd import binding as ob
-    t = upload_attention(cfg, inp)
+    t = upload_attention(cfg, inp, head_major)
     lse = torch.full((cfg.B, cfg.Hq, cfg.T), float("nan"), dtype=torch.float32, device=DEV) if want_lse else None
     out = ob.ouro_verify_attn(t["q"], t["k_cache"], t["v_cache"], t["cu_seqlens"], t["k_blk"], t["v_blk"], t["meta"],
-                              max_seqlen=t["max_seqlen"] if max_seqlen is None else max_seqlen, lse=lse)
+                              max_seqlen=t["max_seqlen"] if max_seqlen is None else max_seqlen, lse=lse,
+                              head_major=head_major)
     torch.cuda.synchronize()
     return out, lse, t
 

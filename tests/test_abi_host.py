@@ -37,10 +37,10 @@ def test_version_and_status_strings():
 
 def test_struct_sizes_match_the_header_layout():
     # 8 int32 + 7 pointers + float(+pad) + 7 pointers/size_t
-    assert C.sizeof(ob.ouro_attn_desc) == 32 + 7 * 8 + 8 + 7 * 8
+    assert C.sizeof(ob.ouro_attn_desc) == 32 + 7 * 8 + 8 + 7 * 8 + 16
     assert C.sizeof(ob.ouro_lmhead_desc) == 24 + 8 * 8
     assert C.sizeof(ob.ouro_accept_desc) == 24 + 16 * 8
-    assert C.sizeof(ob.ouro_kv_commit_desc) == 32 + 9 * 8
+    assert C.sizeof(ob.ouro_kv_commit_desc) == 32 + 9 * 8 + 16
 
 
 def _attn_desc(**kw):

@@ -15,8 +15,8 @@ def _oracle(inp, heads=None):
                               inp["pid"], inp["boff"], heads=heads)
 
 
-def _check(cfg, inp, heads=None, lse_tol=None):
-    out, lse, _ = run_attention(cfg, inp)
+def _check(cfg, inp, heads=None, lse_tol=None, head_major=False):
+    out, lse, _ = run_attention(cfg, inp, head_major=head_major)
     ref = _oracle(inp, heads)
     got = to_np64(out)
     got_lse = to_np64(lse)
@@ -65,6 +65,7 @@ def test_bf16_small_shapes(kw, branch):
     _check(cfg, W.make_attention_inputs(cfg, 1234, branch=branch))
 
 
+@pytest.mark.parametrize("head_major", [False, True])
 @pytest.mark.parametrize("rw", [1, 2, 4])
 @pytest.mark.parametrize("kw, chunk", [
     (dict(B=2, Hq=4, Hkv=2, L=(0, 300), gamma=10, K=5, beta_p=6), 0),         # 80 rows; one sequence is all block
@@ -73,15 +74,20 @@ def test_bf16_small_shapes(kw, branch):
     (dict(B=4, Hq=2, Hkv=1, L=(30, 2000), gamma=8, K=4, beta_p=6), 512),      # uneven lengths, empty chunk slots
     (dict(B=1, Hq=1, Hkv=1, L=95, gamma=1, K=0, beta_p=0), 0),                # a single row
 ])
-def test_bf16_every_kernel_variant(monkeypatch, kw, chunk, rw):
+def test_bf16_every_kernel_variant(monkeypatch, kw, chunk, rw, head_major):
     """The launch heuristic picks the row blocks per workgroup (1: waves split the keys; 2, 4: waves split the
     rows and share staged tiles) and the chunk length; force each combination so that all three kernels see
-    several stages, several chunks and a ragged tail."""
+    several stages, several chunks and a ragged tail, with the cache in either layout."""
     monkeypatch.setenv("OURO_ATTN_RW", str(rw))
     if chunk:
         monkeypatch.setenv("OURO_ATTN_CHUNK", str(chunk))
     cfg = W.scaled(W.CONFIGS[2], **kw)
-    _check(cfg, W.make_attention_inputs(cfg, 4321))
+    _check(cfg, W.make_attention_inputs(cfg, 4321), head_major=head_major)
+
+
+def test_fp32_head_major_cache():
+    cfg = W.scaled(W.CONFIGS[1], B=3, L=(0, 300))
+    _check(cfg, W.make_attention_inputs(cfg, 78), head_major=True)
 
 
 def test_bf16_phrase_hanging_off_the_prefix():
@@ -127,14 +133,15 @@ def test_full_size_configs(cfg_id):
     assert torch.equal(out, out2)
 
 
-def test_full_size_config5_sampled_heads():
+@pytest.mark.parametrize("head_major", [False, True])
+def test_full_size_config5_sampled_heads(head_major):
     cfg = W.CONFIGS[5]
     inp = W.make_attention_inputs(cfg, W.seed_for(5))
     lens = np.diff(inp["cu_seqlens"])
     order = np.argsort(lens)
     seqs = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]       # shortest, median, longest sequence
     heads = [(b, h) for b in seqs for h in (0, 13, 31)]
-    _check(cfg, inp, heads)
+    _check(cfg, inp, heads, head_major=head_major)
 
 
 def test_workspace_is_reusable_across_shapes_and_calls():

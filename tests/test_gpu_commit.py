@@ -45,7 +45,8 @@ def _random_accepts(cfg, rng, full=False):
     (2, dict(B=6, Hq=8, Hkv=8, L=(10, 50)), 9),         # room for only some of the commits: overflow flags
     (5, dict(B=16, L=(1, 64)), 14),                     # many sequences
 ])
-def test_commit_matches_the_oracle_bit_for_bit(cfg_id, kw, room):
+@pytest.mark.parametrize("head_major", [False, True])
+def test_commit_matches_the_oracle_bit_for_bit(cfg_id, kw, room, head_major):
     rng = np.random.default_rng(cfg_id * 10 + room)
     cfg = W.scaled(W.CONFIGS[cfg_id], **kw)
     inp = W.make_attention_inputs(cfg, 900 + cfg_id)
@@ -55,10 +56,15 @@ def test_commit_matches_the_oracle_bit_for_bit(cfg_id, kw, room):
     if room < cfg.gamma + cfg.beta_p:
         assert ref["overflow"].any() and not ref["overflow"].all()      # the case really has both outcomes
     kd, vd = _up(k, cfg), _up(v, cfg)
+    if head_major:                                                       # the same values as [Hkv, rows, D]
+        kd, vd = kd.permute(1, 0, 2).contiguous(), vd.permute(1, 0, 2).contiguous()
     len_d = torch.from_numpy(lens.astype(np.int32)).to(DEV)
     ovf = ob.ouro_kv_commit(_up(inp["k_blk"], cfg), _up(inp["v_blk"], cfg), torch.from_numpy(idx).to(DEV),
-                            torch.from_numpy(n_acc).to(DEV), kd, vd, torch.from_numpy(cu).to(DEV), len_d)
+                            torch.from_numpy(n_acc).to(DEV), kd, vd, torch.from_numpy(cu).to(DEV), len_d,
+                            head_major=head_major)
     torch.cuda.synchronize()
+    if head_major:
+        kd, vd = kd.permute(1, 0, 2), vd.permute(1, 0, 2)
     assert np.array_equal(ovf.cpu().numpy(), ref["overflow"])
     assert np.array_equal(len_d.cpu().numpy(), ref["seq_len"])
     assert np.array_equal(kd.float().cpu().numpy(), ref["k_cache"])      # every row, used or spare, bit for bit
