@@ -39,6 +39,7 @@ struct LmArgs {
   const __bf16* w;
   float2* part;        // [nslab][R]
   int R, Hd, V;
+  int nslab, nrtile;
   int tiled;        // W given as contiguous [slab][k-tile][128][64] tiles
 };
 
@@ -71,8 +72,14 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int col = lane & 31, half = lane >> 5;
-  const int slab0 = blockIdx.x * C::kWRows;
-  const int r0 = blockIdx.y * C::kHRows;
+  // workgroup id -> (slab, row tile): the row tiles of one slab sit 8 ids apart, i.e. run at the same time on the
+  // same XCD and share its L2, so that W still comes from HBM once when R needs several row tiles
+  const int per = 8 * a.nrtile;
+  const int blk = blockIdx.x / per, rem = blockIdx.x - blk * per;
+  const int slab = blk * 8 + (rem & 7);
+  if (slab >= a.nslab) return;
+  const int slab0 = slab * C::kWRows;
+  const int r0 = (rem >> 3) * C::kHRows;
   const int R = a.R, Hd = a.Hd, V = a.V;
   unsigned char* wl = lds + wave * C::kWaveLds;
   unsigned char* hl = wl + C::kWRows * 128;
@@ -88,7 +95,7 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   const size_t wstep = a.tiled ? 128 * 64 : 64;
 #pragma unroll
   for (int p = 0; p < MT * 4; ++p)
-    wrow[p] = a.tiled ? a.w + (static_cast<size_t>(blockIdx.x) * (Hd / 64) * 128 + 8 * p + lr) * 64 + 8 * lc
+    wrow[p] = a.tiled ? a.w + (static_cast<size_t>(slab) * (Hd / 64) * 128 + 8 * p + lr) * 64 + 8 * lc
                       : a.w + static_cast<size_t>(min(slab0 + 8 * p + lr, V - 1)) * Hd + 8 * lc;   // rows past V: duplicate, masked later
 #pragma unroll
   for (int p = 0; p < NT * 4; ++p)
@@ -207,7 +214,7 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
       const int i2 = besti[mt * C::kHRows + rl];
       if (better(v2, i2, bv, bi)) { bv = v2; bi = i2; }
     }
-    a.part[static_cast<size_t>(blockIdx.x) * R + r0 + rl] = make_float2(bv, __int_as_float(bi));
+    a.part[static_cast<size_t>(slab) * R + r0 + rl] = make_float2(bv, __int_as_float(bi));
   }
 }
 
@@ -238,7 +245,8 @@ int launch_variant(const LmArgs& a, const LmPlan& plan, hipStream_t stream) {
     if (e != hipSuccess) return hip_failed(e);
     attr_set = true;
   }
-  hipLaunchKernelGGL((lmhead_bf16_kernel<MT, NT>), dim3(plan.nslab, plan.nrtile), dim3(256), C::kLdsBytes, stream, a);
+  const unsigned grid = static_cast<unsigned>((plan.nslab + 7) / 8) * 8u * plan.nrtile;
+  hipLaunchKernelGGL((lmhead_bf16_kernel<MT, NT>), dim3(grid), dim3(256), C::kLdsBytes, stream, a);
   return check_launch();
 }
 
@@ -260,6 +268,8 @@ int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_
   a.Hd = d.Hd;
   a.V = d.V;
   a.tiled = d.w_layout == OURO_W_TILED;
+  a.nslab = plan.nslab;
+  a.nrtile = plan.nrtile;
   if (plan.variant == 3) return launch_lmhead_bf16_tile(d, plan, stream);
   if (plan.variant == 1) return launch_variant<4, 2>(a, plan, stream);
   return launch_variant<4, 4>(a, plan, stream);
