@@ -253,6 +253,72 @@ typedef struct {
 OURO_API int ouro_kv_commit(const ouro_kv_commit_desc* desc, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------ */
+/* The rest of the verifying layer around the attention.  The paper verifies the block with */
+/* one forward of the target model (Sec. 3.2) and fixes one thing about that forward beyond  */
+/* the mask: since every lengthened draft of Eq. (7) is an ordinary linear sequence, a block   */
+/* token's position is the number of tokens before it in its own draft,                      */
+/*   pos = L_b + i                 for main token i,                                        */
+/*   pos = L_b + b_j + 1 + i       for the i-th block token of a phrase hanging off main b_j. */
+/* The operations themselves are the target model's (Llama-2: RMSNorm, rotate-half rotary     */
+/* embedding, SwiGLU); all inner arithmetic in fp32.                                         */
+/* ------------------------------------------------------------------------------------ */
+
+/* Rotary embedding of the block's queries and keys, in place, at the positions above: the     */
+/* pair (x[i], x[i + D/2]) of every head is rotated by the angle pos * base^(-2i/D).           */
+typedef struct {
+  uint32_t struct_size;        /* sizeof(ouro_rope_desc) */
+  int32_t dtype;
+  int32_t B, T, Hq, Hkv, D;    /* D even */
+  float base;                  /* <= 0: 10000 */
+  void* q;                     /* [B, T, Hq, D] in/out */
+  void* k_blk;                 /* [B, T, Hkv, D] in/out */
+  const ouro_tok_meta* meta;   /* [B, T] */
+  const int64_t* cu_seqlens;   /* [B+1], as in ouro_attn_desc */
+  const int32_t* seq_len;      /* optional [B], as in ouro_attn_desc */
+  int32_t* positions;          /* optional out [B, T] */
+} ouro_rope_desc;
+OURO_API int ouro_rope_block(const ouro_rope_desc* desc, void* hip_stream);
+
+/* out[r, :] = x[r, :] / sqrt(mean(x[r, :]^2) + eps) * gain */
+typedef struct {
+  uint32_t struct_size;
+  int32_t dtype;
+  int32_t R, Hd;
+  float eps;
+  const void* x;               /* [R, Hd] */
+  const void* gain;            /* [Hd] */
+  void* out;                   /* [R, Hd]; may alias x */
+} ouro_rmsnorm_desc;
+OURO_API int ouro_rmsnorm(const ouro_rmsnorm_desc* desc, void* hip_stream);
+
+/* out[r, n] = sum_k x[r, k] * w[n, k] (+ residual[r, n]): every projection of the layer.  bf16 only (bf16 MFMA,  */
+/* fp32 accumulation, one rounding at the end).  The weight is streamed from HBM once, like the LM head's, and may   */
+/* be given in the same tiled form (ouro_lmhead_pack_w with V = N, Hd = K).                                        */
+typedef struct {
+  uint32_t struct_size;
+  int32_t dtype;               /* OURO_BF16 */
+  int32_t R;                   /* rows, >= 0 */
+  int32_t K;                   /* input features, multiple of 64 */
+  int32_t N;                   /* output features, multiple of 8 */
+  int32_t w_layout;            /* OURO_W_ROW_MAJOR or OURO_W_TILED */
+  const void* x;               /* [R, K] */
+  const void* w;               /* [N, K] or tiled */
+  const void* residual;        /* optional [R, N]; may alias out */
+  void* out;                   /* [R, N] */
+} ouro_linear_desc;
+OURO_API int ouro_linear(const ouro_linear_desc* desc, void* hip_stream);
+
+/* out[r, f] = silu(gate_up[r, f]) * gate_up[r, F + f], silu(z) = z / (1 + exp(-z)) */
+typedef struct {
+  uint32_t struct_size;
+  int32_t dtype;
+  int32_t R, F;
+  const void* gate_up;         /* [R, 2F]: gate columns then up columns (one fused projection) */
+  void* out;                   /* [R, F] */
+} ouro_silu_mul_desc;
+OURO_API int ouro_silu_mul(const ouro_silu_mul_desc* desc, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------ */
 /* Host-side helpers                                                                     */
 /* ------------------------------------------------------------------------------------ */
 /* Debug check of a HOST copy of one sequence's metadata against the layout rules above

@@ -68,6 +68,38 @@ class ouro_kv_commit_desc(C.Structure):
     ]
 
 
+class ouro_rope_desc(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("dtype", C.c_int32),
+        ("B", C.c_int32), ("T", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+        ("base", C.c_float),
+        ("q", C.c_void_p), ("k_blk", C.c_void_p), ("meta", C.c_void_p), ("cu_seqlens", C.c_void_p),
+        ("seq_len", C.c_void_p), ("positions", C.c_void_p),
+    ]
+
+
+class ouro_rmsnorm_desc(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("dtype", C.c_int32), ("R", C.c_int32), ("Hd", C.c_int32), ("eps", C.c_float),
+        ("x", C.c_void_p), ("gain", C.c_void_p), ("out", C.c_void_p),
+    ]
+
+
+class ouro_linear_desc(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("dtype", C.c_int32), ("R", C.c_int32), ("K", C.c_int32), ("N", C.c_int32),
+        ("w_layout", C.c_int32),
+        ("x", C.c_void_p), ("w", C.c_void_p), ("residual", C.c_void_p), ("out", C.c_void_p),
+    ]
+
+
+class ouro_silu_mul_desc(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("dtype", C.c_int32), ("R", C.c_int32), ("F", C.c_int32),
+        ("gate_up", C.c_void_p), ("out", C.c_void_p),
+    ]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(
@@ -90,6 +122,10 @@ def _load() -> C.CDLL:
     lib.ouro_accept.argtypes = [C.POINTER(ouro_accept_desc), C.c_void_p]
     lib.ouro_kv_commit.restype = C.c_int
     lib.ouro_kv_commit.argtypes = [C.POINTER(ouro_kv_commit_desc), C.c_void_p]
+    for name, desc in (("ouro_rope_block", ouro_rope_desc), ("ouro_rmsnorm", ouro_rmsnorm_desc),
+                       ("ouro_linear", ouro_linear_desc), ("ouro_silu_mul", ouro_silu_mul_desc)):
+        getattr(lib, name).restype = C.c_int
+        getattr(lib, name).argtypes = [C.POINTER(desc), C.c_void_p]
     lib.ouro_validate_meta_host.restype = C.c_int
     lib.ouro_validate_meta_host.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.ouro_status_string.restype = C.c_char_p
@@ -336,3 +372,64 @@ def ouro_kv_commit(k_blk, v_blk, accept_idx, n_accept, k_cache, v_cache, cu_seql
                             head_major)
     _check(lib.ouro_kv_commit(C.byref(d), _stream(stream)), "ouro_kv_commit")
     return overflow
+
+
+def ouro_rope_block(q, k_blk, meta, cu_seqlens, seq_len=None, base: float = 0.0, positions=None, stream=None):
+    """Rotary embedding of the block's q [B,T,Hq,D] and k_blk [B,T,Hkv,D], in place, at the positions the draft
+    structure gives (cached tokens + tokens before it in the token's own draft).  Returns positions if given."""
+    assert q.is_contiguous() and k_blk.is_contiguous() and q.dtype == k_blk.dtype
+    B, T, Hq, D = q.shape
+    d = ouro_rope_desc()
+    d.struct_size = C.sizeof(ouro_rope_desc)
+    d.dtype = _dtype_code(q)
+    d.B, d.T, d.Hq, d.Hkv, d.D = B, T, Hq, k_blk.shape[2], D
+    d.base = float(base)
+    d.q, d.k_blk, d.meta, d.cu_seqlens = _ptr(q), _ptr(k_blk), _ptr(meta), _ptr(cu_seqlens)
+    d.seq_len, d.positions = _ptr(seq_len), _ptr(positions)
+    _check(lib.ouro_rope_block(C.byref(d), _stream(stream)), "ouro_rope_block")
+    return positions
+
+
+def ouro_rmsnorm(x, gain, eps: float, out=None, stream=None):
+    assert x.is_contiguous() and gain.is_contiguous() and gain.dtype == x.dtype
+    if out is None:
+        out = torch.empty_like(x)
+    d = ouro_rmsnorm_desc()
+    d.struct_size = C.sizeof(ouro_rmsnorm_desc)
+    d.dtype = _dtype_code(x)
+    d.R, d.Hd, d.eps = x.shape[0], x.shape[1], float(eps)
+    d.x, d.gain, d.out = _ptr(x), _ptr(gain), _ptr(out)
+    _check(lib.ouro_rmsnorm(C.byref(d), _stream(stream)), "ouro_rmsnorm")
+    return out
+
+
+def ouro_linear(x, w, residual=None, out=None, stream=None):
+    """out = x . w^T (+ residual); w is a [N, K] bf16 tensor or a TiledWeight."""
+    assert x.is_contiguous() and x.dtype == torch.bfloat16
+    tiled = isinstance(w, TiledWeight)
+    N, K = (w.V, w.Hd) if tiled else tuple(w.shape)
+    assert K == x.shape[1]
+    if out is None:
+        out = torch.empty(x.shape[0], N, dtype=x.dtype, device=x.device)
+    d = ouro_linear_desc()
+    d.struct_size = C.sizeof(ouro_linear_desc)
+    d.dtype = OURO_BF16
+    d.R, d.K, d.N = x.shape[0], K, N
+    d.w_layout = OURO_W_TILED if tiled else OURO_W_ROW_MAJOR
+    d.x, d.w, d.residual, d.out = _ptr(x), _ptr(w.data if tiled else w), _ptr(residual), _ptr(out)
+    _check(lib.ouro_linear(C.byref(d), _stream(stream)), "ouro_linear")
+    return out
+
+
+def ouro_silu_mul(gate_up, out=None, stream=None):
+    assert gate_up.is_contiguous() and gate_up.shape[1] % 2 == 0
+    R, F = gate_up.shape[0], gate_up.shape[1] // 2
+    if out is None:
+        out = torch.empty(R, F, dtype=gate_up.dtype, device=gate_up.device)
+    d = ouro_silu_mul_desc()
+    d.struct_size = C.sizeof(ouro_silu_mul_desc)
+    d.dtype = _dtype_code(gate_up)
+    d.R, d.F = R, F
+    d.gate_up, d.out = _ptr(gate_up), _ptr(out)
+    _check(lib.ouro_silu_mul(C.byref(d), _stream(stream)), "ouro_silu_mul")
+    return out

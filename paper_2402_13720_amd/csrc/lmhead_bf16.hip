@@ -33,6 +33,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef unsigned __attribute__((ext_vector_type(4))) u32x4;   // 16-byte staging register
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 
 struct LmArgs {
   const __bf16* hidden;
@@ -41,6 +42,9 @@ struct LmArgs {
   int R, Hd, V;
   int nslab, nrtile;
   int tiled;        // W given as contiguous [slab][k-tile][128][64] tiles
+  // plain-projection mode (kStore): out[r, v] = product (+ residual[r, v]), bf16, row stride V
+  __bf16* out;
+  const __bf16* residual;
 };
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
@@ -66,7 +70,10 @@ struct LmCfg {
   static constexpr int kLdsBytes = kBestOff + MT * kHRows * 8;
 };
 
-template <int MT, int NT>
+// kStore = false: LM head, the epilogue reduces to one (value, id) pair per (slab, row).
+// kStore = true: the same streaming product as a plain projection x . W^T, the epilogue writes the bf16 outputs
+// (optionally adding a residual): the other weight matrices of the verifying layer are streamed the same way.
+template <int MT, int NT, bool kStore>
 __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   using C = LmCfg<MT, NT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -181,6 +188,27 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
     __syncthreads();
     const int tile = rd * 4 + wave;
     const int mt = tile / NT, nt = tile % NT;
+    if constexpr (kStore) {
+      // lane (col, half) holds, for row r0 + 32*nt + col, the outputs of columns slab0 + 32*mt + 8*ig + 4*half + 0..3
+      const int r = r0 + 32 * nt + col;
+#pragma unroll
+      for (int ig = 0; ig < 4; ++ig) {
+        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int wv = 0; wv < 4; ++wv) sum += reinterpret_cast<const f32x4*>(lds)[((wv * 4 + wave) * 4 + ig) * 64 + lane];
+        const int v = slab0 + 32 * mt + 8 * ig + 4 * half;
+        if (r < R && v < V) {                                    // V is a multiple of 8 in this mode: whole groups
+          const size_t o = static_cast<size_t>(r) * V + v;
+          if (a.residual) {
+            const bf16x4 res = *reinterpret_cast<const bf16x4*>(a.residual + o);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sum[e] += static_cast<float>(res[e]);
+          }
+          *reinterpret_cast<bf16x4*>(a.out + o) = __builtin_convertvector(sum, bf16x4);
+        }
+      }
+      continue;
+    }
     float bv = -INFINITY;
     int bi = 0x7fffffff;
 #pragma unroll
@@ -203,6 +231,7 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
       besti[mt * C::kHRows + 32 * nt + col] = bi;
     }
   }
+  if constexpr (kStore) return;
   __syncthreads();
   for (int rl = threadIdx.x; rl < C::kHRows; rl += 256) {
     if (r0 + rl >= R) continue;
@@ -235,18 +264,18 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const u32x4* __restrict__ s
   dst[i] = x;
 }
 
-template <int MT, int NT>
+template <int MT, int NT, bool kStore>
 int launch_variant(const LmArgs& a, const LmPlan& plan, hipStream_t stream) {
   using C = LmCfg<MT, NT>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_bf16_kernel<MT, NT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_bf16_kernel<MT, NT, kStore>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
     if (e != hipSuccess) return hip_failed(e);
     attr_set = true;
   }
   const unsigned grid = static_cast<unsigned>((plan.nslab + 7) / 8) * 8u * plan.nrtile;
-  hipLaunchKernelGGL((lmhead_bf16_kernel<MT, NT>), dim3(grid), dim3(256), C::kLdsBytes, stream, a);
+  hipLaunchKernelGGL((lmhead_bf16_kernel<MT, NT, kStore>), dim3(grid), dim3(256), C::kLdsBytes, stream, a);
   return check_launch();
 }
 
@@ -271,8 +300,32 @@ int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_
   a.nslab = plan.nslab;
   a.nrtile = plan.nrtile;
   if (plan.variant == 3) return launch_lmhead_bf16_tile(d, plan, stream);
-  if (plan.variant == 1) return launch_variant<4, 2>(a, plan, stream);
-  return launch_variant<4, 4>(a, plan, stream);
+  if (plan.variant == 1) return launch_variant<4, 2, false>(a, plan, stream);
+  return launch_variant<4, 4, false>(a, plan, stream);
+}
+
+int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream) {
+  LmArgs a{};
+  a.hidden = static_cast<const __bf16*>(d.x);
+  a.w = static_cast<const __bf16*>(d.w);
+  a.R = d.R;
+  a.Hd = d.K;
+  a.V = d.N;
+  a.tiled = d.w_layout == OURO_W_TILED;
+  a.out = static_cast<__bf16*>(d.out);
+  a.residual = static_cast<const __bf16*>(d.residual);
+  LmPlan plan{};
+  plan.slab = 128;
+  plan.nslab = (d.N + 127) / 128;
+  a.nslab = plan.nslab;
+  if (d.R <= 64) {
+    plan.rtile = 64;
+    a.nrtile = plan.nrtile = 1;
+    return launch_variant<4, 2, true>(a, plan, stream);
+  }
+  plan.rtile = 128;                               // more rows: 128-row tiles; the tiles of a slab share an XCD's L2
+  a.nrtile = plan.nrtile = (d.R + 127) / 128;
+  return launch_variant<4, 4, true>(a, plan, stream);
 }
 
 }  // namespace ouro

@@ -234,6 +234,49 @@ int ouro_kv_commit(const ouro_kv_commit_desc* desc, void* hip_stream) {
   return launch_kv_commit(*desc, static_cast<hipStream_t>(hip_stream));
 }
 
+int ouro_rope_block(const ouro_rope_desc* d, void* hip_stream) {
+  if (!d) return OURO_E_NULLPTR;
+  if (d->struct_size != sizeof(ouro_rope_desc)) return OURO_E_BAD_STRUCT;
+  if (d->dtype != OURO_F32 && d->dtype != OURO_BF16) return OURO_E_UNSUPPORTED_DTYPE;
+  if (d->B < 0 || d->B > 65535 || d->T < 1 || d->T > 128 || d->Hq < 1 || d->Hkv < 1 || d->D < 2 || d->D % 2 != 0 || d->D > 1024)
+    return OURO_E_BAD_SHAPE;
+  if (d->B == 0) return OURO_OK;
+  if (!d->q || !d->k_blk || !d->meta || !d->cu_seqlens) return OURO_E_NULLPTR;
+  return launch_rope_block(*d, static_cast<hipStream_t>(hip_stream));
+}
+
+int ouro_rmsnorm(const ouro_rmsnorm_desc* d, void* hip_stream) {
+  if (!d) return OURO_E_NULLPTR;
+  if (d->struct_size != sizeof(ouro_rmsnorm_desc)) return OURO_E_BAD_STRUCT;
+  if (d->dtype != OURO_F32 && d->dtype != OURO_BF16) return OURO_E_UNSUPPORTED_DTYPE;
+  if (d->R < 0 || d->Hd < 1 || !(d->eps >= 0.f)) return OURO_E_BAD_SHAPE;
+  if (d->R == 0) return OURO_OK;
+  if (!d->x || !d->gain || !d->out) return OURO_E_NULLPTR;
+  return launch_rmsnorm(*d, static_cast<hipStream_t>(hip_stream));
+}
+
+int ouro_linear(const ouro_linear_desc* d, void* hip_stream) {
+  if (!d) return OURO_E_NULLPTR;
+  if (d->struct_size != sizeof(ouro_linear_desc)) return OURO_E_BAD_STRUCT;
+  if (d->dtype != OURO_BF16) return OURO_E_UNSUPPORTED_DTYPE;
+  if (d->R < 0 || d->K < 64 || d->K % 64 != 0 || d->N < 8 || d->N % 8 != 0) return OURO_E_BAD_SHAPE;
+  if (d->w_layout != OURO_W_ROW_MAJOR && d->w_layout != OURO_W_TILED) return OURO_E_BAD_SHAPE;
+  if (d->R == 0) return OURO_OK;
+  if (!d->x || !d->w || !d->out) return OURO_E_NULLPTR;
+  if (!aligned16(d->x) || !aligned16(d->w) || !aligned16(d->out) || !aligned16(d->residual)) return OURO_E_MISALIGNED;
+  return launch_linear_bf16(*d, static_cast<hipStream_t>(hip_stream));
+}
+
+int ouro_silu_mul(const ouro_silu_mul_desc* d, void* hip_stream) {
+  if (!d) return OURO_E_NULLPTR;
+  if (d->struct_size != sizeof(ouro_silu_mul_desc)) return OURO_E_BAD_STRUCT;
+  if (d->dtype != OURO_F32 && d->dtype != OURO_BF16) return OURO_E_UNSUPPORTED_DTYPE;
+  if (d->R < 0 || d->F < 1) return OURO_E_BAD_SHAPE;
+  if (d->R == 0) return OURO_OK;
+  if (!d->gate_up || !d->out) return OURO_E_NULLPTR;
+  return launch_silu_mul(*d, static_cast<hipStream_t>(hip_stream));
+}
+
 int ouro_validate_meta_host(const ouro_tok_meta* m, int32_t T, int32_t gamma, int32_t K, int32_t beta) {
   if (!m) return OURO_E_NULLPTR;
   if (T < 1 || gamma < 1 || K < 0 || beta < 0 || static_cast<long>(gamma) + static_cast<long>(K) * beta != T)

@@ -58,4 +58,10 @@ int launch_lmhead_final(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream
 int launch_accept(const ouro_accept_desc& d, hipStream_t stream);
 int launch_kv_commit(const ouro_kv_commit_desc& d, hipStream_t stream);
 
+// ---- the rest of the verifying layer ---------------------------------------------------
+int launch_rope_block(const ouro_rope_desc& d, hipStream_t stream);
+int launch_rmsnorm(const ouro_rmsnorm_desc& d, hipStream_t stream);
+int launch_silu_mul(const ouro_silu_mul_desc& d, hipStream_t stream);
+int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream);
+
 }  // namespace ouro

@@ -22,6 +22,7 @@ def test_every_declared_symbol_is_exported():
     names = _declared_functions()
     assert {"ouro_verify_attn", "ouro_lmhead_argmax", "ouro_accept", "ouro_verify_attn_workspace",
             "ouro_lmhead_argmax_workspace", "ouro_lmhead_packed_w_bytes", "ouro_lmhead_pack_w", "ouro_kv_commit",
+            "ouro_rope_block", "ouro_rmsnorm", "ouro_linear", "ouro_silu_mul",
             "ouro_validate_meta_host", "ouro_status_string", "ouro_last_hip_error", "ouro_version"} <= set(names)
     for n in names:
         assert hasattr(ob.lib, n), n
@@ -167,6 +168,34 @@ def test_kv_commit_descriptor_validation():
     full = dict(k_blk=p, v_blk=p, accept_idx=p, n_accept=p, k_cache=p, v_cache=p, cu_seqlens=p, seq_len=p, overflow=p)
     assert f(C.byref(_commit_desc(**{**full, "k_cache": p + 8})), None) == -5
     assert f(C.byref(_commit_desc(B=0)), None) == 0
+
+
+def test_layer_descriptor_validation():
+    for name, desc in (("ouro_rope_block", ob.ouro_rope_desc), ("ouro_rmsnorm", ob.ouro_rmsnorm_desc),
+                       ("ouro_linear", ob.ouro_linear_desc), ("ouro_silu_mul", ob.ouro_silu_mul_desc)):
+        f = getattr(ob.lib, name)
+        assert f(None, None) == -1
+        d = desc()
+        d.struct_size = 4
+        assert f(C.byref(d), None) == -7
+    d = ob.ouro_linear_desc()
+    d.struct_size = C.sizeof(ob.ouro_linear_desc)
+    d.dtype, d.R, d.K, d.N = ob.OURO_F32, 4, 64, 8
+    assert ob.lib.ouro_linear(C.byref(d), None) == -3                     # bf16 only
+    d.dtype, d.K = ob.OURO_BF16, 100
+    assert ob.lib.ouro_linear(C.byref(d), None) == -2                     # K must be a multiple of 64
+    d.K, d.N = 64, 12
+    assert ob.lib.ouro_linear(C.byref(d), None) == -2                     # N must be a multiple of 8
+    d.N = 8
+    assert ob.lib.ouro_linear(C.byref(d), None) == -1                     # pointers missing
+    d.R = 0
+    assert ob.lib.ouro_linear(C.byref(d), None) == 0
+    r = ob.ouro_rope_desc()
+    r.struct_size = C.sizeof(ob.ouro_rope_desc)
+    r.dtype, r.B, r.T, r.Hq, r.Hkv, r.D = ob.OURO_BF16, 1, 8, 2, 2, 7
+    assert ob.lib.ouro_rope_block(C.byref(r), None) == -2                 # odd head dim
+    r.D = 8
+    assert ob.lib.ouro_rope_block(C.byref(r), None) == -1
 
 
 def test_validate_meta_host():

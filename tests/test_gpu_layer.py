@@ -1,0 +1,142 @@
+"""GPU parity of the layer pieces around the attention (positions + rotary embedding, RMSNorm, projections, SwiGLU)
+against the layer oracle, and of one whole verifying layer chained on the GPU."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer_oracle as LO, verify_oracle as O
+from paper_2402_13720_amd import binding as ob, workloads as W
+from gpu_util import DEV, to_np64
+
+pytestmark = pytest.mark.gpu
+BF16_EPS = 2.0 ** -8          # relative spacing bound of a value rounded to bf16 (RNE: error <= 2^-9 |x|)
+
+
+def _bf(x):
+    return W.round_to_bf16(np.asarray(x, dtype=np.float32))
+
+
+def _up(x, dt=torch.bfloat16):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV).to(dt).contiguous()
+
+
+@pytest.mark.parametrize("cfg_id, kw, dt", [
+    (1, dict(B=3, L=(0, 200)), torch.float32),
+    (2, dict(B=2, Hq=4, Hkv=2, L=(0, 300)), torch.bfloat16),
+    (5, dict(B=4, Hq=4, Hkv=4, L=(512, 8192)), torch.bfloat16),          # positions in the thousands
+])
+@pytest.mark.parametrize("with_len", [False, True])
+def test_rope_block(cfg_id, kw, dt, with_len):
+    cfg = W.scaled(W.CONFIGS[cfg_id], **kw)
+    inp = W.make_attention_inputs(cfg, 300 + cfg_id, branch="uniform")
+    inp["boff"][0, cfg.gamma:cfg.gamma + cfg.beta_p] = -1                # one phrase hangs off the prefix
+    cu = inp["cu_seqlens"]
+    lens = np.diff(cu).astype(np.int32)
+    if with_len:                                                        # regions with room: lengths given apart
+        lens = np.maximum(lens - 3, 0).astype(np.int32)
+    pos_ref = LO.block_positions(inp["pid"], inp["boff"], lens)
+    q_ref, k_ref = LO.rope(inp["q"], pos_ref), LO.rope(inp["k_blk"], pos_ref)
+    q, k = _up(inp["q"], dt), _up(inp["k_blk"], dt)
+    pos = torch.empty(cfg.B, cfg.T, dtype=torch.int32, device=DEV)
+    ob.ouro_rope_block(q, k, ob.pack_meta(inp["pid"], inp["boff"]).to(DEV), torch.from_numpy(cu).to(DEV),
+                       seq_len=torch.from_numpy(lens).to(DEV) if with_len else None, positions=pos)
+    torch.cuda.synchronize()
+    assert np.array_equal(pos.cpu().numpy(), pos_ref)                   # integer work: exact
+    xmax = float(np.abs(inp["q"]).max())
+    # fp32 angle = pos * inv_freq carries a relative 2^-23 error -> pos_max * 2^-23 radians; outputs then round to dt
+    tol = 2.0 * xmax * (pos_ref.max() * 2.0 ** -23 + (BF16_EPS if dt == torch.bfloat16 else 2.0 ** -22))
+    assert np.abs(to_np64(q) - q_ref).max() <= tol and np.abs(to_np64(k) - k_ref).max() <= tol
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("R, Hd", [(1, 64), (64, 4096), (37, 5120)])
+def test_rmsnorm(dt, R, Hd):
+    rng = np.random.default_rng(R + Hd)
+    x, g = _bf(rng.standard_normal((R, Hd)) * 3.0), _bf(1.0 + 0.1 * rng.standard_normal(Hd))
+    ref = LO.rmsnorm(x, g, 1e-5)
+    out = ob.ouro_rmsnorm(_up(x, dt), _up(g, dt), 1e-5)
+    torch.cuda.synchronize()
+    tol = np.abs(ref).max() * (BF16_EPS if dt == torch.bfloat16 else 1e-5)
+    assert np.abs(to_np64(out) - ref).max() <= tol
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+def test_silu_mul(dt):
+    rng = np.random.default_rng(9)
+    gu = _bf(rng.standard_normal((33, 2 * 1000)) * 4.0)
+    ref = LO.silu_mul(gu)
+    out = ob.ouro_silu_mul(_up(gu, dt))
+    torch.cuda.synchronize()
+    tol = np.abs(ref).max() * (BF16_EPS if dt == torch.bfloat16 else 1e-5)
+    assert np.abs(to_np64(out) - ref).max() <= tol
+
+
+@pytest.mark.parametrize("R, K, N", [(64, 4096, 1024), (1, 64, 8), (37, 320, 264), (128, 1024, 640), (300, 512, 384)])
+@pytest.mark.parametrize("tiled", [False, True])
+@pytest.mark.parametrize("with_res", [False, True])
+def test_linear(R, K, N, tiled, with_res):
+    rng = np.random.default_rng(R * 7 + N)
+    x, w = _bf(rng.standard_normal((R, K))), _bf(rng.standard_normal((N, K)) * 0.05)
+    res = _bf(rng.standard_normal((R, N))) if with_res else None
+    ref = LO.linear(x, w, res)
+    w_d = _up(w)
+    if tiled:
+        w_d = ob.ouro_lmhead_pack_w(w_d)
+    out = ob.ouro_linear(_up(x), w_d, residual=None if res is None else _up(res))
+    torch.cuda.synchronize()
+    # fp32 accumulation of exact bf16 products (error ~1e-6 relative to the sum of magnitudes), one bf16 rounding
+    tol = np.abs(ref).max() * BF16_EPS + 1e-4
+    assert np.abs(to_np64(out) - ref).max() <= tol
+
+
+def test_one_verifying_layer_chained_on_the_gpu():
+    """x -> RMSNorm -> fused QKV projection -> rotary embedding at the draft positions -> draft-block attention ->
+    output projection + residual -> RMSNorm -> fused gate/up projection -> SwiGLU -> down projection + residual.
+    The oracle chain rounds to bf16 wherever the GPU chain stores bf16, so both see the same intermediate values up
+    to the rounding of each stage's own arithmetic."""
+    cfg = W.scaled(W.CONFIGS[2], B=2, Hq=8, Hkv=4, L=(40, 700), gamma=8, K=4, beta_p=6)   # hidden 1024, T = 32
+    Hd, D, F = cfg.Hq * cfg.D, cfg.D, 1536
+    rng = np.random.default_rng(77)
+    inp = W.make_attention_inputs(cfg, 4242)
+    lens = np.diff(inp["cu_seqlens"]).astype(np.int32)
+    R = cfg.B * cfg.T
+    x = _bf(rng.standard_normal((R, Hd)))
+    g1, g2 = _bf(1 + 0.1 * rng.standard_normal(Hd)), _bf(1 + 0.1 * rng.standard_normal(Hd))
+    nqkv = (cfg.Hq + 2 * cfg.Hkv) * D
+    wqkv, wo = _bf(rng.standard_normal((nqkv, Hd)) * Hd ** -0.5), _bf(rng.standard_normal((Hd, Hd)) * Hd ** -0.5)
+    wgu, wd = _bf(rng.standard_normal((2 * F, Hd)) * Hd ** -0.5), _bf(rng.standard_normal((Hd, F)) * F ** -0.5)
+
+    # ---- oracle chain (fp64 arithmetic, bf16 storage between the stages)
+    h = _bf(LO.rmsnorm(x, g1, 1e-5))
+    qkv = _bf(LO.linear(h, wqkv)).reshape(cfg.B, cfg.T, cfg.Hq + 2 * cfg.Hkv, D)
+    q0, k0, v0 = qkv[:, :, :cfg.Hq], qkv[:, :, cfg.Hq:cfg.Hq + cfg.Hkv], qkv[:, :, cfg.Hq + cfg.Hkv:]
+    pos = LO.block_positions(inp["pid"], inp["boff"], lens)
+    q1, k1 = _bf(LO.rope(q0, pos)), _bf(LO.rope(k0, pos))
+    att = _bf(O.verify_attention(q1, inp["k_cache"], inp["v_cache"], inp["cu_seqlens"], k1, np.ascontiguousarray(v0),
+                                 inp["pid"], inp["boff"])["out"]).reshape(R, Hd)
+    x1 = _bf(LO.linear(att, wo, x))
+    h2 = _bf(LO.rmsnorm(x1, g2, 1e-5))
+    act = _bf(LO.silu_mul(_bf(LO.linear(h2, wgu))))
+    ref = LO.linear(act, wd, x1)
+
+    # ---- GPU chain
+    meta = ob.pack_meta(inp["pid"], inp["boff"]).to(DEV)
+    cu_d = torch.from_numpy(inp["cu_seqlens"]).to(DEV)
+    x_d = _up(x)
+    h_d = ob.ouro_rmsnorm(x_d, _up(g1), 1e-5)
+    qkv_d = ob.ouro_linear(h_d, ob.ouro_lmhead_pack_w(_up(wqkv))).view(cfg.B, cfg.T, cfg.Hq + 2 * cfg.Hkv, D)
+    q_d = qkv_d[:, :, :cfg.Hq].contiguous()
+    k_d = qkv_d[:, :, cfg.Hq:cfg.Hq + cfg.Hkv].contiguous()
+    v_d = qkv_d[:, :, cfg.Hq + cfg.Hkv:].contiguous()
+    ob.ouro_rope_block(q_d, k_d, meta, cu_d)
+    att_d = ob.ouro_verify_attn(q_d, _up(inp["k_cache"]), _up(inp["v_cache"]), cu_d, k_d, v_d, meta, int(lens.max()))
+    x1_d = ob.ouro_linear(att_d.view(R, Hd), ob.ouro_lmhead_pack_w(_up(wo)), residual=x_d)
+    h2_d = ob.ouro_rmsnorm(x1_d, _up(g2), 1e-5)
+    act_d = ob.ouro_silu_mul(ob.ouro_linear(h2_d, ob.ouro_lmhead_pack_w(_up(wgu))))
+    out_d = ob.ouro_linear(act_d, ob.ouro_lmhead_pack_w(_up(wd)), residual=x1_d)
+    torch.cuda.synchronize()
+    err = np.abs(to_np64(out_d) - ref).max()
+    scale = np.abs(ref).max()
+    print("layer chain: max-abs err %.3g on outputs of magnitude %.3g" % (err, scale), flush=True)
+    # each of the ~8 bf16 stores can differ by one rounding step between the chains; they add up incoherently
+    assert err <= 8 * BF16_EPS * scale
