@@ -305,7 +305,12 @@ typedef struct {
   const void* w;               /* [N, K] or tiled */
   const void* residual;        /* optional [R, N]; may alias out */
   void* out;                   /* [R, N] */
+  void* workspace;             /* >= ouro_linear_workspace() bytes, 16-byte aligned; contents arbitrary.  Needed when
+                                  N is small: the k range is then split over several workgroups whose fp32 partial
+                                  sums are added in a fixed order by a second small kernel */
+  size_t workspace_bytes;
 } ouro_linear_desc;
+OURO_API size_t ouro_linear_workspace(const ouro_linear_desc* desc);   /* host-only; 0 if invalid or none needed */
 OURO_API int ouro_linear(const ouro_linear_desc* desc, void* hip_stream);
 
 /* out[r, f] = silu(gate_up[r, f]) * gate_up[r, F + f], silu(z) = z / (1 + exp(-z)) */

@@ -90,6 +90,7 @@ class ouro_linear_desc(C.Structure):
         ("struct_size", C.c_uint32), ("dtype", C.c_int32), ("R", C.c_int32), ("K", C.c_int32), ("N", C.c_int32),
         ("w_layout", C.c_int32),
         ("x", C.c_void_p), ("w", C.c_void_p), ("residual", C.c_void_p), ("out", C.c_void_p),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
 
 
@@ -126,6 +127,8 @@ def _load() -> C.CDLL:
                        ("ouro_linear", ouro_linear_desc), ("ouro_silu_mul", ouro_silu_mul_desc)):
         getattr(lib, name).restype = C.c_int
         getattr(lib, name).argtypes = [C.POINTER(desc), C.c_void_p]
+    lib.ouro_linear_workspace.restype = C.c_size_t
+    lib.ouro_linear_workspace.argtypes = [C.POINTER(ouro_linear_desc)]
     lib.ouro_validate_meta_host.restype = C.c_int
     lib.ouro_validate_meta_host.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.ouro_status_string.restype = C.c_char_p
@@ -403,7 +406,7 @@ def ouro_rmsnorm(x, gain, eps: float, out=None, stream=None):
     return out
 
 
-def ouro_linear(x, w, residual=None, out=None, stream=None):
+def ouro_linear(x, w, residual=None, out=None, stream=None, workspace=None):
     """out = x . w^T (+ residual); w is a [N, K] bf16 tensor or a TiledWeight."""
     assert x.is_contiguous() and x.dtype == torch.bfloat16
     tiled = isinstance(w, TiledWeight)
@@ -417,6 +420,12 @@ def ouro_linear(x, w, residual=None, out=None, stream=None):
     d.R, d.K, d.N = x.shape[0], K, N
     d.w_layout = OURO_W_TILED if tiled else OURO_W_ROW_MAJOR
     d.x, d.w, d.residual, d.out = _ptr(x), _ptr(w.data if tiled else w), _ptr(residual), _ptr(out)
+    if workspace is None:
+        need = int(lib.ouro_linear_workspace(C.byref(d)))
+        if need:
+            workspace = alloc_workspace(need, x.device)
+    d.workspace = _ptr(workspace)
+    d.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.ouro_linear(C.byref(d), _stream(stream)), "ouro_linear")
     return out
 

@@ -22,6 +22,9 @@
 //     slower: store acknowledgement, ticket and reload are three device-scope round trips
 //     that every workgroup pays at the very end, when nothing is left to overlap them with.
 #include <math.h>
+#include <stdlib.h>
+
+#include <algorithm>
 
 #include "ouro_internal.hpp"
 
@@ -45,6 +48,10 @@ struct LmArgs {
   // plain-projection mode (kStore): out[r, v] = product (+ residual[r, v]), bf16, row stride V
   __bf16* out;
   const __bf16* residual;
+  // ... with the k range split over ksplit workgroups per (slab, row tile) when the grid would otherwise leave most
+  // compute units idle: fp32 partial sums go to part_f32[ks][R][V] and linear_reduce_kernel finishes
+  float* part_f32;
+  int ksplit;
 };
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
@@ -81,12 +88,15 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   const int col = lane & 31, half = lane >> 5;
   // workgroup id -> (slab, row tile): the row tiles of one slab sit 8 ids apart, i.e. run at the same time on the
   // same XCD and share its L2, so that W still comes from HBM once when R needs several row tiles
-  const int per = 8 * a.nrtile;
+  const int inner = kStore ? a.nrtile * a.ksplit : a.nrtile;   // workgroups per slab (they share the slab's W rows)
+  const int per = 8 * inner;
   const int blk = blockIdx.x / per, rem = blockIdx.x - blk * per;
   const int slab = blk * 8 + (rem & 7);
   if (slab >= a.nslab) return;
   const int slab0 = slab * C::kWRows;
-  const int r0 = (rem >> 3) * C::kHRows;
+  const int sub = rem >> 3;
+  const int ks = kStore ? sub / a.nrtile : 0;
+  const int r0 = (sub - ks * a.nrtile) * C::kHRows;
   const int R = a.R, Hd = a.Hd, V = a.V;
   unsigned char* wl = lds + wave * C::kWaveLds;
   unsigned char* hl = wl + C::kWRows * 128;
@@ -124,8 +134,12 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.f;
 
-  const int nkt = Hd / 64;
-  int kt = wave;
+  // this workgroup's k-tiles: all of them, or its share of an even split
+  const int nkt_all = Hd / 64;
+  const int kt_per = kStore ? (nkt_all + a.ksplit - 1) / a.ksplit : nkt_all;
+  const int kt0 = ks * kt_per;
+  const int nkt = min(nkt_all, kt0 + kt_per);
+  int kt = kt0 + wave;
   if (kt < nkt) OURO_LM_ISSUE_LOADS(kt)
   for (; kt < nkt; kt += 4) {
     // Each staging register is copied to LDS and immediately re-armed with its load of the wave's next
@@ -199,6 +213,10 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
         const int v = slab0 + 32 * mt + 8 * ig + 4 * half;
         if (r < R && v < V) {                                    // V is a multiple of 8 in this mode: whole groups
           const size_t o = static_cast<size_t>(r) * V + v;
+          if (a.ksplit > 1) {
+            *reinterpret_cast<f32x4*>(a.part_f32 + static_cast<size_t>(ks) * R * V + o) = sum;
+            continue;
+          }
           if (a.residual) {
             const bf16x4 res = *reinterpret_cast<const bf16x4*>(a.residual + o);
 #pragma unroll
@@ -247,6 +265,21 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   }
 }
 
+// out = bf16(sum over the k splits in ascending order (+ residual)); 4 outputs per thread
+__global__ __launch_bounds__(256) void linear_reduce_kernel(const float* __restrict__ part, const __bf16* residual,
+                                                            __bf16* out, size_t n, int ksplit) {
+  const size_t i = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
+  if (i >= n) return;
+  f32x4 sum = *reinterpret_cast<const f32x4*>(part + i);
+  for (int ks = 1; ks < ksplit; ++ks) sum += *reinterpret_cast<const f32x4*>(part + static_cast<size_t>(ks) * n + i);
+  if (residual) {
+    const bf16x4 res = *reinterpret_cast<const bf16x4*>(residual + i);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sum[e] += static_cast<float>(res[e]);
+  }
+  *reinterpret_cast<bf16x4*>(out + i) = __builtin_convertvector(sum, bf16x4);
+}
+
 // Row-major bf16 [V, Hd] -> [ceil(V/128)][Hd/64][128][64] tiles, 16 bytes per thread; rows past V become zero.
 __global__ __launch_bounds__(256) void pack_w_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int V, int Hd,
                                                      size_t n16) {
@@ -274,7 +307,7 @@ int launch_variant(const LmArgs& a, const LmPlan& plan, hipStream_t stream) {
     if (e != hipSuccess) return hip_failed(e);
     attr_set = true;
   }
-  const unsigned grid = static_cast<unsigned>((plan.nslab + 7) / 8) * 8u * plan.nrtile;
+  const unsigned grid = static_cast<unsigned>((plan.nslab + 7) / 8) * 8u * plan.nrtile * (kStore ? a.ksplit : 1);
   hipLaunchKernelGGL((lmhead_bf16_kernel<MT, NT, kStore>), dim3(grid), dim3(256), C::kLdsBytes, stream, a);
   return check_launch();
 }
@@ -304,6 +337,22 @@ int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_
   return launch_variant<4, 4, false>(a, plan, stream);
 }
 
+// Split of the k range of a projection over workgroups: enough of them to occupy the chip, at least 8 k-tiles each.
+int linear_ksplit(int R, int K, int N) {
+  const int nrtile = R <= 64 ? 1 : (R + 127) / 128;
+  const long wgs = static_cast<long>((N + 127) / 128) * nrtile;
+  long ks = std::max<long>(1, 256 / std::max<long>(wgs, 1));
+  ks = std::min<long>(ks, std::max(1, K / 64 / 8));
+  const char* env = std::getenv("OURO_LINEAR_KSPLIT");
+  if (env && *env) ks = std::max(1L, std::min<long>(std::atol(env), K / 64));
+  return static_cast<int>(ks);
+}
+
+size_t linear_workspace_bytes(int R, int K, int N) {
+  const int ks = linear_ksplit(R, K, N);
+  return ks > 1 ? static_cast<size_t>(ks) * R * N * sizeof(float) : 0;
+}
+
 int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream) {
   LmArgs a{};
   a.hidden = static_cast<const __bf16*>(d.x);
@@ -314,18 +363,27 @@ int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream) {
   a.tiled = d.w_layout == OURO_W_TILED;
   a.out = static_cast<__bf16*>(d.out);
   a.residual = static_cast<const __bf16*>(d.residual);
+  a.ksplit = linear_ksplit(d.R, d.K, d.N);
+  a.part_f32 = static_cast<float*>(d.workspace);
   LmPlan plan{};
   plan.slab = 128;
   plan.nslab = (d.N + 127) / 128;
   a.nslab = plan.nslab;
+  int st;
   if (d.R <= 64) {
     plan.rtile = 64;
     a.nrtile = plan.nrtile = 1;
-    return launch_variant<4, 2, true>(a, plan, stream);
+    st = launch_variant<4, 2, true>(a, plan, stream);
+  } else {
+    plan.rtile = 128;                             // more rows: 128-row tiles; the tiles of a slab share an XCD's L2
+    a.nrtile = plan.nrtile = (d.R + 127) / 128;
+    st = launch_variant<4, 4, true>(a, plan, stream);
   }
-  plan.rtile = 128;                               // more rows: 128-row tiles; the tiles of a slab share an XCD's L2
-  a.nrtile = plan.nrtile = (d.R + 127) / 128;
-  return launch_variant<4, 4, true>(a, plan, stream);
+  if (st != OURO_OK || a.ksplit == 1) return st;
+  const size_t n = static_cast<size_t>(d.R) * d.N;
+  hipLaunchKernelGGL(linear_reduce_kernel, dim3(static_cast<unsigned>((n / 4 + 255) / 256)), dim3(256), 0, stream,
+                     a.part_f32, a.residual, a.out, n, a.ksplit);
+  return check_launch();
 }
 
 }  // namespace ouro

@@ -255,15 +255,32 @@ int ouro_rmsnorm(const ouro_rmsnorm_desc* d, void* hip_stream) {
   return launch_rmsnorm(*d, static_cast<hipStream_t>(hip_stream));
 }
 
-int ouro_linear(const ouro_linear_desc* d, void* hip_stream) {
+static int validate_linear(const ouro_linear_desc* d) {
   if (!d) return OURO_E_NULLPTR;
   if (d->struct_size != sizeof(ouro_linear_desc)) return OURO_E_BAD_STRUCT;
   if (d->dtype != OURO_BF16) return OURO_E_UNSUPPORTED_DTYPE;
   if (d->R < 0 || d->K < 64 || d->K % 64 != 0 || d->N < 8 || d->N % 8 != 0) return OURO_E_BAD_SHAPE;
   if (d->w_layout != OURO_W_ROW_MAJOR && d->w_layout != OURO_W_TILED) return OURO_E_BAD_SHAPE;
+  return OURO_OK;
+}
+
+size_t ouro_linear_workspace(const ouro_linear_desc* d) {
+  if (validate_linear(d) != OURO_OK || d->R == 0) return 0;
+  return linear_workspace_bytes(d->R, d->K, d->N);
+}
+
+int ouro_linear(const ouro_linear_desc* d, void* hip_stream) {
+  int st = validate_linear(d);
+  if (st != OURO_OK) return st;
   if (d->R == 0) return OURO_OK;
   if (!d->x || !d->w || !d->out) return OURO_E_NULLPTR;
-  if (!aligned16(d->x) || !aligned16(d->w) || !aligned16(d->out) || !aligned16(d->residual)) return OURO_E_MISALIGNED;
+  if (!aligned16(d->x) || !aligned16(d->w) || !aligned16(d->out) || !aligned16(d->residual) || !aligned16(d->workspace))
+    return OURO_E_MISALIGNED;
+  const size_t need = linear_workspace_bytes(d->R, d->K, d->N);
+  if (need > 0) {
+    if (!d->workspace) return OURO_E_NULLPTR;
+    if (d->workspace_bytes < need) return OURO_E_WORKSPACE_TOO_SMALL;
+  }
   return launch_linear_bf16(*d, static_cast<hipStream_t>(hip_stream));
 }
 

@@ -63,5 +63,6 @@ int launch_rope_block(const ouro_rope_desc& d, hipStream_t stream);
 int launch_rmsnorm(const ouro_rmsnorm_desc& d, hipStream_t stream);
 int launch_silu_mul(const ouro_silu_mul_desc& d, hipStream_t stream);
 int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream);
+size_t linear_workspace_bytes(int R, int K, int N);
 
 }  // namespace ouro

@@ -89,6 +89,19 @@ def test_linear(R, K, N, tiled, with_res):
     assert np.abs(to_np64(out) - ref).max() <= tol
 
 
+@pytest.mark.parametrize("ksplit", [2, 3, 5])
+def test_linear_uneven_k_split(monkeypatch, ksplit):
+    """The k range split over workgroups, including splits that do not divide the 5 k-tiles evenly (one share empty)."""
+    monkeypatch.setenv("OURO_LINEAR_KSPLIT", str(ksplit))
+    rng = np.random.default_rng(ksplit)
+    x, w, res = _bf(rng.standard_normal((70, 320))), _bf(rng.standard_normal((264, 320)) * 0.05), _bf(rng.standard_normal((70, 264)))
+    ref = LO.linear(x, w, res)
+    ws = torch.full((ksplit * 70 * 264 * 4,), 0xA5, dtype=torch.uint8, device=DEV)     # contents must not matter
+    out = ob.ouro_linear(_up(x), _up(w), residual=_up(res), workspace=ws)
+    torch.cuda.synchronize()
+    assert np.abs(to_np64(out) - ref).max() <= np.abs(ref).max() * BF16_EPS + 1e-4
+
+
 def test_one_verifying_layer_chained_on_the_gpu():
     """x -> RMSNorm -> fused QKV projection -> rotary embedding at the draft positions -> draft-block attention ->
     output projection + residual -> RMSNorm -> fused gate/up projection -> SwiGLU -> down projection + residual.
