@@ -1,9 +1,14 @@
-// bf16 draft-block attention for gfx950: split-KV with in-workgroup key splitting.
+// bf16 draft-block attention for gfx950: split-KV flash-style kernels.
 //
 // What is computed (Sec. 3.2, Eq. (8)): every block row attends to the whole cached prefix
 // of its sequence plus the block tokens of its own lengthened draft.  The block part of the
-// mask is evaluated from per-token (phrase_id, branch_off) pairs in registers; only the
-// key tiles that overlap the block (the last T keys) pay for it, cache tiles are mask-free.
+// mask is evaluated from per-token (phrase_id, branch_off) pairs (the row's pair in registers,
+// the phrase ids of the block keys in a small LDS table); only the key tiles that overlap the
+// block (the last T keys) pay for it, cache tiles are mask-free.
+//
+// Two kernels share the tile building blocks below: attn_bf16_kernel (the waves of a workgroup
+// split the keys; described next) and attn_bf16_rows_kernel (the waves split the query rows and
+// share the staged tiles; described where it is defined).
 //
 // Work decomposition.  Query rows of one (sequence, KV head) are the T*G rows of the G query
 // heads sharing that KV head (row = t*G + head_in_group), cut into row blocks of 32 rows.
