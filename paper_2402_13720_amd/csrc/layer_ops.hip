@@ -38,48 +38,118 @@ __device__ int depth_of(const ouro_tok_meta* meta, int t) {
 // One workgroup per (sequence, block token); threads sweep (head, rotation pair) of q and then of k.
 template <typename T>
 __global__ __launch_bounds__(256) void rope_block_kernel(ouro_rope_desc d, float log2_base) {
+  __shared__ ouro_tok_meta smeta[128];                  // the sequence's block metadata: the walk below stays in LDS
   const int b = blockIdx.x / d.T, t = blockIdx.x - b * d.T;
+  for (int i = threadIdx.x; i <= t; i += 256) smeta[i] = d.meta[static_cast<size_t>(b) * d.T + i];
   const int L = d.seq_len ? d.seq_len[b] : static_cast<int>(d.cu_seqlens[b + 1] - d.cu_seqlens[b]);
-  const int pos = L + depth_of(d.meta + static_cast<size_t>(b) * d.T, t);
+  __syncthreads();
+  const int pos = L + depth_of(smeta, t);
   if (d.positions && threadIdx.x == 0) d.positions[blockIdx.x] = pos;
   const int half = d.D / 2;
   T* q = static_cast<T*>(d.q) + static_cast<size_t>(blockIdx.x) * d.Hq * d.D;
   T* k = static_cast<T*>(d.k_blk) + static_cast<size_t>(blockIdx.x) * d.Hkv * d.D;
-  const int nq = d.Hq * half, nk = d.Hkv * half;
-  for (int p = threadIdx.x; p < nq + nk; p += 256) {
-    const bool is_q = p < nq;
-    const int pp = is_q ? p : p - nq;
-    const int h = pp / half, i = pp - h * half;
-    T* x = (is_q ? q : k) + static_cast<size_t>(h) * d.D;
-    // angle = pos * base^(-2i/D); the argument can be thousands of radians: full-range sincosf
-    const float inv = exp2f(-2.0f * static_cast<float>(i) / static_cast<float>(d.D) * log2_base);
-    float s, c;
-    sincosf(static_cast<float>(pos) * inv, &s, &c);
-    const float x0 = Elem<T>::load(x + i), x1 = Elem<T>::load(x + i + half);
-    Elem<T>::store(x + i, x0 * c - x1 * s);
-    Elem<T>::store(x + i + half, x1 * c + x0 * s);
+  // angle = pos * base^(-2i/D) can be thousands of radians: it is formed and reduced to [-pi, pi] in fp64
+  // (a handful of fp64 operations per pair), after which the fast fp32 sine/cosine are accurate to ~1e-6
+#define OURO_ROPE_SINCOS(I, S, C)                                                                              \
+  {                                                                                                            \
+    const float inv_ = exp2f(-2.0f * static_cast<float>(I) / static_cast<float>(d.D) * log2_base);             \
+    const double ang_ = static_cast<double>(pos) * static_cast<double>(inv_);                                  \
+    const float red_ = static_cast<float>(ang_ - 6.283185307179586 * rint(ang_ * 0.15915494309189535));        \
+    S = __sinf(red_);                                                                                          \
+    C = __cosf(red_);                                                                                          \
   }
+  typedef T vec8 __attribute__((ext_vector_type(8)));
+  const bool vec = half % 8 == 0 && ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k)) & 15) == 0;
+  if (vec) {
+    // work item = 8 consecutive rotation pairs of one head: two 16-byte (bf16) vectors in, two out
+    const int per_head = half / 8;
+    const int nq = d.Hq * per_head, nk = d.Hkv * per_head;
+    for (int p = threadIdx.x; p < nq + nk; p += 256) {
+      const bool is_q = p < nq;
+      const int pp = is_q ? p : p - nq;
+      const int h = pp / per_head, i0 = (pp - h * per_head) * 8;
+      T* x = (is_q ? q : k) + static_cast<size_t>(h) * d.D + i0;
+      const vec8 a = *reinterpret_cast<const vec8*>(x), bb = *reinterpret_cast<const vec8*>(x + half);
+      vec8 oa, ob;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float sn, cs;
+        OURO_ROPE_SINCOS(i0 + e, sn, cs)
+        const float x0 = static_cast<float>(a[e]), x1 = static_cast<float>(bb[e]);
+        oa[e] = static_cast<T>(x0 * cs - x1 * sn);
+        ob[e] = static_cast<T>(x1 * cs + x0 * sn);
+      }
+      *reinterpret_cast<vec8*>(x) = oa;
+      *reinterpret_cast<vec8*>(x + half) = ob;
+    }
+  } else {
+    const int nq = d.Hq * half, nk = d.Hkv * half;
+    for (int p = threadIdx.x; p < nq + nk; p += 256) {
+      const bool is_q = p < nq;
+      const int pp = is_q ? p : p - nq;
+      const int h = pp / half, i = pp - h * half;
+      T* x = (is_q ? q : k) + static_cast<size_t>(h) * d.D;
+      float sn, cs;
+      OURO_ROPE_SINCOS(i, sn, cs)
+      const float x0 = Elem<T>::load(x + i), x1 = Elem<T>::load(x + i + half);
+      Elem<T>::store(x + i, x0 * cs - x1 * sn);
+      Elem<T>::store(x + i + half, x1 * cs + x0 * sn);
+    }
+  }
+#undef OURO_ROPE_SINCOS
 }
 
-// One workgroup per row: sum of squares (fp32, fixed reduction order), then scale by the gain.
+// One workgroup per row: sum of squares (fp32, fixed reduction order), then scale by the gain.  The row is read
+// once, 8 elements (16 or 32 bytes) per thread and step, and kept in registers when it fits (Hd <= 8192).
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(ouro_rmsnorm_desc d) {
   __shared__ float part[4];
+  constexpr int kKeep = 4;                                // steps of 2048 elements held in registers
   const int r = blockIdx.x;
   const T* x = static_cast<const T*>(d.x) + static_cast<size_t>(r) * d.Hd;
   const T* g = static_cast<const T*>(d.gain);
   T* y = static_cast<T*>(d.out) + static_cast<size_t>(r) * d.Hd;
+  const bool vec = d.Hd % 8 == 0 && d.Hd <= kKeep * 2048 &&
+                   ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(y)) & 15) == 0;
+  typedef T vec8 __attribute__((ext_vector_type(8)));
+  vec8 keep[kKeep];
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d.Hd; i += 256) {
-    const float v = Elem<T>::load(x + i);
-    ss += v * v;
+  if (vec) {
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) {
+      const int i = (k * 256 + threadIdx.x) * 8;
+      if (i < d.Hd) {
+        keep[k] = *reinterpret_cast<const vec8*>(x + i);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const float v = static_cast<float>(keep[k][e]); ss += v * v; }
+      }
+    }
+  } else {
+    for (int i = threadIdx.x; i < d.Hd; i += 256) {
+      const float v = Elem<T>::load(x + i);
+      ss += v * v;
+    }
   }
   for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
   __syncthreads();
   const float tot = (part[0] + part[1]) + (part[2] + part[3]);
   const float scale = 1.0f / sqrtf(tot / static_cast<float>(d.Hd) + d.eps);
-  for (int i = threadIdx.x; i < d.Hd; i += 256) Elem<T>::store(y + i, Elem<T>::load(x + i) * scale * Elem<T>::load(g + i));
+  if (vec) {
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) {
+      const int i = (k * 256 + threadIdx.x) * 8;
+      if (i < d.Hd) {
+        const vec8 gv = *reinterpret_cast<const vec8*>(g + i);
+        vec8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = static_cast<T>(static_cast<float>(keep[k][e]) * scale * static_cast<float>(gv[e]));
+        *reinterpret_cast<vec8*>(y + i) = o;
+      }
+    }
+  } else {
+    for (int i = threadIdx.x; i < d.Hd; i += 256) Elem<T>::store(y + i, Elem<T>::load(x + i) * scale * Elem<T>::load(g + i));
+  }
 }
 
 // out[r, f] = silu(gate_up[r, f]) * gate_up[r, F + f]
