@@ -247,24 +247,26 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   unsigned char* kl = lds + kQBytes + wave * kWaveLds;
   unsigned char* vl = kl + kKBytes;
   short* kpid = reinterpret_cast<short*>(lds + kMainLds);
-  for (int i = tid; i < T; i += 256) kpid[i] = a.meta[static_cast<size_t>(b) * T + i].phrase_id;
   const int col = lane & 31, half = lane >> 5;
   const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
   const int row0 = rb * kRows;
 
-  // ---- Q tile -> LDS (coalesced: 16 lanes per 256-byte row), read back as the B operand of S^T = K . Q^T ----
-  for (int p = tid; p < kRows * 16; p += 256) {
+  // ---- prologue loads: all of them are issued before anything waits, so that the workgroup pays one memory
+  // round trip, not one per item (phrase ids of the block keys, the Q tile, this lane's metadata, the first tile)
+  const short my_kpid = tid < T ? a.meta[static_cast<size_t>(b) * T + tid].phrase_id : static_cast<short>(0);
+  u32x4 qreg[kRows * 16 / 256];                   // Q tile: 16 lanes per 256-byte row, 2 pieces per thread
+#pragma unroll
+  for (int u = 0; u < kRows * 16 / 256; ++u) {
+    const int p = tid + 256 * u;
     const int row = p >> 4, c = p & 15;
     const int rr = min(row0 + row, M - 1);        // rows past M are computed on a duplicate and never stored
     const int t = rr / G, hh = rr - t * G;
-    const __bf16* qp = a.q + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
-    *reinterpret_cast<u32x4*>(ql + k_slot(row, c) * 16) = *reinterpret_cast<const u32x4*>(qp + 8 * c);
+    qreg[u] = *reinterpret_cast<const u32x4*>(a.q + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD + 8 * c);
   }
   // this lane's query row (its column of S^T) and that row's metadata
   const int rq = min(row0 + col, M - 1);
   const int tq = rq / G;
   const ouro_tok_meta mq = a.meta[static_cast<size_t>(b) * T + tq];
-  const int pidq = mq.phrase_id, boffq = mq.branch_off;
 
   // ---- staging: lane (kq = lane/16, c16 = lane%16) loads 16 B of 8 key rows per tile ----
   // Load i of a lane fetches key 4*i + kq of the tile, so one load instruction covers 4 adjacent
@@ -290,6 +292,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   // this wave's tiles: k_begin + 32*(wave + 4*i)
   int tile = k_begin + 32 * wave;
   if (tile < k_end) { OURO_ATTN_ISSUE_LOADS(tile, kr, vr) }
+  // ---- Q tile and phrase-id table -> LDS (the Q tile is read back as the B operand of S^T = K . Q^T) ----
+  __builtin_amdgcn_sched_barrier(0);              // keep the stores (and their waits) behind every load above
+  const int pidq = mq.phrase_id, boffq = mq.branch_off;
+  if (tid < T) kpid[tid] = my_kpid;
+#pragma unroll
+  for (int u = 0; u < kRows * 16 / 256; ++u) {
+    const int p = tid + 256 * u;
+    *reinterpret_cast<u32x4*>(ql + k_slot(p >> 4, p & 15) * 16) = qreg[u];
+  }
   __syncthreads();                                // Q tile complete
   for (; tile < k_end; tile += 128) {
     OURO_ATTN_STORE_TILE(kl, vl, kr, vr)
@@ -511,7 +522,7 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
 
   constexpr int kStageBytes4 = 4 * kWaveLds;      // one stage: 4 x (K tile, V^T tile)
   short* kpid = reinterpret_cast<short*>(lds + rows_main_lds<RW>());
-  for (int i = tid; i < T; i += 256) kpid[i] = a.meta[static_cast<size_t>(b) * T + i].phrase_id;
+  const short my_kpid = tid < T ? a.meta[static_cast<size_t>(b) * T + tid].phrase_id : static_cast<short>(0);
   const int col = lane & 31, half = lane >> 5;
   const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
   const int row0 = rb * kRowsWg + 32 * rw;        // first row of this wave's block (may lie past M: duplicates)
@@ -550,8 +561,10 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
     if ((PH) == 2) { OURO_ATTN_STORE_V(nk_ + kKBytes, vr, 4, 8) OURO_ATTN_ISSUE_V(NEXT, vr) }                      \
   }
 
-  // prologue: stage 0 -> buffer 0, stage 1 in flight
+  // prologue: stage 0 -> buffer 0, stage 1 in flight (every prologue load is issued before anything waits)
   OURO_ATTN_ISSUE_LOADS(k_begin + 32 * wave, kr, vr)
+  __builtin_amdgcn_sched_barrier(0);
+  if (tid < T) kpid[tid] = my_kpid;
   {
     unsigned char* kl = lds + wave * kWaveLds;
     OURO_ATTN_STORE_K(kl, kr)
