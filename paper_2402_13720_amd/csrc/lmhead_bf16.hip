@@ -80,11 +80,12 @@ struct LmCfg {
 // kStore = false: LM head, the epilogue reduces to one (value, id) pair per (slab, row).
 // kStore = true: the same streaming product as a plain projection x . W^T, the epilogue writes the bf16 outputs
 // (optionally adding a residual): the other weight matrices of the verifying layer are streamed the same way.
-template <int MT, int NT, bool kStore>
+// kTiled: W is in the tiled layout (every slab padded to 128 rows), else row-major.
+template <int MT, int NT, bool kStore, bool kTiled>
 __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   using C = LmCfg<MT, NT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int col = lane & 31, half = lane >> 5;
   // workgroup id -> (slab, row tile): the row tiles of one slab sit 8 ids apart, i.e. run at the same time on the
   // same XCD and share its L2, so that W still comes from HBM once when R needs several row tiles
@@ -101,30 +102,51 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   unsigned char* wl = lds + wave * C::kWaveLds;
   unsigned char* hl = wl + C::kWRows * 128;
 
-  // lane (lr = lane/8, lc = lane%8) moves chunk lc of rows 8*p + lr
+  // lane (lr = lane/8, lc = lane%8) moves chunk lc of rows 8*p + lr.  Addresses = one uniform base per operand +
+  // a per-lane 32-bit element offset per row (fixed for the whole kernel) + the k-tile step.
   const int lr = lane >> 3, lc = lane & 7;
-  u32x4 wreg[MT * 4], hreg[NT * 4];
-  // Row pointers of this lane are fixed for the whole kernel; only the k offset moves.
-  const __bf16* wrow[MT * 4];
-  const __bf16* hrow[NT * 4];
-  // Row-major W: row pointers, k-tile kt at +64*kt.  Tiled W: the slab's tiles are contiguous 16 KB blocks,
-  // row r of k-tile kt at (kt*128 + r)*64, so one load instruction of the wave reads 1 KB contiguous.
-  const size_t wstep = a.tiled ? 128 * 64 : 64;
+  // Row-major W: k-tile kt at +64*kt.  Tiled W: the slab's tiles are contiguous 16 KB blocks, row r of k-tile kt at
+  // (kt*128 + r)*64, so one load instruction of the wave reads 1 KB contiguous.
+  // Loads go through raw buffer descriptors (one per operand, covering exactly the rows this workgroup reads):
+  // address = descriptor base + 32-bit per-lane byte offset (fixed for the whole kernel) + wave-uniform offset
+  // (k-tile, and for the padded tiled layout also the row group), so no 64-bit address arithmetic or pointer
+  // registers live in the loop.  Row-major W and the hidden rows need a per-row clamp (rows past V or R: duplicate
+  // of the last one, masked or unused later) and keep one offset register per row group.
+  const unsigned wstep = kTiled ? 128 * 64 * 2 : 64 * 2;
+  const __bf16* wptr = kTiled ? a.w + static_cast<size_t>(slab) * (Hd / 64) * 128 * 64 : a.w + static_cast<size_t>(slab0) * Hd;
+  const unsigned wbytes = static_cast<unsigned>(kTiled ? 128 : min(C::kWRows, V - slab0)) * static_cast<unsigned>(Hd) * 2u;
+  const unsigned hbytes = static_cast<unsigned>(min(C::kHRows, R - r0)) * static_cast<unsigned>(Hd) * 2u;
+  const __amdgpu_buffer_rsrc_t wbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(wptr), 0, wbytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t hbuf =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.hidden + static_cast<size_t>(r0) * Hd), 0, hbytes, 0x00020000);
+  unsigned woff[kTiled ? 1 : MT * 4], hoff[NT * 4];
+  if constexpr (kTiled) {
+    woff[0] = static_cast<unsigned>(lr * 128 + 16 * lc);
+  } else {
 #pragma unroll
-  for (int p = 0; p < MT * 4; ++p)
-    wrow[p] = a.tiled ? a.w + (static_cast<size_t>(slab) * (Hd / 64) * 128 + 8 * p + lr) * 64 + 8 * lc
-                      : a.w + static_cast<size_t>(min(slab0 + 8 * p + lr, V - 1)) * Hd + 8 * lc;   // rows past V: duplicate, masked later
+    for (int p = 0; p < MT * 4; ++p)
+      woff[p] = static_cast<unsigned>(min(8 * p + lr, V - 1 - slab0)) * static_cast<unsigned>(Hd * 2) + 16 * lc;
+  }
 #pragma unroll
   for (int p = 0; p < NT * 4; ++p)
-    hrow[p] = a.hidden + static_cast<size_t>(min(r0 + 8 * p + lr, R - 1)) * Hd + 8 * lc;
-#define OURO_LM_ISSUE_LOADS(KT)                                                            \
-  {                                                                                        \
-    const size_t koff = static_cast<size_t>(KT) * 64;                                      \
-    _Pragma("unroll") for (int p = 0; p < MT * 4; ++p)                                     \
-        wreg[p] = *reinterpret_cast<const u32x4*>(wrow[p] + static_cast<size_t>(KT) * wstep); \
-    _Pragma("unroll") for (int p = 0; p < NT * 4; ++p)                                     \
-        hreg[p] = *reinterpret_cast<const u32x4*>(hrow[p] + koff);                         \
-  }
+    hoff[p] = static_cast<unsigned>(min(8 * p + lr, R - 1 - r0)) * static_cast<unsigned>(Hd * 2) + 16 * lc;
+#define OURO_LM_WLOAD(P, KT) \
+  __builtin_amdgcn_raw_buffer_load_b128(wbuf, woff[kTiled ? 0 : (P)], (KT) * wstep + (kTiled ? (P) * 1024 : 0), 0)
+  // LDS slot of (row 8p + lr, chunk lc): the swizzle term depends on p only through its parity
+  const unsigned lds_even = static_cast<unsigned>(lr * 128 + ((lc ^ ((lr >> 1) & 7)) * 16));
+  const unsigned lds_odd = static_cast<unsigned>(lr * 128 + ((lc ^ (((lr >> 1) + 4) & 7)) * 16));
+#define OURO_LM_LDS_SLOT(P) ((((P) & 1) ? lds_odd : lds_even) + (P) * 1024)
+
+  // W is the stream that comes from HBM: two k-tiles of it are in flight per wave (two staging sets, if the
+  // registers allow: kWSets), one k-tile of the hidden rows (they come from L2).
+  constexpr int kWSets = (C::kTiles <= 8 && kTiled) ? 2 : 1;
+  u32x4 wreg[kWSets][MT * 4], hreg[NT * 4];
+#define OURO_LM_LOAD_W(SET, KT)                                                                       \
+  _Pragma("unroll") for (int p = 0; p < MT * 4; ++p)                                                  \
+      wreg[SET][p] = OURO_LM_WLOAD(p, KT);
+#define OURO_LM_LOAD_H(KT)                                                                            \
+  _Pragma("unroll") for (int p = 0; p < NT * 4; ++p)                                                  \
+      hreg[p] = __builtin_amdgcn_raw_buffer_load_b128(hbuf, hoff[p], (KT) * 128, 0);
 
   f32x16 acc[MT][NT];
 #pragma unroll
@@ -134,51 +156,70 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.f;
 
-  // this workgroup's k-tiles: all of them, or its share of an even split
+  // this workgroup's k-tiles: all of them, or its share of an even split; this wave's: first + 4*j, j = 0..nj-1
   const int nkt_all = Hd / 64;
   const int kt_per = kStore ? (nkt_all + a.ksplit - 1) / a.ksplit : nkt_all;
   const int kt0 = ks * kt_per;
   const int nkt = min(nkt_all, kt0 + kt_per);
-  int kt = kt0 + wave;
-  if (kt < nkt) OURO_LM_ISSUE_LOADS(kt)
-  for (; kt < nkt; kt += 4) {
-    // Each staging register is copied to LDS and immediately re-armed with its load of the wave's next
-    // k-tile, so the memory queue of the wave is never empty while the tile is being written (the last
-    // iteration harmlessly re-reads its own tile).
-    const size_t ktn = static_cast<size_t>(kt + 4 < nkt ? kt + 4 : kt);
-    const size_t knext = ktn * 64, wnext = ktn * wstep;
-#pragma unroll
-    for (int p = 0; p < MT * 4; ++p) {
-      *reinterpret_cast<u32x4*>(wl + tile_slot(8 * p + lr, lc) * 16) = wreg[p];
-      wreg[p] = *reinterpret_cast<const u32x4*>(wrow[p] + wnext);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int p = 0; p < NT * 4; ++p) {
-      *reinterpret_cast<u32x4*>(hl + tile_slot(8 * p + lr, lc) * 16) = hreg[p];
-      hreg[p] = *reinterpret_cast<const u32x4*>(hrow[p] + knext);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    wave_lds_fence();
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      bf16x8 af[MT], bf[NT];
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        af[mt] = *reinterpret_cast<const bf16x8*>(wl + tile_slot(32 * mt + col, 2 * s + half) * 16);
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        bf[nt] = *reinterpret_cast<const bf16x8*>(hl + tile_slot(32 * nt + col, 2 * s + half) * 16);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bf[nt], acc[mt][nt], 0, 0, 0);
-    }
-    wave_lds_fence();
+  const int first = kt0 + wave;
+  const int nj = first < nkt ? (nkt - first + 3) / 4 : 0;
+  const int last = first + 4 * max(nj - 1, 0);            // loads past the wave's share re-read this tile (harmless)
+  const int kt_safe = min(last, nkt_all - 1);
+
+// One k-tile: staging registers (W set SET, hidden rows) -> this wave's LDS tiles, each register re-armed at once with
+// its next load (W: KT_W, the tile kWSets steps ahead; hidden: KT_H, the next tile), then the MFMAs.  Loads and stores
+// are unconditional so that the compiler's counted waits stay exact; only the MFMAs of a step past the end are skipped.
+#define OURO_LM_KTILE(SET, KT_W, KT_H, VALID)                                                         \
+  {                                                                                                   \
+    _Pragma("unroll") for (int p = 0; p < MT * 4; ++p) {                                              \
+      *reinterpret_cast<u32x4*>(wl + OURO_LM_LDS_SLOT(p)) = wreg[SET][p];                             \
+      wreg[SET][p] = OURO_LM_WLOAD(p, KT_W);                                                          \
+      __builtin_amdgcn_sched_barrier(0);                                                              \
+    }                                                                                                 \
+    _Pragma("unroll") for (int p = 0; p < NT * 4; ++p) {                                              \
+      *reinterpret_cast<u32x4*>(hl + OURO_LM_LDS_SLOT(p)) = hreg[p];                                  \
+      hreg[p] = __builtin_amdgcn_raw_buffer_load_b128(hbuf, hoff[p], (KT_H) * 128, 0);                \
+      __builtin_amdgcn_sched_barrier(0);                                                              \
+    }                                                                                                 \
+    wave_lds_fence();                                                                                 \
+    if (VALID) {                                                                                      \
+      _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                                 \
+        bf16x8 af[MT], bf[NT];                                                                        \
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                             \
+            af[mt] = *reinterpret_cast<const bf16x8*>(wl + tile_slot(32 * mt + col, 2 * s + half) * 16); \
+        _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                             \
+            bf[nt] = *reinterpret_cast<const bf16x8*>(hl + tile_slot(32 * nt + col, 2 * s + half) * 16); \
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                             \
+            _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                         \
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bf[nt], acc[mt][nt], 0, 0, 0); \
+      }                                                                                               \
+    }                                                                                                 \
+    wave_lds_fence();                                                                                 \
   }
 
-#undef OURO_LM_ISSUE_LOADS
+  if (nj > 0) {
+    OURO_LM_LOAD_W(0, first)
+    if (kWSets == 2) { OURO_LM_LOAD_W(kWSets - 1, min(first + 4, kt_safe)) }
+    OURO_LM_LOAD_H(first)
+    if (kWSets == 2) {
+      for (int j = 0; j < nj; j += 2) {
+        const int t0 = first + 4 * j;
+        OURO_LM_KTILE(0, min(t0 + 8, kt_safe), min(t0 + 4, kt_safe), true)
+        OURO_LM_KTILE(kWSets - 1, min(t0 + 12, kt_safe), min(t0 + 8, kt_safe), j + 1 < nj)
+      }
+    } else {
+      for (int j = 0; j < nj; ++j) {
+        const int t0 = first + 4 * j;
+        OURO_LM_KTILE(0, min(t0 + 4, kt_safe), min(t0 + 4, kt_safe), true)
+      }
+    }
+  }
+#undef OURO_LM_KTILE
+#undef OURO_LM_LOAD_W
+#undef OURO_LM_LOAD_H
+#undef OURO_LM_WLOAD
+#undef OURO_LM_LDS_SLOT
+
 
   // ---- sum the 4 waves' accumulators, 4 tiles per round; wave w reduces tile 4*round + w ----
   float* bestv = reinterpret_cast<float*>(lds + C::kBestOff);
@@ -297,19 +338,25 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const u32x4* __restrict__ s
   dst[i] = x;
 }
 
-template <int MT, int NT, bool kStore>
-int launch_variant(const LmArgs& a, const LmPlan& plan, hipStream_t stream) {
+template <int MT, int NT, bool kStore, bool kTiled>
+int launch_instance(const LmArgs& a, const LmPlan& plan, hipStream_t stream) {
   using C = LmCfg<MT, NT>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_bf16_kernel<MT, NT, kStore>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_bf16_kernel<MT, NT, kStore, kTiled>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
     if (e != hipSuccess) return hip_failed(e);
     attr_set = true;
   }
   const unsigned grid = static_cast<unsigned>((plan.nslab + 7) / 8) * 8u * plan.nrtile * (kStore ? a.ksplit : 1);
-  hipLaunchKernelGGL((lmhead_bf16_kernel<MT, NT, kStore>), dim3(grid), dim3(256), C::kLdsBytes, stream, a);
+  hipLaunchKernelGGL((lmhead_bf16_kernel<MT, NT, kStore, kTiled>), dim3(grid), dim3(256), C::kLdsBytes, stream, a);
   return check_launch();
+}
+
+template <int MT, int NT, bool kStore>
+int launch_variant(const LmArgs& a, const LmPlan& plan, hipStream_t stream) {
+  return a.tiled ? launch_instance<MT, NT, kStore, true>(a, plan, stream)
+                 : launch_instance<MT, NT, kStore, false>(a, plan, stream);
 }
 
 }  // namespace
