@@ -10,9 +10,10 @@
 //     (split-K inside the workgroup), so the waves never synchronise in the main loop and
 //     together read 512 contiguous bytes of every W row per round;
 //   * per k-tile a wave moves its W tile (MT*32 x 64) and hidden tile (NT*32 x 64) with
-//     coalesced 16-byte loads into registers, then into its private XOR-swizzled LDS
-//     region, and issues MT*NT v_mfma_f32_32x32x16_bf16 per 16-wide k step; the loads of
-//     the wave's next k-tile are issued before the math of the current one;
+//     coalesced 16-byte buffer loads into registers, then into its private XOR-swizzled LDS
+//     region, and issues MT*NT v_mfma_f32_32x32x16_bf16 per 16-wide k step; every staging
+//     register is re-armed with its next load right after its LDS write (W two k-tiles
+//     ahead where the registers allow, the L2-resident hidden rows one);
 //   * after the loop the 4 partial accumulator sets are summed through LDS (fixed order),
 //     and the arg-max epilogue reduces lane -> wave -> workgroup; one (value, index) pair
 //     per (slab, row) goes to the workspace, the logits never leave the chip;
