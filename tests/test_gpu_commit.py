@@ -135,3 +135,26 @@ def test_two_steps_of_the_loop():
         assert np.array_equal(kd.float().cpu().numpy(), ref["k_cache"])
         assert np.array_equal(vd.float().cpu().numpy(), ref["v_cache"])
         k_h, v_h, len_h = ref["k_cache"], ref["v_cache"], ref["seq_len"]
+
+
+def test_commit_edge_cases():
+    """Nothing accepted anywhere; many sequences; a one-token block; B = 0 is a no-op."""
+    rng = np.random.default_rng(21)
+    cfg = W.scaled(W.CONFIGS[2], B=300, Hq=2, Hkv=2, L=(0, 6), gamma=1, K=0, beta_p=0)       # T = 1
+    inp = W.make_attention_inputs(cfg, 77)
+    k, v, cu, lens = _roomy(cfg, inp, 1, rng)
+    for n_acc in (np.zeros(cfg.B, dtype=np.int32), np.ones(cfg.B, dtype=np.int32)):
+        idx = np.zeros((cfg.B, 1), dtype=np.int32)
+        ref = O.kv_commit(k, v, cu, lens, inp["k_blk"], inp["v_blk"], idx, n_acc)
+        kd, vd = _up(k, cfg), _up(v, cfg)
+        len_d = torch.from_numpy(lens.astype(np.int32)).to(DEV)
+        ovf = ob.ouro_kv_commit(_up(inp["k_blk"], cfg), _up(inp["v_blk"], cfg), torch.from_numpy(idx).to(DEV),
+                                torch.from_numpy(n_acc).to(DEV), kd, vd, torch.from_numpy(cu).to(DEV), len_d)
+        torch.cuda.synchronize()
+        assert not ovf.cpu().numpy().any()
+        assert np.array_equal(len_d.cpu().numpy(), ref["seq_len"])
+        assert np.array_equal(kd.float().cpu().numpy(), ref["k_cache"]) and np.array_equal(vd.float().cpu().numpy(), ref["v_cache"])
+    d = ob.ouro_kv_commit_desc()
+    d.struct_size = __import__("ctypes").sizeof(ob.ouro_kv_commit_desc)
+    d.dtype, d.B, d.T, d.Hkv, d.D, d.max_accept = ob.OURO_BF16, 0, 4, 2, 128, 4
+    assert ob.lib.ouro_kv_commit(__import__("ctypes").byref(d), None) == 0

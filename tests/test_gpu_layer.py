@@ -153,3 +153,35 @@ def test_one_verifying_layer_chained_on_the_gpu():
     print("layer chain: max-abs err %.3g on outputs of magnitude %.3g" % (err, scale), flush=True)
     # each of the ~8 bf16 stores can differ by one rounding step between the chains; they add up incoherently
     assert err <= 8 * BF16_EPS * scale
+
+
+def test_layer_ops_edge_shapes():
+    """One-token blocks, a single row, odd sizes that take the scalar paths, in-place RMSNorm."""
+    rng = np.random.default_rng(31)
+    cfg = W.scaled(W.CONFIGS[2], B=3, Hq=2, Hkv=1, L=(0, 50), gamma=1, K=0, beta_p=0, D=128)     # T = 1
+    inp = W.make_attention_inputs(cfg, 88)
+    lens = np.diff(inp["cu_seqlens"]).astype(np.int32)
+    pos_ref = LO.block_positions(inp["pid"], inp["boff"], lens)
+    q, k = _up(inp["q"]), _up(inp["k_blk"])
+    pos = torch.empty(cfg.B, 1, dtype=torch.int32, device=DEV)
+    ob.ouro_rope_block(q, k, ob.pack_meta(inp["pid"], inp["boff"]).to(DEV), torch.from_numpy(inp["cu_seqlens"]).to(DEV),
+                       positions=pos)
+    torch.cuda.synchronize()
+    assert np.array_equal(pos.cpu().numpy(), pos_ref) and np.array_equal(pos_ref[:, 0], lens)
+    assert np.abs(to_np64(q) - LO.rope(inp["q"], pos_ref)).max() <= 2 * np.abs(inp["q"]).max() * BF16_EPS
+    # head dim 12 (not a multiple of 16): scalar rotary path, fp32
+    x = rng.standard_normal((1, 1, 3, 12)).astype(np.float32)
+    xk = rng.standard_normal((1, 1, 1, 12)).astype(np.float32)
+    qd, kd = _up(x, torch.float32), _up(xk, torch.float32)
+    ob.ouro_rope_block(qd, kd, ob.pack_meta(np.zeros((1, 1), np.int16), np.zeros((1, 1), np.int16)).to(DEV),
+                       torch.tensor([0, 9], dtype=torch.int64, device=DEV))
+    torch.cuda.synchronize()
+    assert np.abs(to_np64(qd) - LO.rope(x, np.array([[9]]))).max() <= 1e-5
+    # RMSNorm: a row length that is not a multiple of 8, a long row (beyond the register-resident path), in place
+    for Hd in (100, 20000):
+        xr, g = _bf(rng.standard_normal((3, Hd))), _bf(1 + 0.1 * rng.standard_normal(Hd))
+        xd = _up(xr)
+        ob.ouro_rmsnorm(xd, _up(g), 1e-6, out=xd)
+        torch.cuda.synchronize()
+        ref = LO.rmsnorm(xr, g, 1e-6)
+        assert np.abs(to_np64(xd) - ref).max() <= np.abs(ref).max() * BF16_EPS
