@@ -15,14 +15,28 @@ constexpr int kMaxT = 128;
 
 __global__ __launch_bounds__(64) void accept_kernel(ouro_accept_desc d) {
   __shared__ unsigned char match[kMaxT];
+  __shared__ int32_t tok[kMaxT], arg[kMaxT];            // the sequence's block, staged once: every later lookup is LDS
+  __shared__ ouro_tok_meta meta[kMaxT];
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
   const int T = d.T, gamma = d.gamma, K = d.K, beta = d.beta;
-  const int32_t* tok = d.draft_tok + static_cast<size_t>(b) * T;
-  const int32_t* arg = d.argmax + static_cast<size_t>(b) * T;
-  const ouro_tok_meta* meta = d.meta + static_cast<size_t>(b) * T;
   const bool have_root = d.root_pred != nullptr;
+  {
+    // all global loads of the kernel are issued here, back to back: one memory round trip
+    const int32_t* gtok = d.draft_tok + static_cast<size_t>(b) * T;
+    const int32_t* garg = d.argmax + static_cast<size_t>(b) * T;
+    const ouro_tok_meta* gmeta = d.meta + static_cast<size_t>(b) * T;
+    const int t0 = lane, t1 = lane + 64;
+    const int32_t k0 = t0 < T ? gtok[t0] : 0, k1 = t1 < T ? gtok[t1] : 0;
+    const int32_t a0 = t0 < T ? garg[t0] : 0, a1 = t1 < T ? garg[t1] : 0;
+    const ouro_tok_meta z = {0, 0};
+    const ouro_tok_meta m0 = t0 < T ? gmeta[t0] : z, m1 = t1 < T ? gmeta[t1] : z;
+    tok[t0] = k0; tok[t1] = k1;
+    arg[t0] = a0; arg[t1] = a1;
+    meta[t0] = m0; meta[t1] = m1;
+  }
   const int32_t root = have_root ? d.root_pred[b] : -1;
+  __syncthreads();
 
   for (int t = lane; t < T; t += 64) {
     int parent;

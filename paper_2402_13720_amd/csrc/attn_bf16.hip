@@ -726,27 +726,27 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
   const int r = rb * rows_wg + row;
   if (r >= a.M) return;
-  const int n = (a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - a.cu[b])) + a.T;
-  const int nchb = (n + a.chunk - 1) / a.chunk;
-  if (nchb == 1) return;                            // written directly by the main kernel
   const size_t gbase = static_cast<size_t>(group) * a.nch * rows_wg;
   float m_star = -INFINITY, lsum = 0.f;
   f32x8 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int ch0 = 0; ch0 < nchb; ch0 += 4) {
-    float m_c[4], l_c[4];
-    f32x4 x0[4], x1[4];
+  float m_c[4], l_c[4];
+  f32x4 x0[4], x1[4];
+  // `last` bounds the chunk index of a batch of four partial loads
+  auto load4 = [&](int ch0, int last) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int ch = min(ch0 + u, nchb - 1);          // clamped duplicates are skipped below
+      const int ch = min(ch0 + u, last);
       const size_t prow = gbase + static_cast<size_t>(ch) * rows_wg + row;
       m_c[u] = a.part_ml[prow * 2];
       l_c[u] = a.part_ml[prow * 2 + 1];
       x0[u] = *reinterpret_cast<const f32x4*>(a.part_o + prow * kD + 8 * c);
       x1[u] = *reinterpret_cast<const f32x4*>(a.part_o + prow * kD + 8 * c + 4);
     }
+  };
+  auto merge4 = [&](int ch0, int nchb) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      if (ch0 + u >= nchb) continue;
+      if (ch0 + u >= nchb) continue;                  // slots past the sequence's chunks hold nothing
       const float m_new = fmaxf(m_star, m_c[u]);
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
       const float fa = exp2f(m_star - m_safe), fb = exp2f(m_c[u] - m_safe);
@@ -758,6 +758,17 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
         acc[4 + e] = acc[4 + e] * fa + x1[u][e] * fb;
       }
     }
+  };
+  // The first batch is addressed without the sequence length (the workspace holds a.nch slots per
+  // group, so every slot is readable), which puts its loads in flight together with the length's.
+  load4(0, a.nch - 1);
+  const int n = (a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - a.cu[b])) + a.T;
+  const int nchb = (n + a.chunk - 1) / a.chunk;
+  if (nchb == 1) return;                            // written directly by the main kernel
+  merge4(0, nchb);
+  for (int ch0 = 4; ch0 < nchb; ch0 += 4) {
+    load4(ch0, nchb - 1);
+    merge4(ch0, nchb);
   }
   const float inv = 1.0f / lsum;
   const int t = r / a.G, hh = r - t * a.G;

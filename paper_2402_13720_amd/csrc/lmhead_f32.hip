@@ -68,10 +68,19 @@ __global__ __launch_bounds__(256) void lmhead_final_kernel(const float2* part, i
   if (r >= R) return;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  for (int s = lane; s < nslab; s += 64) {
-    const float2 p = part[static_cast<size_t>(s) * R + r];
-    const int i = __float_as_int(p.y);
-    if (better(p.x, i, bv, bi)) { bv = p.x; bi = i; }
+  // loads in batches of 8 independent ones (one memory round trip per 512 slabs, not one per 64)
+  for (int s0 = lane; s0 < nslab; s0 += 64 * 8) {
+    float2 p[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = s0 + 64 * u;
+      p[u] = s < nslab ? part[static_cast<size_t>(s) * R + r] : make_float2(-INFINITY, __int_as_float(0x7fffffff));
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = __float_as_int(p[u].y);
+      if (better(p[u].x, i, bv, bi)) { bv = p[u].x; bi = i; }
+    }
   }
   for (int off = 32; off >= 1; off >>= 1) {
     const float ov = __shfl_xor(bv, off);
