@@ -30,8 +30,9 @@
 //                                    order of V^T permuted to match when V is transposed)
 //
 // The next tile's global loads are issued before the current tile's math.  After the loop
-// the 4 wave states (O, running max, running sum) are merged pairwise through LDS, staged
-// row-major in LDS and written with coalesced 16-byte stores.  A sequence that spans several
+// the 4 wave states (O, running max, running sum) go row-major to LDS once; every thread then
+// folds the four states of its 4 output floats and writes them with a coalesced 16-byte (fp32
+// partial) or 8-byte (bf16 output) store.  A sequence that spans several
 // chunks leaves one fp32 partial per workgroup, and a second small kernel merges the partials
 // of a row in ascending chunk order (deterministic) and writes bf16.  (A single-launch variant
 // in which the last workgroup of a row block merged the partials was measured slower: the
@@ -48,6 +49,7 @@ namespace ouro {
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(8 * sizeof(float)))) float f32x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
@@ -87,10 +89,9 @@ constexpr int cmax(int x, int y) { return x > y ? x : y; }
 constexpr int kRows = 32;                                  // query rows per workgroup
 constexpr int kQBytes = kRows * 256;                       // Q tile shared by the 4 waves, same swizzle as the K tile
 constexpr int kStateBytes = 16 * 64 * 16;                  // O accumulators of one wave, lane-major
-constexpr int kMergeBytes = 2 * kStateBytes + 2 * 64 * 8;  // two slots + their (max, sum) pairs
-constexpr int kStageBytes = kRows * kStageRow * 4 + kRows * 8;
+constexpr int kMergeBytes = 4 * kRows * (kStageRow * 4 + 8);   // the four wave states, row-major, + their (max, sum) pairs
 constexpr int kPidBytes = 128 * 2;                         // phrase ids of the block keys (T <= 128)
-constexpr int kMainLds = kQBytes + cmax(cmax(4 * kWaveLds, kMergeBytes), kStageBytes);
+constexpr int kMainLds = cmax(kQBytes + 4 * kWaveLds, kMergeBytes);   // the merge reuses the tiles' space
 constexpr int kLdsBytes = kMainLds + kPidBytes;            // 72 KB: two workgroups per CU
 
 // Slot (16 bytes = 8 keys of one head-dim element d) of the transposed V tile.
@@ -310,95 +311,67 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     wave_lds_fence();                               // reads of this tile precede the next tile's LDS writes
   }
 
-  // ---- merge the 4 wave states pairwise through LDS: (2,3) -> (0,1), then 1 -> 0 ----
-  unsigned char* scratch = lds + kQBytes;
-  f32x4* slot_o = reinterpret_cast<f32x4*>(scratch);
-  float* slot_ml = reinterpret_cast<float*>(scratch + 2 * kStateBytes);
-#pragma unroll
-  for (int sft = 2; sft >= 1; sft >>= 1) {
-    __syncthreads();
-    if (wave >= sft && wave < 2 * sft) {
-      const int slot = wave - sft;
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int ig = 0; ig < 4; ++ig) {
-          f32x4 v4 = {o[dt][4 * ig + 0], o[dt][4 * ig + 1], o[dt][4 * ig + 2], o[dt][4 * ig + 3]};
-          slot_o[(slot * 16 + dt * 4 + ig) * 64 + lane] = v4;
-        }
-      slot_ml[(slot * 64 + lane) * 2 + 0] = m_run;
-      slot_ml[(slot * 64 + lane) * 2 + 1] = l_run;
-    }
-    __syncthreads();
-    if (wave < sft) {
-      const int slot = wave;
-      const float m_b = slot_ml[(slot * 64 + lane) * 2 + 0];
-      const float l_b = slot_ml[(slot * 64 + lane) * 2 + 1];
-      const float m_new = fmaxf(m_run, m_b);
-      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-      const float fa = exp2f(m_run - m_safe), fb = exp2f(m_b - m_safe);
-      m_run = m_new;
-      l_run = l_run * fa + l_b * fb;
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int ig = 0; ig < 4; ++ig) {
-          const f32x4 ob = slot_o[(slot * 16 + dt * 4 + ig) * 64 + lane];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[dt][4 * ig + e] = o[dt][4 * ig + e] * fa + ob[e] * fb;
-        }
-    }
-  }
-  __syncthreads();
-
-  // ---- wave 0 stages the workgroup's state row-major: stage_o[row][132], stage_ml[row][2] ----
-  float* stage_o = reinterpret_cast<float*>(scratch);
-  float* stage_ml = stage_o + kRows * kStageRow;
-  if (wave == 0) {
+  // ---- merge of the 4 wave states.  Every wave leaves its state row-major in LDS (O rows of kStageRow floats,
+  // one (max, sum) pair per row; the Q and K/V tiles are dead by now), then thread (row, c) folds the four
+  // states of its 4 output floats in wave order, O = sum_w 2^(m_w - m*) O_w, and writes them straight to memory:
+  // the normalised bf16 output when the workgroup saw every key of the sequence, else its fp32 partial.
+  __syncthreads();                                // all waves are done with the tiles
+  float* st_o = reinterpret_cast<float*>(lds);                                  // [4][kRows][kStageRow]
+  float* st_ml = st_o + 4 * kRows * kStageRow;                                  // [4][kRows][2]
+  {
     const float l_tot = l_run + __shfl_xor(l_run, 32);
+    float* mine = st_o + (wave * kRows + col) * kStageRow;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int ig = 0; ig < 4; ++ig) {
         f32x4 v4 = {o[dt][4 * ig + 0], o[dt][4 * ig + 1], o[dt][4 * ig + 2], o[dt][4 * ig + 3]};
-        *reinterpret_cast<f32x4*>(stage_o + col * kStageRow + 32 * dt + 8 * ig + 4 * half) = v4;
+        *reinterpret_cast<f32x4*>(mine + 32 * dt + 8 * ig + 4 * half) = v4;
       }
     if (half == 0) {
-      stage_ml[col * 2 + 0] = m_run;
-      stage_ml[col * 2 + 1] = l_tot;
+      st_ml[(wave * kRows + col) * 2 + 0] = m_run;
+      st_ml[(wave * kRows + col) * 2 + 1] = l_tot;
     }
   }
   __syncthreads();
 
   const int group = bg * a.nrb + rb;
-  if (nchb == 1) {
-    // ---- the workgroup saw every key of the sequence: normalise and write bf16, 16 B per thread ----
-    for (int p = tid; p < kRows * 16; p += 256) {
-      const int row = p >> 4, c = p & 15;
+  const size_t pbase = (static_cast<size_t>(group) * a.nch + chunk) * kRows;
+#pragma unroll
+  for (int u = 0; u < kRows * 32 / 256; ++u) {
+    const int p = tid + 256 * u;
+    const int row = p >> 5, c = p & 31;
+    float m_w[4], l_w[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      m_w[w] = st_ml[(w * kRows + row) * 2 + 0];
+      l_w[w] = st_ml[(w * kRows + row) * 2 + 1];
+    }
+    const float m_star = fmaxf(fmaxf(m_w[0], m_w[1]), fmaxf(m_w[2], m_w[3]));
+    const float m_safe = m_star == -INFINITY ? 0.f : m_star;
+    float lsum = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = exp2f(m_w[w] - m_safe);       // a wave without keys has m = -inf, O = 0: factor 0
+      lsum += f * l_w[w];
+      acc += f * *reinterpret_cast<const f32x4*>(st_o + (w * kRows + row) * kStageRow + 4 * c);
+    }
+    if (nchb == 1) {
+      // the workgroup saw every key of the sequence: normalise and write bf16
       const int r = row0 + row;
       if (r >= M) continue;
-      const float inv = 1.0f / stage_ml[row * 2 + 1];
-      const f32x4 x0 = *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 8 * c);
-      const f32x4 x1 = *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 8 * c + 4);
-      f32x8 v8 = {x0[0] * inv, x0[1] * inv, x0[2] * inv, x0[3] * inv, x1[0] * inv, x1[1] * inv, x1[2] * inv, x1[3] * inv};
       const int t = r / G, hh = r - t * G;
       __bf16* op = a.out + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
-      *reinterpret_cast<bf16x8*>(op + 8 * c) = __builtin_convertvector(v8, bf16x8);
+      *reinterpret_cast<bf16x4*>(op + 4 * c) = __builtin_convertvector(acc * (1.0f / lsum), bf16x4);
       if (a.lse && c == 0)
-        a.lse[(static_cast<size_t>(b) * Hq + g * G + hh) * T + t] =
-            (stage_ml[row * 2] + log2f(stage_ml[row * 2 + 1])) * kLn2;
+        a.lse[(static_cast<size_t>(b) * Hq + g * G + hh) * T + t] = (m_star + log2f(lsum)) * kLn2;
+    } else {
+      // several chunks: leave a partial for the combine kernel (plain coalesced stores, no waiting)
+      *reinterpret_cast<f32x4*>(a.part_o + (pbase + row) * kD + 4 * c) = acc;
+      if (c == 0) *reinterpret_cast<float2*>(a.part_ml + (pbase + row) * 2) = make_float2(m_star, lsum);
     }
-    return;
   }
-
-  // ---- several chunks: leave a partial for the combine kernel (plain coalesced stores, no waiting) ----
-  const size_t pbase = (static_cast<size_t>(group) * a.nch + chunk) * kRows;
-  for (int p = tid; p < kRows * 32; p += 256) {
-    const int row = p >> 5, c = p & 31;
-    *reinterpret_cast<f32x4*>(a.part_o + (pbase + row) * kD + 4 * c) =
-        *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 4 * c);
-  }
-  for (int p = tid; p < kRows * 2; p += 256) a.part_ml[pbase * 2 + p] = stage_ml[p];
 }
 
 // ---- row-split variant: more than 32 query rows per (sequence, KV head) -------------------------------------
