@@ -44,6 +44,8 @@ def parse_args():
                     help="also time the rest of one verifying layer around the attention (RMSNorm, fused QKV projection, "
                          "rotary embedding at the draft positions, attention, output projection, RMSNorm, SwiGLU MLP) and "
                          "report it as an extra 'layer' object; the headline value is unchanged")
+    ap.add_argument("--lm-rows", default="", help="comma-separated row counts (e.g. 1024,2048,4096): also time the LM "
+                    "head alone at these R on the workload's vocabulary x hidden (MFMA-bound regime); adds lmhead_large_R")
     ap.add_argument("--kv-layout", default="head", choices=["head", "row"],
                     help="KV-cache layout: [Hkv, rows, D] (every (sequence, KV head) stream contiguous; default) or "
                          "[rows, Hkv, D]")
@@ -119,6 +121,35 @@ def cpu_baseline(cfg, inp, w, draws, budget_s):
         "step_seconds_scaled": t_step,
         "stage_seconds_scaled": {"attention": t_att, "lmhead_argmax": t_lm, "accept": t_acc},
     }
+
+
+def time_lmhead_rows(cfg, ob, torch, ws, rows_list, iters=60, warm=60):
+    """ouro_lmhead_argmax alone at large row counts R (hidden ~ N(0,1)), the weight copies cycled through as in the
+    step.  Returns one record per R: microseconds per call (whole call, both kernels) and the bf16 MFMA fraction."""
+    import ctypes as C
+    dev = torch.device("cuda:0")
+    out = []
+    stream = torch.cuda.current_stream()
+    hs = stream.cuda_stream or None
+    gen = torch.Generator().manual_seed(20240213)
+    for R in rows_list:
+        h = torch.randn(R, cfg.hidden, generator=gen).to(torch.bfloat16).to(dev)
+        arg = torch.empty(R, dtype=torch.int32, device=dev)
+        wsp = ob.alloc_workspace(ob.ouro_lmhead_argmax_workspace(h, ws[0]), dev)
+        descs = [ob.make_lmhead_desc(h, w, arg, None, wsp) for w in ws]
+        for i in range(warm):
+            ob.lib.ouro_lmhead_argmax(C.byref(descs[i % len(descs)]), hs)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(iters):
+            if ob.lib.ouro_lmhead_argmax(C.byref(descs[i % len(descs)]), hs) != 0:
+                raise RuntimeError("ouro_lmhead_argmax failed")
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / iters
+        tflops = 2.0 * R * cfg.hidden * cfg.V / us / 1e6
+        out.append({"R": R, "us_per_call": us, "TFLOP/s": tflops, "frac_of_mfma_peak": tflops / MFMA_BF16_PEAK_TFLOPS})
+    return out
 
 
 def time_layer(cfg, ob, torch, q, k_blk, v_blk, kcs, vcs, cu, meta, max_seqlen, head_major, steps):
@@ -373,6 +404,10 @@ def main():
                  "achieved_GBs": lbytes / us / 1e3, "frac_of_hbm_peak": lbytes / us / 1e3 / HBM_PEAK_GBS,
                  "how": "9 library calls + 3 strided copies that split the fused QKV output, replayed from a HIP graph"}
 
+    large_r = None
+    if args.lm_rows and cfg.dtype == "bf16":
+        large_r = time_lmhead_rows(cfg, ob, torch, ws, [int(x) for x in args.lm_rows.split(",") if x])
+
     ms_step = elapsed * 1e3 / args.steps
     seg = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(3)] for ev in events.values()])   # ms
     t_attn, t_lm, t_acc = (float(x) for x in seg.mean(axis=0))
@@ -423,6 +458,7 @@ def main():
                           "algorithmic_bytes": at_bytes, "mfma_tflops": at_tflops},
         "lmhead_mfma_frac": lm_tflops / MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else None,
         "layer": layer,
+        "lmhead_large_R": large_r,
         "cpu_baseline": cpu,
         "accepted_per_sequence": acc_out["n_accept"].cpu().tolist()[:16],
     }
