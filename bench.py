@@ -181,9 +181,7 @@ def time_layer(cfg, ob, torch, q, k_blk, v_blk, kcs, vcs, cu, meta, max_seqlen, 
         w = ws[r % ncopy]
         ob.ouro_rmsnorm(x, g1, 1e-5, out=h, stream=stream)
         ob.ouro_linear(h, w["qkv"], out=qkv, workspace=lin_ws, stream=stream)
-        v4 = qkv.view(cfg.B, cfg.T, cfg.Hq + 2 * cfg.Hkv, D)
-        qb.copy_(v4[:, :, :cfg.Hq]); kb.copy_(v4[:, :, cfg.Hq:cfg.Hq + cfg.Hkv]); vb.copy_(v4[:, :, cfg.Hq + cfg.Hkv:])
-        ob.ouro_rope_block(qb, kb, meta, cu, stream=stream)
+        ob.ouro_rope_block(qb, kb, meta, cu, stream=stream, qkv=qkv, v_blk=vb)    # rotary + split of the fused output
         ob.ouro_verify_attn(qb, kcs[r % len(kcs)], vcs[r % len(vcs)], cu, kb, vb, meta, max_seqlen, out=att,
                             workspace=att_ws, stream=stream, head_major=head_major)
         ob.ouro_linear(att.view(R, Hd), w["o"], residual=x, out=x1, workspace=lin_ws, stream=stream)
@@ -402,7 +400,7 @@ def main():
         lbytes = wbytes + attn_algorithmic_bytes(cfg, total_rows)
         layer = {"us_per_layer": us, "mlp_width": F, "weight_bytes": wbytes, "algorithmic_bytes": lbytes,
                  "achieved_GBs": lbytes / us / 1e3, "frac_of_hbm_peak": lbytes / us / 1e3 / HBM_PEAK_GBS,
-                 "how": "9 library calls + 3 strided copies that split the fused QKV output, replayed from a HIP graph"}
+                 "how": "10 library calls (norm, QKV, rotary+split, attention, o, norm, gate/up, SwiGLU, down), replayed from a HIP graph"}
 
     large_r = None
     if args.lm_rows and cfg.dtype == "bf16":

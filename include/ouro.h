@@ -263,19 +263,26 @@ OURO_API int ouro_kv_commit(const ouro_kv_commit_desc* desc, void* hip_stream);
 /* embedding, SwiGLU); all inner arithmetic in fp32.                                         */
 /* ------------------------------------------------------------------------------------ */
 
-/* Rotary embedding of the block's queries and keys, in place, at the positions above: the     */
-/* pair (x[i], x[i + D/2]) of every head is rotated by the angle pos * base^(-2i/D).           */
+/* Rotary embedding of the block's queries and keys at the positions above: the pair           */
+/* (x[i], x[i + D/2]) of every head is rotated by the angle pos * base^(-2i/D).                */
+/* Two forms.  In place (qkv NULL): q and k_blk are rotated where they are.  From a fused       */
+/* projection (qkv non-NULL): row b*T + t of qkv holds [Hq heads | Hkv key heads | Hkv value    */
+/* heads], each of D elements; the rotated queries and keys are written to q and k_blk and the   */
+/* values are copied to v_blk, so that one launch turns the projection's output into the three   */
+/* operands ouro_verify_attn takes.  qkv must not overlap q, k_blk or v_blk.                     */
 typedef struct {
   uint32_t struct_size;        /* sizeof(ouro_rope_desc) */
   int32_t dtype;
   int32_t B, T, Hq, Hkv, D;    /* D even */
   float base;                  /* <= 0: 10000 */
-  void* q;                     /* [B, T, Hq, D] in/out */
-  void* k_blk;                 /* [B, T, Hkv, D] in/out */
+  void* q;                     /* [B, T, Hq, D] in/out (out only with qkv) */
+  void* k_blk;                 /* [B, T, Hkv, D] in/out (out only with qkv) */
   const ouro_tok_meta* meta;   /* [B, T] */
   const int64_t* cu_seqlens;   /* [B+1], as in ouro_attn_desc */
   const int32_t* seq_len;      /* optional [B], as in ouro_attn_desc */
   int32_t* positions;          /* optional out [B, T] */
+  const void* qkv;             /* optional [B*T, (Hq + 2*Hkv) * D]: source of the second form */
+  void* v_blk;                 /* [B, T, Hkv, D] out; required with qkv, ignored without */
 } ouro_rope_desc;
 OURO_API int ouro_rope_block(const ouro_rope_desc* desc, void* hip_stream);
 

@@ -74,7 +74,7 @@ class ouro_rope_desc(C.Structure):
         ("B", C.c_int32), ("T", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
         ("base", C.c_float),
         ("q", C.c_void_p), ("k_blk", C.c_void_p), ("meta", C.c_void_p), ("cu_seqlens", C.c_void_p),
-        ("seq_len", C.c_void_p), ("positions", C.c_void_p),
+        ("seq_len", C.c_void_p), ("positions", C.c_void_p), ("qkv", C.c_void_p), ("v_blk", C.c_void_p),
     ]
 
 
@@ -377,10 +377,15 @@ def ouro_kv_commit(k_blk, v_blk, accept_idx, n_accept, k_cache, v_cache, cu_seql
     return overflow
 
 
-def ouro_rope_block(q, k_blk, meta, cu_seqlens, seq_len=None, base: float = 0.0, positions=None, stream=None):
-    """Rotary embedding of the block's q [B,T,Hq,D] and k_blk [B,T,Hkv,D], in place, at the positions the draft
-    structure gives (cached tokens + tokens before it in the token's own draft).  Returns positions if given."""
+def ouro_rope_block(q, k_blk, meta, cu_seqlens, seq_len=None, base: float = 0.0, positions=None, stream=None,
+                    qkv=None, v_blk=None):
+    """Rotary embedding of the block's q [B,T,Hq,D] and k_blk [B,T,Hkv,D] at the positions the draft structure gives
+    (cached tokens + tokens before it in the token's own draft): in place, or, with qkv [B*T, (Hq+2*Hkv)*D] (a fused
+    projection's output), read from there, with the value heads copied to v_blk.  Returns positions if given."""
     assert q.is_contiguous() and k_blk.is_contiguous() and q.dtype == k_blk.dtype
+    if qkv is not None:
+        assert v_blk is not None and v_blk.is_contiguous() and qkv.is_contiguous() and qkv.dtype == q.dtype
+        assert qkv.numel() == q.numel() + k_blk.numel() + v_blk.numel() and v_blk.shape == k_blk.shape
     B, T, Hq, D = q.shape
     d = ouro_rope_desc()
     d.struct_size = C.sizeof(ouro_rope_desc)
@@ -389,6 +394,7 @@ def ouro_rope_block(q, k_blk, meta, cu_seqlens, seq_len=None, base: float = 0.0,
     d.base = float(base)
     d.q, d.k_blk, d.meta, d.cu_seqlens = _ptr(q), _ptr(k_blk), _ptr(meta), _ptr(cu_seqlens)
     d.seq_len, d.positions = _ptr(seq_len), _ptr(positions)
+    d.qkv, d.v_blk = _ptr(qkv), _ptr(v_blk)
     _check(lib.ouro_rope_block(C.byref(d), _stream(stream)), "ouro_rope_block")
     return positions
 

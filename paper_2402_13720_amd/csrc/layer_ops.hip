@@ -48,6 +48,10 @@ __global__ __launch_bounds__(256) void rope_block_kernel(ouro_rope_desc d, float
   const int half = d.D / 2;
   T* q = static_cast<T*>(d.q) + static_cast<size_t>(blockIdx.x) * d.Hq * d.D;
   T* k = static_cast<T*>(d.k_blk) + static_cast<size_t>(blockIdx.x) * d.Hkv * d.D;
+  // sources: the operands themselves (in place), or this token's row of a fused projection [q heads | k heads | v heads]
+  const T* row = d.qkv ? static_cast<const T*>(d.qkv) + static_cast<size_t>(blockIdx.x) * (d.Hq + 2 * d.Hkv) * d.D : nullptr;
+  const T* qs = row ? row : q;
+  const T* ks = row ? row + static_cast<size_t>(d.Hq) * d.D : k;
   // angle = pos * base^(-2i/D) can be thousands of radians: it is formed and reduced to [-pi, pi] in fp64
   // (a handful of fp64 operations per pair), after which the fast fp32 sine/cosine are accurate to ~1e-6
 #define OURO_ROPE_SINCOS(I, S, C)                                                                              \
@@ -59,7 +63,8 @@ __global__ __launch_bounds__(256) void rope_block_kernel(ouro_rope_desc d, float
     C = __cosf(red_);                                                                                          \
   }
   typedef T vec8 __attribute__((ext_vector_type(8)));
-  const bool vec = half % 8 == 0 && ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k)) & 15) == 0;
+  const bool vec = half % 8 == 0 && ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) |
+                                      reinterpret_cast<uintptr_t>(qs) | reinterpret_cast<uintptr_t>(ks)) & 15) == 0;
   if (vec) {
     // work item = 8 consecutive rotation pairs of one head: two 16-byte (bf16) vectors in, two out
     const int per_head = half / 8;
@@ -69,7 +74,8 @@ __global__ __launch_bounds__(256) void rope_block_kernel(ouro_rope_desc d, float
       const int pp = is_q ? p : p - nq;
       const int h = pp / per_head, i0 = (pp - h * per_head) * 8;
       T* x = (is_q ? q : k) + static_cast<size_t>(h) * d.D + i0;
-      const vec8 a = *reinterpret_cast<const vec8*>(x), bb = *reinterpret_cast<const vec8*>(x + half);
+      const T* xs = (is_q ? qs : ks) + static_cast<size_t>(h) * d.D + i0;
+      const vec8 a = *reinterpret_cast<const vec8*>(xs), bb = *reinterpret_cast<const vec8*>(xs + half);
       vec8 oa, ob;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -89,14 +95,26 @@ __global__ __launch_bounds__(256) void rope_block_kernel(ouro_rope_desc d, float
       const int pp = is_q ? p : p - nq;
       const int h = pp / half, i = pp - h * half;
       T* x = (is_q ? q : k) + static_cast<size_t>(h) * d.D;
+      const T* xs = (is_q ? qs : ks) + static_cast<size_t>(h) * d.D;
       float sn, cs;
       OURO_ROPE_SINCOS(i, sn, cs)
-      const float x0 = Elem<T>::load(x + i), x1 = Elem<T>::load(x + i + half);
+      const float x0 = Elem<T>::load(xs + i), x1 = Elem<T>::load(xs + i + half);
       Elem<T>::store(x + i, x0 * cs - x1 * sn);
       Elem<T>::store(x + i + half, x1 * cs + x0 * sn);
     }
   }
 #undef OURO_ROPE_SINCOS
+  if (row) {
+    // the value heads of the fused row are copied as they are
+    const T* vs = row + static_cast<size_t>(d.Hq + d.Hkv) * d.D;
+    T* v = static_cast<T*>(d.v_blk) + static_cast<size_t>(blockIdx.x) * d.Hkv * d.D;
+    const int n = d.Hkv * d.D;
+    if (n % 8 == 0 && ((reinterpret_cast<uintptr_t>(vs) | reinterpret_cast<uintptr_t>(v)) & 15) == 0) {
+      for (int i = threadIdx.x * 8; i < n; i += 256 * 8) *reinterpret_cast<vec8*>(v + i) = *reinterpret_cast<const vec8*>(vs + i);
+    } else {
+      for (int i = threadIdx.x; i < n; i += 256) v[i] = vs[i];
+    }
+  }
 }
 
 // One workgroup per row: sum of squares (fp32, fixed reduction order), then scale by the gain.  The row is read

@@ -242,6 +242,7 @@ int ouro_rope_block(const ouro_rope_desc* d, void* hip_stream) {
     return OURO_E_BAD_SHAPE;
   if (d->B == 0) return OURO_OK;
   if (!d->q || !d->k_blk || !d->meta || !d->cu_seqlens) return OURO_E_NULLPTR;
+  if (d->qkv && !d->v_blk) return OURO_E_NULLPTR;
   return launch_rope_block(*d, static_cast<hipStream_t>(hip_stream));
 }
 

@@ -196,6 +196,7 @@ def test_layer_descriptor_validation():
     assert ob.lib.ouro_rope_block(C.byref(r), None) == -2                 # odd head dim
     r.D = 8
     assert ob.lib.ouro_rope_block(C.byref(r), None) == -1
+    assert C.sizeof(ob.ouro_rope_desc) == 32 + 8 * 8                      # 8 ints/floats, 8 pointers
 
 
 def test_validate_meta_host():

@@ -22,6 +22,42 @@ def _up(x, dt=torch.bfloat16):
 
 @pytest.mark.parametrize("cfg_id, kw, dt", [
     (1, dict(B=3, L=(0, 200)), torch.float32),
+    (2, dict(B=2, Hq=4, Hkv=2, L=(0, 300)), torch.bfloat16),             # grouped-query: fewer key/value heads
+    (5, dict(B=4, Hq=4, Hkv=4, L=(512, 8192)), torch.bfloat16),
+    (1, dict(B=2, Hq=3, Hkv=1, D=6, L=(0, 50)), torch.float32),          # head dim without 16-byte vectors
+])
+def test_rope_block_from_fused_projection(cfg_id, kw, dt):
+    """Second form of ouro_rope_block: rows [q heads | k heads | v heads] of a fused projection in, q and k_blk rotated
+    and v_blk copied out; against the oracle's rotation of the split operands, and bit for bit against the in-place form."""
+    cfg = W.scaled(W.CONFIGS[cfg_id], **kw)
+    inp = W.make_attention_inputs(cfg, 400 + cfg_id, branch="uniform")
+    cu = inp["cu_seqlens"]
+    lens = np.diff(cu).astype(np.int32)
+    pos_ref = LO.block_positions(inp["pid"], inp["boff"], lens)
+    q_ref, k_ref = LO.rope(inp["q"], pos_ref), LO.rope(inp["k_blk"], pos_ref)
+    fused = np.concatenate([inp["q"], inp["k_blk"], inp["v_blk"]], axis=2).reshape(cfg.B * cfg.T, -1)
+    qkv = _up(fused, dt)
+    snapshot = qkv.clone()
+    q = torch.full((cfg.B, cfg.T, cfg.Hq, cfg.D), 7.0, dtype=dt, device=DEV)
+    k = torch.full((cfg.B, cfg.T, cfg.Hkv, cfg.D), 7.0, dtype=dt, device=DEV)
+    v = torch.full((cfg.B, cfg.T, cfg.Hkv, cfg.D), 7.0, dtype=dt, device=DEV)
+    meta, cu_d = ob.pack_meta(inp["pid"], inp["boff"]).to(DEV), torch.from_numpy(cu).to(DEV)
+    pos = torch.empty(cfg.B, cfg.T, dtype=torch.int32, device=DEV)
+    ob.ouro_rope_block(q, k, meta, cu_d, positions=pos, qkv=qkv, v_blk=v)
+    q2, k2 = _up(inp["q"], dt), _up(inp["k_blk"], dt)
+    ob.ouro_rope_block(q2, k2, meta, cu_d)
+    torch.cuda.synchronize()
+    assert np.array_equal(pos.cpu().numpy(), pos_ref)
+    assert torch.equal(qkv, snapshot)                                    # the source is read only
+    assert torch.equal(v, _up(inp["v_blk"], dt))                         # a copy: exact
+    assert torch.equal(q, q2) and torch.equal(k, k2)                     # same arithmetic as the in-place form
+    xmax = float(np.abs(inp["q"]).max())
+    tol = 2.0 * xmax * (pos_ref.max() * 2.0 ** -23 + (BF16_EPS if dt == torch.bfloat16 else 2.0 ** -22))
+    assert np.abs(to_np64(q) - q_ref).max() <= tol and np.abs(to_np64(k) - k_ref).max() <= tol
+
+
+@pytest.mark.parametrize("cfg_id, kw, dt", [
+    (1, dict(B=3, L=(0, 200)), torch.float32),
     (2, dict(B=2, Hq=4, Hkv=2, L=(0, 300)), torch.bfloat16),
     (5, dict(B=4, Hq=4, Hkv=4, L=(512, 8192)), torch.bfloat16),          # positions in the thousands
 ])
