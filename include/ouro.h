@@ -301,17 +301,23 @@ OURO_API int ouro_rmsnorm(const ouro_rmsnorm_desc* desc, void* hip_stream);
 /* out[r, n] = sum_k x[r, k] * w[n, k] (+ residual[r, n]): every projection of the layer.  bf16 only (bf16 MFMA,  */
 /* fp32 accumulation, one rounding at the end).  The weight is streamed from HBM once, like the LM head's, and may   */
 /* be given in the same tiled form (ouro_lmhead_pack_w with V = N, Hd = K).                                        */
+/* Epilogue OURO_EPI_SWIGLU_PAIRS (the MLP's first projection and its gate in one launch): rows 2j and 2j+1 of w    */
+/* are the gate and the up projection of feature j, and out[r, j] = silu(y[r, 2j]) * y[r, 2j+1] with y the fp32     */
+/* product, silu(a) = a / (1 + exp(-a)); out is then [R, N/2], N a multiple of 16, residual NULL.                    */
+enum { OURO_EPI_NONE = 0, OURO_EPI_SWIGLU_PAIRS = 1 };
 typedef struct {
   uint32_t struct_size;
   int32_t dtype;               /* OURO_BF16 */
   int32_t R;                   /* rows, >= 0 */
   int32_t K;                   /* input features, multiple of 64 */
-  int32_t N;                   /* output features, multiple of 8 */
+  int32_t N;                   /* output features (rows of w), multiple of 8 */
   int32_t w_layout;            /* OURO_W_ROW_MAJOR or OURO_W_TILED */
+  int32_t epilogue;            /* OURO_EPI_NONE or OURO_EPI_SWIGLU_PAIRS */
+  int32_t reserved0;           /* 0 */
   const void* x;               /* [R, K] */
   const void* w;               /* [N, K] or tiled */
   const void* residual;        /* optional [R, N]; may alias out */
-  void* out;                   /* [R, N] */
+  void* out;                   /* [R, N]  ([R, N/2] with OURO_EPI_SWIGLU_PAIRS) */
   void* workspace;             /* >= ouro_linear_workspace() bytes, 16-byte aligned; contents arbitrary.  Needed when
                                   N is small: the k range is then split over several workgroups whose fp32 partial
                                   sums are added in a fixed order by a second small kernel */

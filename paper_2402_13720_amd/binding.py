@@ -88,7 +88,7 @@ class ouro_rmsnorm_desc(C.Structure):
 class ouro_linear_desc(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32), ("dtype", C.c_int32), ("R", C.c_int32), ("K", C.c_int32), ("N", C.c_int32),
-        ("w_layout", C.c_int32),
+        ("w_layout", C.c_int32), ("epilogue", C.c_int32), ("reserved0", C.c_int32),
         ("x", C.c_void_p), ("w", C.c_void_p), ("residual", C.c_void_p), ("out", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
@@ -412,19 +412,31 @@ def ouro_rmsnorm(x, gain, eps: float, out=None, stream=None):
     return out
 
 
-def ouro_linear(x, w, residual=None, out=None, stream=None, workspace=None):
-    """out = x . w^T (+ residual); w is a [N, K] bf16 tensor or a TiledWeight."""
+OURO_EPI_NONE, OURO_EPI_SWIGLU_PAIRS = 0, 1
+
+
+def interleave_gate_up(w_gate: torch.Tensor, w_up: torch.Tensor) -> torch.Tensor:
+    """[F, K] gate and up weights -> [2F, K] with rows (gate_0, up_0, gate_1, up_1, ..): the layout the
+    swiglu epilogue of ouro_linear expects.  A load-time step."""
+    assert w_gate.shape == w_up.shape
+    return torch.stack([w_gate, w_up], dim=1).reshape(2 * w_gate.shape[0], w_gate.shape[1]).contiguous()
+
+
+def ouro_linear(x, w, residual=None, out=None, stream=None, workspace=None, swiglu: bool = False):
+    """out = x . w^T (+ residual); w is a [N, K] bf16 tensor or a TiledWeight.  swiglu: w holds interleaved
+    (gate, up) rows and out [R, N/2] = silu(gate) * up."""
     assert x.is_contiguous() and x.dtype == torch.bfloat16
     tiled = isinstance(w, TiledWeight)
     N, K = (w.V, w.Hd) if tiled else tuple(w.shape)
     assert K == x.shape[1]
     if out is None:
-        out = torch.empty(x.shape[0], N, dtype=x.dtype, device=x.device)
+        out = torch.empty(x.shape[0], N // 2 if swiglu else N, dtype=x.dtype, device=x.device)
     d = ouro_linear_desc()
     d.struct_size = C.sizeof(ouro_linear_desc)
     d.dtype = OURO_BF16
     d.R, d.K, d.N = x.shape[0], K, N
     d.w_layout = OURO_W_TILED if tiled else OURO_W_ROW_MAJOR
+    d.epilogue = OURO_EPI_SWIGLU_PAIRS if swiglu else OURO_EPI_NONE
     d.x, d.w, d.residual, d.out = _ptr(x), _ptr(w.data if tiled else w), _ptr(residual), _ptr(out)
     if workspace is None:
         need = int(lib.ouro_linear_workspace(C.byref(d)))

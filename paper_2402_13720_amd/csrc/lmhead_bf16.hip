@@ -53,7 +53,11 @@ struct LmArgs {
   // compute units idle: fp32 partial sums go to part_f32[ks][R][V] and linear_reduce_kernel finishes
   float* part_f32;
   int ksplit;
+  int swiglu;       // kStore: columns 2j, 2j+1 are gate and up of feature j; out[r, j] = silu(gate) * up, row stride V/2
 };
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + expf(-g)) * u; }
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
@@ -259,6 +263,11 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
             *reinterpret_cast<f32x4*>(a.part_f32 + static_cast<size_t>(ks) * R * V + o) = sum;
             continue;
           }
+          if (a.swiglu) {
+            const bf16x2 act = {static_cast<__bf16>(silu_mul(sum[0], sum[1])), static_cast<__bf16>(silu_mul(sum[2], sum[3]))};
+            *reinterpret_cast<bf16x2*>(a.out + o / 2) = act;         // o = r*V + v with V and v even: r*(V/2) + v/2
+            continue;
+          }
           if (a.residual) {
             const bf16x4 res = *reinterpret_cast<const bf16x4*>(a.residual + o);
 #pragma unroll
@@ -309,11 +318,16 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
 
 // out = bf16(sum over the k splits in ascending order (+ residual)); 4 outputs per thread
 __global__ __launch_bounds__(256) void linear_reduce_kernel(const float* __restrict__ part, const __bf16* residual,
-                                                            __bf16* out, size_t n, int ksplit) {
+                                                            __bf16* out, size_t n, int ksplit, int swiglu) {
   const size_t i = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
   if (i >= n) return;
   f32x4 sum = *reinterpret_cast<const f32x4*>(part + i);
   for (int ks = 1; ks < ksplit; ++ks) sum += *reinterpret_cast<const f32x4*>(part + static_cast<size_t>(ks) * n + i);
+  if (swiglu) {                                                        // (gate, up) pairs -> [R, N/2]
+    const bf16x2 act = {static_cast<__bf16>(silu_mul(sum[0], sum[1])), static_cast<__bf16>(silu_mul(sum[2], sum[3]))};
+    *reinterpret_cast<bf16x2*>(out + i / 2) = act;
+    return;
+  }
   if (residual) {
     const bf16x4 res = *reinterpret_cast<const bf16x4*>(residual + i);
 #pragma unroll
@@ -413,6 +427,7 @@ int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream) {
   a.residual = static_cast<const __bf16*>(d.residual);
   a.ksplit = linear_ksplit(d.R, d.K, d.N);
   a.part_f32 = static_cast<float*>(d.workspace);
+  a.swiglu = d.epilogue == OURO_EPI_SWIGLU_PAIRS;
   LmPlan plan{};
   plan.slab = 128;
   plan.nslab = (d.N + 127) / 128;
@@ -430,7 +445,7 @@ int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream) {
   if (st != OURO_OK || a.ksplit == 1) return st;
   const size_t n = static_cast<size_t>(d.R) * d.N;
   hipLaunchKernelGGL(linear_reduce_kernel, dim3(static_cast<unsigned>((n / 4 + 255) / 256)), dim3(256), 0, stream,
-                     a.part_f32, a.residual, a.out, n, a.ksplit);
+                     a.part_f32, a.residual, a.out, n, a.ksplit, a.swiglu);
   return check_launch();
 }
 

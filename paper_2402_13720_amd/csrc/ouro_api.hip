@@ -262,6 +262,8 @@ static int validate_linear(const ouro_linear_desc* d) {
   if (d->dtype != OURO_BF16) return OURO_E_UNSUPPORTED_DTYPE;
   if (d->R < 0 || d->K < 64 || d->K % 64 != 0 || d->N < 8 || d->N % 8 != 0) return OURO_E_BAD_SHAPE;
   if (d->w_layout != OURO_W_ROW_MAJOR && d->w_layout != OURO_W_TILED) return OURO_E_BAD_SHAPE;
+  if (d->epilogue != OURO_EPI_NONE && d->epilogue != OURO_EPI_SWIGLU_PAIRS) return OURO_E_BAD_SHAPE;
+  if (d->epilogue == OURO_EPI_SWIGLU_PAIRS && (d->N % 16 != 0 || d->residual)) return OURO_E_BAD_SHAPE;
   return OURO_OK;
 }
 

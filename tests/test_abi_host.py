@@ -186,7 +186,12 @@ def test_layer_descriptor_validation():
     assert ob.lib.ouro_linear(C.byref(d), None) == -2                     # K must be a multiple of 64
     d.K, d.N = 64, 12
     assert ob.lib.ouro_linear(C.byref(d), None) == -2                     # N must be a multiple of 8
-    d.N = 8
+    d.N, d.epilogue = 8, ob.OURO_EPI_SWIGLU_PAIRS
+    assert ob.lib.ouro_linear(C.byref(d), None) == -2                     # gated form: N must be a multiple of 16
+    d.epilogue = 7
+    assert ob.lib.ouro_linear(C.byref(d), None) == -2                     # unknown epilogue
+    d.epilogue = ob.OURO_EPI_NONE
+    assert C.sizeof(ob.ouro_linear_desc) == 32 + 5 * 8 + 8
     assert ob.lib.ouro_linear(C.byref(d), None) == -1                     # pointers missing
     d.R = 0
     assert ob.lib.ouro_linear(C.byref(d), None) == 0

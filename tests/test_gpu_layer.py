@@ -125,6 +125,33 @@ def test_linear(R, K, N, tiled, with_res):
     assert np.abs(to_np64(out) - ref).max() <= tol
 
 
+@pytest.mark.parametrize("R,K,F,tiled,ksplit", [
+    (64, 256, 344, True, 0),        # F not a multiple of 64: the last slab is ragged
+    (128, 320, 64, False, 0),       # 128-row instance
+    (70, 320, 136, True, 3),        # k range split: the activation is applied by the reduction kernel
+    (1, 64, 8, False, 0),
+])
+def test_linear_swiglu_epilogue(monkeypatch, R, K, F, tiled, ksplit):
+    """Gate and up projection with the gate applied in the epilogue: interleaved (gate_j, up_j) weight rows in, [R, F] out,
+    against the oracle's projection followed by its SiLU gate (no bf16 rounding of the pre-activations in between)."""
+    if ksplit:
+        monkeypatch.setenv("OURO_LINEAR_KSPLIT", str(ksplit))
+    rng = np.random.default_rng(R + K + F)
+    x = _bf(rng.standard_normal((R, K)))
+    wg, wu = _bf(rng.standard_normal((F, K)) * 0.08), _bf(rng.standard_normal((F, K)) * 0.08)
+    ref = LO.silu_mul(np.concatenate([LO.linear(x, wg), LO.linear(x, wu)], axis=1))
+    w_d = ob.interleave_gate_up(_up(wg), _up(wu))
+    assert torch.equal(w_d[0::2], _up(wg)) and torch.equal(w_d[1::2], _up(wu))
+    if tiled:
+        w_d = ob.ouro_lmhead_pack_w(w_d)
+    out = ob.ouro_linear(_up(x), w_d, swiglu=True)
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == (R, F)
+    # fp32 product and gate, one bf16 rounding; the gate's slope is at most 1.1, so the product's error carries over
+    tol = np.abs(ref).max() * BF16_EPS + 1e-4
+    assert np.abs(to_np64(out) - ref).max() <= tol
+
+
 @pytest.mark.parametrize("ksplit", [2, 3, 5])
 def test_linear_uneven_k_split(monkeypatch, ksplit):
     """The k range split over workgroups, including splits that do not divide the 5 k-tiles evenly (one share empty)."""
@@ -189,6 +216,23 @@ def test_one_verifying_layer_chained_on_the_gpu():
     print("layer chain: max-abs err %.3g on outputs of magnitude %.3g" % (err, scale), flush=True)
     # each of the ~8 bf16 stores can differ by one rounding step between the chains; they add up incoherently
     assert err <= 8 * BF16_EPS * scale
+
+    # ---- the same layer with the fused forms: rotary + split straight from the fused projection's output, and the
+    # SwiGLU gate in the epilogue of the gate/up projection (weights interleaved at load time)
+    qkv2 = ob.ouro_linear(h_d, ob.ouro_lmhead_pack_w(_up(wqkv)))
+    q2, k2, v2 = torch.empty_like(q_d), torch.empty_like(k_d), torch.empty_like(v_d)
+    ob.ouro_rope_block(q2, k2, meta, cu_d, qkv=qkv2, v_blk=v2)
+    att2 = ob.ouro_verify_attn(q2, _up(inp["k_cache"]), _up(inp["v_cache"]), cu_d, k2, v2, meta, int(lens.max()))
+    x1b = ob.ouro_linear(att2.view(R, Hd), ob.ouro_lmhead_pack_w(_up(wo)), residual=x_d)
+    h2b = ob.ouro_rmsnorm(x1b, _up(g2), 1e-5)
+    w_pairs = ob.ouro_lmhead_pack_w(ob.interleave_gate_up(_up(wgu[:F]), _up(wgu[F:])))
+    act2 = ob.ouro_linear(h2b, w_pairs, swiglu=True)
+    out2 = ob.ouro_linear(act2, ob.ouro_lmhead_pack_w(_up(wd)), residual=x1b)
+    torch.cuda.synchronize()
+    assert torch.equal(q2, q_d) and torch.equal(k2, k_d) and torch.equal(v2, v_d) and torch.equal(x1b, x1_d)
+    err2 = np.abs(to_np64(out2) - ref).max()
+    print("layer chain, fused forms: max-abs err %.3g" % err2, flush=True)
+    assert err2 <= 8 * BF16_EPS * scale
 
 
 def test_layer_ops_edge_shapes():
