@@ -167,26 +167,22 @@ def time_layer(cfg, ob, torch, q, k_blk, v_blk, kcs, vcs, cu, meta, max_seqlen, 
     ws = [{name: ob.ouro_lmhead_pack_w((torch.randn(n, k, generator=gen, device=dev) * k ** -0.5).to(dt))
            for name, (n, k) in shapes.items()} for _ in range(ncopy)]
     x = torch.randn(R, Hd, generator=gen, device=dev).to(dt)
-    g1, g2 = torch.ones(Hd, device=dev, dtype=dt), torch.ones(Hd, device=dev, dtype=dt)
-    h = torch.empty_like(x)
     qkv = torch.empty(R, nqkv, device=dev, dtype=dt)
     qb, kb, vb = torch.empty_like(q), torch.empty_like(k_blk), torch.empty_like(v_blk)
     att = torch.empty_like(q)
-    x1, h2, out = torch.empty_like(x), torch.empty_like(x), torch.empty_like(x)
+    x1, out = torch.empty_like(x), torch.empty_like(x)
     act = torch.empty(R, F, device=dev, dtype=dt)
     lin_ws = ob.alloc_workspace(64 << 20, dev)
     att_ws = ob.alloc_workspace(ob.ouro_verify_attn_workspace(q, k_blk, max_seqlen), dev)
 
     def layer(r, stream):
         w = ws[r % ncopy]
-        ob.ouro_rmsnorm(x, g1, 1e-5, out=h, stream=stream)
-        ob.ouro_linear(h, w["qkv"], out=qkv, workspace=lin_ws, stream=stream)
+        ob.ouro_linear(x, w["qkv"], out=qkv, workspace=lin_ws, stream=stream, rms_eps=1e-5)      # RMSNorm folded in
         ob.ouro_rope_block(qb, kb, meta, cu, stream=stream, qkv=qkv, v_blk=vb)    # rotary + split of the fused output
         ob.ouro_verify_attn(qb, kcs[r % len(kcs)], vcs[r % len(vcs)], cu, kb, vb, meta, max_seqlen, out=att,
                             workspace=att_ws, stream=stream, head_major=head_major)
         ob.ouro_linear(att.view(R, Hd), w["o"], residual=x, out=x1, workspace=lin_ws, stream=stream)
-        ob.ouro_rmsnorm(x1, g2, 1e-5, out=h2, stream=stream)
-        ob.ouro_linear(h2, w["gu"], out=act, workspace=lin_ws, stream=stream, swiglu=True)   # gate applied in the epilogue
+        ob.ouro_linear(x1, w["gu"], out=act, workspace=lin_ws, stream=stream, swiglu=True, rms_eps=1e-5)   # norm + gate
         ob.ouro_linear(act, w["down"], residual=x1, out=out, workspace=lin_ws, stream=stream)
 
     side = torch.cuda.Stream()
@@ -399,7 +395,7 @@ def main():
         lbytes = wbytes + attn_algorithmic_bytes(cfg, total_rows)
         layer = {"us_per_layer": us, "mlp_width": F, "weight_bytes": wbytes, "algorithmic_bytes": lbytes,
                  "achieved_GBs": lbytes / us / 1e3, "frac_of_hbm_peak": lbytes / us / 1e3 / HBM_PEAK_GBS,
-                 "how": "9 library calls (norm, QKV, rotary+split, attention, o + residual, norm, gate/up with the SwiGLU gate in its epilogue, down + residual), replayed from a HIP graph"}
+                 "how": "7 library calls (QKV with RMSNorm folded in, rotary + split, attention, o + residual, gate/up with RMSNorm folded in and the SwiGLU gate in its epilogue, down + residual), replayed from a HIP graph"}
 
     large_r = None
     if args.lm_rows and cfg.dtype == "bf16":

@@ -313,7 +313,9 @@ typedef struct {
   int32_t N;                   /* output features (rows of w), multiple of 8 */
   int32_t w_layout;            /* OURO_W_ROW_MAJOR or OURO_W_TILED */
   int32_t epilogue;            /* OURO_EPI_NONE or OURO_EPI_SWIGLU_PAIRS */
-  int32_t reserved0;           /* 0 */
+  float rms_eps;               /* > 0: the product's row r is scaled by 1 / sqrt(mean_k x[r, k]^2 + rms_eps) before the
+                                  epilogue and the residual: RMSNorm of the input with its gain folded into w
+                                  (w[n, k] * gain[k], done by the caller at load time), in the same launch; <= 0: off */
   const void* x;               /* [R, K] */
   const void* w;               /* [N, K] or tiled */
   const void* residual;        /* optional [R, N]; may alias out */

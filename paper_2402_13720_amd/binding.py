@@ -88,7 +88,7 @@ class ouro_rmsnorm_desc(C.Structure):
 class ouro_linear_desc(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32), ("dtype", C.c_int32), ("R", C.c_int32), ("K", C.c_int32), ("N", C.c_int32),
-        ("w_layout", C.c_int32), ("epilogue", C.c_int32), ("reserved0", C.c_int32),
+        ("w_layout", C.c_int32), ("epilogue", C.c_int32), ("rms_eps", C.c_float),
         ("x", C.c_void_p), ("w", C.c_void_p), ("residual", C.c_void_p), ("out", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
@@ -422,9 +422,15 @@ def interleave_gate_up(w_gate: torch.Tensor, w_up: torch.Tensor) -> torch.Tensor
     return torch.stack([w_gate, w_up], dim=1).reshape(2 * w_gate.shape[0], w_gate.shape[1]).contiguous()
 
 
-def ouro_linear(x, w, residual=None, out=None, stream=None, workspace=None, swiglu: bool = False):
+def fold_rmsnorm_gain(w: torch.Tensor, gain: torch.Tensor) -> torch.Tensor:
+    """w[n, k] * gain[k] in fp32, rounded once to w's dtype: the weight ouro_linear(rms_eps=...) expects.  Load time."""
+    return (w.float() * gain.float()[None, :]).to(w.dtype).contiguous()
+
+
+def ouro_linear(x, w, residual=None, out=None, stream=None, workspace=None, swiglu: bool = False, rms_eps: float = 0.0):
     """out = x . w^T (+ residual); w is a [N, K] bf16 tensor or a TiledWeight.  swiglu: w holds interleaved
-    (gate, up) rows and out [R, N/2] = silu(gate) * up."""
+    (gate, up) rows and out [R, N/2] = silu(gate) * up.  rms_eps > 0: rows of the product scaled by
+    1/sqrt(mean(x^2) + rms_eps) (RMSNorm of x with the gain folded into w)."""
     assert x.is_contiguous() and x.dtype == torch.bfloat16
     tiled = isinstance(w, TiledWeight)
     N, K = (w.V, w.Hd) if tiled else tuple(w.shape)
@@ -437,6 +443,7 @@ def ouro_linear(x, w, residual=None, out=None, stream=None, workspace=None, swig
     d.R, d.K, d.N = x.shape[0], K, N
     d.w_layout = OURO_W_TILED if tiled else OURO_W_ROW_MAJOR
     d.epilogue = OURO_EPI_SWIGLU_PAIRS if swiglu else OURO_EPI_NONE
+    d.rms_eps = float(rms_eps)
     d.x, d.w, d.residual, d.out = _ptr(x), _ptr(w.data if tiled else w), _ptr(residual), _ptr(out)
     if workspace is None:
         need = int(lib.ouro_linear_workspace(C.byref(d)))

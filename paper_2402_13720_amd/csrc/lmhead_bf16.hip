@@ -54,10 +54,26 @@ struct LmArgs {
   float* part_f32;
   int ksplit;
   int swiglu;       // kStore: columns 2j, 2j+1 are gate and up of feature j; out[r, j] = silu(gate) * up, row stride V/2
+  // kStore, rms_eps > 0: every output row is scaled by 1 / sqrt(mean_k hidden[r, k]^2 + rms_eps) (RMSNorm of the input
+  // with its gain folded into W).  The sums of squares come from the hidden tiles the workgroup stages anyway; with
+  // the k range split, the slab-0 workgroups leave their share in part_ss[ks][R] and the reduction kernel finishes.
+  float rms_eps;
+  float* part_ss;
 };
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + expf(-g)) * u; }
+// sum of the squares of 8 packed bf16 values (a bf16 is the upper half of an fp32)
+__device__ __forceinline__ float sumsq_bf16x8(u32x4 v) {
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float lo = __uint_as_float(v[i] << 16), hi = __uint_as_float(v[i] & 0xffff0000u);
+    s = fmaf(lo, lo, s);
+    s = fmaf(hi, hi, s);
+  }
+  return s;
+}
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
@@ -160,6 +176,12 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.f;
+  // Sums of squares of the hidden rows (rms): lane (col, half) squares the 8 values of row 32nt + col it holds as an MFMA
+  // operand fragment in every k step; the vector ALU does that between the MFMAs, which it would otherwise sit out.
+  const bool rms = kStore && a.rms_eps > 0.f;
+  float ss[kStore ? NT : 1];
+#pragma unroll
+  for (int nt = 0; nt < (kStore ? NT : 1); ++nt) ss[nt] = 0.f;
 
   // this workgroup's k-tiles: all of them, or its share of an even split; this wave's: first + 4*j, j = 0..nj-1
   const int nkt_all = Hd / 64;
@@ -197,6 +219,12 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
         _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                             \
             _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                         \
                 acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bf[nt], acc[mt][nt], 0, 0, 0); \
+        if constexpr (kStore) {                                                                       \
+          if (rms) {                                                                                  \
+            _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                         \
+                ss[nt] += sumsq_bf16x8(__builtin_bit_cast(u32x4, bf[nt]));                            \
+          }                                                                                           \
+        }                                                                                             \
       }                                                                                               \
     }                                                                                                 \
     wave_lds_fence();                                                                                 \
@@ -229,6 +257,16 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   // ---- sum the 4 waves' accumulators, 4 tiles per round; wave w reduces tile 4*round + w ----
   float* bestv = reinterpret_cast<float*>(lds + C::kBestOff);
   int* besti = reinterpret_cast<int*>(lds + C::kBestOff + MT * C::kHRows * 4);
+  float* rowss = bestv;                                       // kStore: [4 waves][kHRows] sums of squares
+  if constexpr (kStore) {
+    if (rms) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const float t = ss[nt] + __shfl_xor(ss[nt], 32);      // the two k halves of row 32nt + col
+        if (half == 0) rowss[wave * C::kHRows + 32 * nt + col] = t;
+      }
+    }
+  }
   constexpr int kRounds = C::kTiles / 4;
   static_assert(C::kTiles % 4 == 0, "tiles per wave must be a multiple of 4");
 #pragma unroll
@@ -251,6 +289,12 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
     if constexpr (kStore) {
       // lane (col, half) holds, for row r0 + 32*nt + col, the outputs of columns slab0 + 32*mt + 8*ig + 4*half + 0..3
       const int r = r0 + 32 * nt + col;
+      float rinv = 1.0f;
+      if (rms && a.ksplit == 1) {                               // (the first barrier of the round ordered the rowss writes)
+        const int rl = 32 * nt + col;
+        const float tot = (rowss[rl] + rowss[C::kHRows + rl]) + (rowss[2 * C::kHRows + rl] + rowss[3 * C::kHRows + rl]);
+        rinv = 1.0f / sqrtf(tot / static_cast<float>(Hd) + a.rms_eps);
+      }
 #pragma unroll
       for (int ig = 0; ig < 4; ++ig) {
         f32x4 sum = {0.f, 0.f, 0.f, 0.f};
@@ -263,6 +307,7 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
             *reinterpret_cast<f32x4*>(a.part_f32 + static_cast<size_t>(ks) * R * V + o) = sum;
             continue;
           }
+          sum *= rinv;
           if (a.swiglu) {
             const bf16x2 act = {static_cast<__bf16>(silu_mul(sum[0], sum[1])), static_cast<__bf16>(silu_mul(sum[2], sum[3]))};
             *reinterpret_cast<bf16x2*>(a.out + o / 2) = act;         // o = r*V + v with V and v even: r*(V/2) + v/2
@@ -300,7 +345,15 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
       besti[mt * C::kHRows + 32 * nt + col] = bi;
     }
   }
-  if constexpr (kStore) return;
+  if constexpr (kStore) {
+    if (rms && a.ksplit > 1 && slab == 0) {
+      for (int rl = threadIdx.x; rl < C::kHRows; rl += 256)
+        if (r0 + rl < R)
+          a.part_ss[static_cast<size_t>(ks) * R + r0 + rl] =
+              (rowss[rl] + rowss[C::kHRows + rl]) + (rowss[2 * C::kHRows + rl] + rowss[3 * C::kHRows + rl]);
+    }
+    return;
+  }
   __syncthreads();
   for (int rl = threadIdx.x; rl < C::kHRows; rl += 256) {
     if (r0 + rl >= R) continue;
@@ -317,12 +370,20 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
 }
 
 // out = bf16(sum over the k splits in ascending order (+ residual)); 4 outputs per thread
+// (part_ss: the k-split shares of the rows' sums of squares, or null; N, K: columns of the product, input features)
 __global__ __launch_bounds__(256) void linear_reduce_kernel(const float* __restrict__ part, const __bf16* residual,
-                                                            __bf16* out, size_t n, int ksplit, int swiglu) {
+                                                            __bf16* out, size_t n, int ksplit, int swiglu,
+                                                            const float* __restrict__ part_ss, int N, int K, float rms_eps) {
   const size_t i = (static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
   if (i >= n) return;
   f32x4 sum = *reinterpret_cast<const f32x4*>(part + i);
   for (int ks = 1; ks < ksplit; ++ks) sum += *reinterpret_cast<const f32x4*>(part + static_cast<size_t>(ks) * n + i);
+  if (part_ss) {
+    const size_t r = i / N, R = n / N;
+    float tot = part_ss[r];
+    for (int ks = 1; ks < ksplit; ++ks) tot += part_ss[static_cast<size_t>(ks) * R + r];
+    sum *= 1.0f / sqrtf(tot / static_cast<float>(K) + rms_eps);
+  }
   if (swiglu) {                                                        // (gate, up) pairs -> [R, N/2]
     const bf16x2 act = {static_cast<__bf16>(silu_mul(sum[0], sum[1])), static_cast<__bf16>(silu_mul(sum[2], sum[3]))};
     *reinterpret_cast<bf16x2*>(out + i / 2) = act;
@@ -412,7 +473,7 @@ int linear_ksplit(int R, int K, int N) {
 
 size_t linear_workspace_bytes(int R, int K, int N) {
   const int ks = linear_ksplit(R, K, N);
-  return ks > 1 ? static_cast<size_t>(ks) * R * N * sizeof(float) : 0;
+  return ks > 1 ? static_cast<size_t>(ks) * R * (static_cast<size_t>(N) + 1) * sizeof(float) : 0;   // partial sums + row shares
 }
 
 int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream) {
@@ -428,6 +489,8 @@ int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream) {
   a.ksplit = linear_ksplit(d.R, d.K, d.N);
   a.part_f32 = static_cast<float*>(d.workspace);
   a.swiglu = d.epilogue == OURO_EPI_SWIGLU_PAIRS;
+  a.rms_eps = d.rms_eps > 0.f ? d.rms_eps : 0.f;
+  a.part_ss = a.part_f32 ? a.part_f32 + static_cast<size_t>(a.ksplit) * d.R * d.N : nullptr;
   LmPlan plan{};
   plan.slab = 128;
   plan.nslab = (d.N + 127) / 128;
@@ -445,7 +508,8 @@ int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream) {
   if (st != OURO_OK || a.ksplit == 1) return st;
   const size_t n = static_cast<size_t>(d.R) * d.N;
   hipLaunchKernelGGL(linear_reduce_kernel, dim3(static_cast<unsigned>((n / 4 + 255) / 256)), dim3(256), 0, stream,
-                     a.part_f32, a.residual, a.out, n, a.ksplit, a.swiglu);
+                     a.part_f32, a.residual, a.out, n, a.ksplit, a.swiglu, a.rms_eps > 0.f ? a.part_ss : nullptr, d.N, d.K,
+                     a.rms_eps);
   return check_launch();
 }
 

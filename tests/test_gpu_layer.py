@@ -152,6 +152,44 @@ def test_linear_swiglu_epilogue(monkeypatch, R, K, F, tiled, ksplit):
     assert np.abs(to_np64(out) - ref).max() <= tol
 
 
+@pytest.mark.parametrize("R,K,N,tiled,ksplit,with_res,swiglu", [
+    (64, 320, 264, True, 0, False, False),
+    (64, 4096, 256, True, 0, True, False),      # the heuristic splits the k range (2 slabs): row sums go through the reduction
+    (128, 320, 136, False, 0, True, False),     # 128-row instance
+    (70, 320, 272, True, 3, False, True),       # split k range, ragged rows, with the SwiGLU gate on top
+    (33, 192, 48, False, 0, False, True),
+    (1, 64, 8, False, 0, False, False),
+])
+def test_linear_with_rmsnorm_folded_in(monkeypatch, R, K, N, tiled, ksplit, with_res, swiglu):
+    """RMSNorm of the input inside the projection: rows of the product scaled by 1/sqrt(mean(x^2) + eps), the gain folded
+    into the weight at load time.  Reference: the oracle's RMSNorm followed by its projection, with the folded weight
+    the GPU gets (so that the comparison isolates the kernel), and separately the unfolded chain at a looser bound."""
+    if ksplit:
+        monkeypatch.setenv("OURO_LINEAR_KSPLIT", str(ksplit))
+    rng = np.random.default_rng(R * 3 + K + N)
+    eps = 1e-5
+    x = _bf(rng.standard_normal((R, K)) * 1.7)
+    w = _bf(rng.standard_normal((N, K)) * 0.05)
+    g = _bf(1 + 0.2 * rng.standard_normal(K))
+    res = _bf(rng.standard_normal((R, N))) if with_res else None
+    w_fold_d = ob.fold_rmsnorm_gain(_up(w), _up(g))
+    w_fold = w_fold_d.float().cpu().numpy().astype(np.float64)
+    ones = np.ones(K)
+    pre = LO.linear(LO.rmsnorm(x, ones, eps), w_fold)                   # = rinv * (x . w_fold^T), fp64
+    pre_unfolded = LO.linear(LO.rmsnorm(x, g, eps), w)
+    post = (lambda y: LO.silu_mul(np.concatenate([y[:, 0::2], y[:, 1::2]], axis=1))) if swiglu else (lambda y: y)
+    ref = post(pre) + (0 if res is None else res)
+    ref_unfolded = post(pre_unfolded) + (0 if res is None else res)
+    w_use = ob.ouro_lmhead_pack_w(w_fold_d) if tiled else w_fold_d
+    out = ob.ouro_linear(_up(x), w_use, residual=None if res is None else _up(res), swiglu=swiglu, rms_eps=eps)
+    torch.cuda.synchronize()
+    got = to_np64(out)
+    tol = np.abs(ref).max() * BF16_EPS + 1e-4
+    assert np.abs(got - ref).max() <= tol
+    # folding rounds every weight once more (relative 2^-9 each, incoherent over K terms)
+    assert np.abs(got - ref_unfolded).max() <= tol + 4 * BF16_EPS * np.abs(pre_unfolded).max()
+
+
 @pytest.mark.parametrize("ksplit", [2, 3, 5])
 def test_linear_uneven_k_split(monkeypatch, ksplit):
     """The k range split over workgroups, including splits that do not divide the 5 k-tiles evenly (one share empty)."""
@@ -159,7 +197,7 @@ def test_linear_uneven_k_split(monkeypatch, ksplit):
     rng = np.random.default_rng(ksplit)
     x, w, res = _bf(rng.standard_normal((70, 320))), _bf(rng.standard_normal((264, 320)) * 0.05), _bf(rng.standard_normal((70, 264)))
     ref = LO.linear(x, w, res)
-    ws = torch.full((ksplit * 70 * 264 * 4,), 0xA5, dtype=torch.uint8, device=DEV)     # contents must not matter
+    ws = torch.full((ksplit * 70 * (264 + 1) * 4,), 0xA5, dtype=torch.uint8, device=DEV)   # contents must not matter
     out = ob.ouro_linear(_up(x), _up(w), residual=_up(res), workspace=ws)
     torch.cuda.synchronize()
     assert np.abs(to_np64(out) - ref).max() <= np.abs(ref).max() * BF16_EPS + 1e-4
@@ -233,6 +271,21 @@ def test_one_verifying_layer_chained_on_the_gpu():
     err2 = np.abs(to_np64(out2) - ref).max()
     print("layer chain, fused forms: max-abs err %.3g" % err2, flush=True)
     assert err2 <= 8 * BF16_EPS * scale
+
+    # ---- and with both RMSNorms folded into the projections that follow them: 7 calls for the layer
+    wqkv_f = ob.ouro_lmhead_pack_w(ob.fold_rmsnorm_gain(_up(wqkv), _up(g1)))
+    wgu_f = ob.ouro_lmhead_pack_w(ob.fold_rmsnorm_gain(ob.interleave_gate_up(_up(wgu[:F]), _up(wgu[F:])), _up(g2)))
+    qkv3 = ob.ouro_linear(x_d, wqkv_f, rms_eps=1e-5)
+    q3, k3, v3 = torch.empty_like(q_d), torch.empty_like(k_d), torch.empty_like(v_d)
+    ob.ouro_rope_block(q3, k3, meta, cu_d, qkv=qkv3, v_blk=v3)
+    att3 = ob.ouro_verify_attn(q3, _up(inp["k_cache"]), _up(inp["v_cache"]), cu_d, k3, v3, meta, int(lens.max()))
+    x1c = ob.ouro_linear(att3.view(R, Hd), ob.ouro_lmhead_pack_w(_up(wo)), residual=x_d)
+    act3 = ob.ouro_linear(x1c, wgu_f, swiglu=True, rms_eps=1e-5)
+    out3 = ob.ouro_linear(act3, ob.ouro_lmhead_pack_w(_up(wd)), residual=x1c)
+    torch.cuda.synchronize()
+    err3 = np.abs(to_np64(out3) - ref).max()
+    print("layer chain, norms folded into the projections: max-abs err %.3g" % err3, flush=True)
+    assert err3 <= 8 * BF16_EPS * scale
 
 
 def test_layer_ops_edge_shapes():
