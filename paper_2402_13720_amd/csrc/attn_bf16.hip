@@ -234,26 +234,24 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int chunk = x / nbg;
   const int bg = x - chunk * nbg;
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
-  const long cu0 = a.cu[b];
-  const int L = a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - cu0);
   const int T = a.T;
-  const int n = L + T;
-  const int k_begin = chunk * a.chunk;
-  if (k_begin >= n) return;                       // chunk slot beyond this sequence (uniform for the workgroup)
-  const int k_end = min(n, k_begin + a.chunk);
-  const int nchb = (n + a.chunk - 1) / a.chunk;   // chunks this sequence really has
-  const int fast_end = min(L, k_end);             // tiles that end by here lie wholly in the cache part of the window
-
-  unsigned char* ql = lds;                        // Q tile, shared
-  unsigned char* kl = lds + kQBytes + wave * kWaveLds;
-  unsigned char* vl = kl + kKBytes;
-  short* kpid = reinterpret_cast<short*>(lds + kMainLds);
   const int col = lane & 31, half = lane >> 5;
   const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
   const int row0 = rb * kRows;
 
   // ---- prologue loads: all of them are issued before anything waits, so that the workgroup pays one memory
-  // round trip, not one per item (phrase ids of the block keys, the Q tile, this lane's metadata, the first tile)
+  // round trip, not one per item.  First the ones that need nothing but the workgroup's indices (the sequence's
+  // offset and length, the phrase ids of the block keys, the Q tile, this lane's metadata): they are in flight
+  // while the offset and length arrive, which the first tile's addresses then need.  (A workgroup whose chunk slot
+  // lies beyond its sequence leaves right after; its few loads are in bounds and unused.)
+  // (offset and length are fetched with vector loads, through an index the compiler cannot see is uniform: a scalar
+  // load's result would have to be waited for at once, because the scalar registers it lands in are spilled)
+  int vzero;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
+  const long cu0_v = a.cu[b + vzero];
+  const int cu1_v = *reinterpret_cast<const int*>(a.cu + b + 1 + vzero);    // low word: a length fits 32 bits
+  int len_v = 0;
+  if (a.len) len_v = a.len[b + vzero];
   const short my_kpid = tid < T ? a.meta[static_cast<size_t>(b) * T + tid].phrase_id : static_cast<short>(0);
   u32x4 qreg[kRows * 16 / 256];                   // Q tile: 16 lanes per 256-byte row, 2 pieces per thread
 #pragma unroll
@@ -268,6 +266,24 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int rq = min(row0 + col, M - 1);
   const int tq = rq / G;
   const ouro_tok_meta mq = a.meta[static_cast<size_t>(b) * T + tq];
+  __builtin_amdgcn_sched_barrier(0);              // keep the loads above ahead of the wait for the length below
+  int c0lo = static_cast<int>(cu0_v), c0hi = static_cast<int>(cu0_v >> 32), c1lo = cu1_v;
+  asm volatile("" : "+v"(c0lo), "+v"(c0hi), "+v"(c1lo), "+v"(len_v));   // first use of the loaded values: here, not earlier
+  const long cu0 = (static_cast<long>(__builtin_amdgcn_readfirstlane(c0hi)) << 32) |
+                   static_cast<unsigned>(__builtin_amdgcn_readfirstlane(c0lo));
+  const int L = __builtin_amdgcn_readfirstlane(a.len ? len_v : c1lo - c0lo);   // a length fits 32 bits
+
+  const int n = L + T;
+  const int k_begin = chunk * a.chunk;
+  if (k_begin >= n) return;                       // chunk slot beyond this sequence (uniform for the workgroup)
+  const int k_end = min(n, k_begin + a.chunk);
+  const int nchb = (n + a.chunk - 1) / a.chunk;   // chunks this sequence really has
+  const int fast_end = min(L, k_end);             // tiles that end by here lie wholly in the cache part of the window
+
+  unsigned char* ql = lds;                        // Q tile, shared
+  unsigned char* kl = lds + kQBytes + wave * kWaveLds;
+  unsigned char* vl = kl + kKBytes;
+  short* kpid = reinterpret_cast<short*>(lds + kMainLds);
 
   // ---- staging: lane (kq = lane/16, c16 = lane%16) loads 16 B of 8 key rows per tile ----
   // Load i of a lane fetches key 4*i + kq of the tile, so one load instruction covers 4 adjacent
