@@ -499,9 +499,37 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
   const int chunk = x / nbg;
   const int bg = x - chunk * nbg;
   const int b = bg / a.Hkv, g = bg - b * a.Hkv;
-  const long cu0 = a.cu[b];
-  const int L = a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - cu0);
   const int T = a.T;
+  const int col = lane & 31, half = lane >> 5;
+  const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
+  const int row0 = rb * kRowsWg + 32 * rw;        // first row of this wave's block (may lie past M: duplicates)
+
+  // ---- prologue loads that need nothing but the workgroup's indices, as in the kernel above: the sequence's offset
+  // and length (vector loads; first use pinned below), the phrase ids of the block keys, this lane's metadata and its
+  // Q fragments straight into registers.  They are in flight while the offset and length arrive.
+  int vzero;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
+  const long cu0_v = a.cu[b + vzero];
+  const int cu1_v = *reinterpret_cast<const int*>(a.cu + b + 1 + vzero);    // low word: a length fits 32 bits
+  int len_v = 0;
+  if (a.len) len_v = a.len[b + vzero];
+  const short my_kpid = tid < T ? a.meta[static_cast<size_t>(b) * T + tid].phrase_id : static_cast<short>(0);
+  const int rq = min(row0 + col, M - 1);          // rows past M are computed on a duplicate and never stored
+  const int tq = rq / G;
+  const ouro_tok_meta mq = a.meta[static_cast<size_t>(b) * T + tq];
+  bf16x8 qf[8], kf[8], vf[8], pf0, pf1;
+  {
+    const __bf16* qp = a.q + ((static_cast<size_t>(b) * T + tq) * Hq + g * G + (rq - tq * G)) * kD + 8 * half;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+  }
+  __builtin_amdgcn_sched_barrier(0);              // keep the loads above ahead of the wait for the length below
+  int c0lo = static_cast<int>(cu0_v), c0hi = static_cast<int>(cu0_v >> 32), c1lo = cu1_v;
+  asm volatile("" : "+v"(c0lo), "+v"(c0hi), "+v"(c1lo), "+v"(len_v));   // first use of the loaded values: here, not earlier
+  const long cu0 = (static_cast<long>(__builtin_amdgcn_readfirstlane(c0hi)) << 32) |
+                   static_cast<unsigned>(__builtin_amdgcn_readfirstlane(c0lo));
+  const int L = __builtin_amdgcn_readfirstlane(a.len ? len_v : c1lo - c0lo);
+
   const int n = L + T;
   const int k_begin = chunk * a.chunk;
   if (k_begin >= n) return;                       // chunk slot beyond this sequence (uniform for the workgroup)
@@ -511,22 +539,7 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
 
   constexpr int kStageBytes4 = 4 * kWaveLds;      // one stage: 4 x (K tile, V^T tile)
   short* kpid = reinterpret_cast<short*>(lds + rows_main_lds<RW>());
-  const short my_kpid = tid < T ? a.meta[static_cast<size_t>(b) * T + tid].phrase_id : static_cast<short>(0);
-  const int col = lane & 31, half = lane >> 5;
-  const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
-  const int row0 = rb * kRowsWg + 32 * rw;        // first row of this wave's block (may lie past M: duplicates)
-
-  // ---- this lane's query row (its column of S^T): metadata, and its Q fragments straight into registers ----
-  const int rq = min(row0 + col, M - 1);          // rows past M are computed on a duplicate and never stored
-  const int tq = rq / G;
-  const ouro_tok_meta mq = a.meta[static_cast<size_t>(b) * T + tq];
   const int pidq = mq.phrase_id, boffq = mq.branch_off;
-  bf16x8 qf[8], kf[8], vf[8], pf0, pf1;
-  {
-    const __bf16* qp = a.q + ((static_cast<size_t>(b) * T + tq) * Hq + g * G + (rq - tq * G)) * kD + 8 * half;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
-  }
 
   const int kq = lane >> 4, c16 = lane & 15;      // staging roles, as in the kernel above
   const int row_base = 16 * (kq >> 1) + 4 * (kq & 1);
