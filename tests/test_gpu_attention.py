@@ -161,3 +161,29 @@ def test_workspace_is_reusable_across_shapes_and_calls():
                                       t["meta"], t["max_seqlen"], workspace=ws)
             torch.cuda.synchronize()
             assert np.abs(to_np64(out) - ref).max() <= 2e-2
+
+
+@pytest.mark.parametrize("cfg_id, kw", [
+    (1, dict(B=2, L=(0, 300))),                                  # fp32 kernel
+    (2, dict(B=2, Hq=4, Hkv=4, L=(100, 900))),                   # key-split bf16 kernel, several chunks
+    (4, dict(B=1, Hq=16, Hkv=2, L=(700, 700))),                  # row-split bf16 kernel (8 query heads per KV head)
+])
+@pytest.mark.parametrize("scale", [0.03, 0.25])
+def test_softmax_scale_given_by_the_caller(cfg_id, kw, scale):
+    """softmax_scale > 0 replaces the default 1/sqrt(D); both sides get the same value.  A flatter and a sharper
+    softmax than the default (0.088 / 0.125) move the result well outside the tolerance if the scale is ignored."""
+    from paper_2402_13720_amd import binding as ob
+    from gpu_util import upload_attention
+    cfg = W.scaled(W.CONFIGS[cfg_id], **kw)
+    inp = W.make_attention_inputs(cfg, 900 + cfg_id)
+    t = upload_attention(cfg, inp, False)
+    lse = torch.full((cfg.B, cfg.Hq, cfg.T), float("nan"), dtype=torch.float32, device=DEV)
+    out = ob.ouro_verify_attn(t["q"], t["k_cache"], t["v_cache"], t["cu_seqlens"], t["k_blk"], t["v_blk"], t["meta"],
+                              max_seqlen=t["max_seqlen"], lse=lse, softmax_scale=scale)
+    torch.cuda.synchronize()
+    ref = O.verify_attention(inp["q"], inp["k_cache"], inp["v_cache"], inp["cu_seqlens"], inp["k_blk"], inp["v_blk"],
+                             inp["pid"], inp["boff"], scale=scale)
+    dflt = _oracle(inp)
+    assert np.abs(to_np64(out) - ref["out"]).max() <= attn_tol(cfg)
+    assert np.abs(to_np64(lse) - ref["lse"]).max() <= (1e-2 if cfg.dtype == "bf16" else 1e-5)
+    assert np.abs(dflt["out"] - ref["out"]).max() > 5 * attn_tol(cfg)          # the case can tell the two scales apart
