@@ -288,6 +288,24 @@ def test_one_verifying_layer_chained_on_the_gpu():
     assert err3 <= 8 * BF16_EPS * scale
 
 
+def test_rope_block_with_a_given_base():
+    """base > 0 replaces the default 10000 (a long-context model's 500000 here); the two differ far beyond the tolerance."""
+    cfg = W.scaled(W.CONFIGS[2], B=2, Hq=4, Hkv=2, L=(3000, 5000))
+    inp = W.make_attention_inputs(cfg, 555)
+    lens = np.diff(inp["cu_seqlens"]).astype(np.int32)
+    pos_ref = LO.block_positions(inp["pid"], inp["boff"], lens)
+    q_ref, q_dflt = LO.rope(inp["q"], pos_ref, base=500000.0), LO.rope(inp["q"], pos_ref)
+    k_ref = LO.rope(inp["k_blk"], pos_ref, base=500000.0)
+    q, k = _up(inp["q"]), _up(inp["k_blk"])
+    ob.ouro_rope_block(q, k, ob.pack_meta(inp["pid"], inp["boff"]).to(DEV), torch.from_numpy(inp["cu_seqlens"]).to(DEV),
+                       base=500000.0)
+    torch.cuda.synchronize()
+    xmax = float(np.abs(inp["q"]).max())
+    tol = 2.0 * xmax * (pos_ref.max() * 2.0 ** -23 + BF16_EPS)
+    assert np.abs(to_np64(q) - q_ref).max() <= tol and np.abs(to_np64(k) - k_ref).max() <= tol
+    assert np.abs(q_dflt - q_ref).max() > 20 * tol
+
+
 def test_layer_ops_edge_shapes():
     """One-token blocks, a single row, odd sizes that take the scalar paths, in-place RMSNorm."""
     rng = np.random.default_rng(31)
