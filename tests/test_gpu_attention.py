@@ -187,3 +187,24 @@ def test_softmax_scale_given_by_the_caller(cfg_id, kw, scale):
     assert np.abs(to_np64(out) - ref["out"]).max() <= attn_tol(cfg)
     assert np.abs(to_np64(lse) - ref["lse"]).max() <= (1e-2 if cfg.dtype == "bf16" else 1e-5)
     assert np.abs(dflt["out"] - ref["out"]).max() > 5 * attn_tol(cfg)          # the case can tell the two scales apart
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_bf16_seeded_random_shapes(monkeypatch, case):
+    """A seeded sweep over shapes nobody picked by hand: batch, head grouping, draft layout, cache lengths from empty to
+    a few tiles, the kernel variant, the chunk length and the cache layout all drawn per case."""
+    rng = np.random.default_rng(7000 + case)
+    Hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 1, 2, 4]))
+    gamma = int(rng.integers(1, 20))
+    K = int(rng.integers(0, 6))
+    bp = int(rng.integers(1, 7)) if K else 0
+    lo = int(rng.choice([0, 1, 31, 64, 200]))
+    hi = lo + int(rng.choice([0, 1, 33, 250, 700]))
+    cfg = W.scaled(W.CONFIGS[2], B=int(rng.integers(1, 5)), Hq=Hkv * G, Hkv=Hkv, L=(lo, hi), gamma=gamma, K=K, beta_p=bp)
+    monkeypatch.setenv("OURO_ATTN_RW", str(int(rng.choice([1, 2, 4]))))
+    chunk = int(rng.choice([0, 128, 256, 384]))
+    if chunk:
+        monkeypatch.setenv("OURO_ATTN_CHUNK", str(chunk))
+    inp = W.make_attention_inputs(cfg, 8000 + case, branch=str(rng.choice(["uniform", "last"])))
+    _check(cfg, inp, head_major=bool(rng.integers(0, 2)))

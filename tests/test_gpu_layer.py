@@ -336,3 +336,33 @@ def test_layer_ops_edge_shapes():
         torch.cuda.synchronize()
         ref = LO.rmsnorm(xr, g, 1e-6)
         assert np.abs(to_np64(xd) - ref).max() <= np.abs(ref).max() * BF16_EPS
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_linear_seeded_random_options(monkeypatch, case):
+    """A seeded sweep over ouro_linear's options together: rows on both sides of the 64-row instance boundary, ragged last
+    slabs, k splits that the heuristic would not pick, residual, the SwiGLU epilogue and the folded RMSNorm."""
+    rng = np.random.default_rng(600 + case)
+    R = int(rng.choice([1, 17, 64, 65, 128, 130]))
+    K = 64 * int(rng.integers(1, 8))
+    swiglu = bool(rng.integers(0, 2))
+    N = 16 * int(rng.integers(1, 30)) if swiglu else 8 * int(rng.integers(1, 60))
+    rms = bool(rng.integers(0, 2))
+    with_res = (not swiglu) and bool(rng.integers(0, 2))
+    ksplit = int(rng.choice([0, 0, 2, 3]))
+    if ksplit:
+        monkeypatch.setenv("OURO_LINEAR_KSPLIT", str(ksplit))
+    eps = 1e-5
+    x = _bf(rng.standard_normal((R, K)) * 1.3)
+    w = _bf(rng.standard_normal((N, K)) * 0.06)
+    res = _bf(rng.standard_normal((R, N))) if with_res else None
+    pre = LO.linear(LO.rmsnorm(x, np.ones(K), eps), w) if rms else LO.linear(x, w)
+    ref = LO.silu_mul(np.concatenate([pre[:, 0::2], pre[:, 1::2]], axis=1)) if swiglu else pre
+    if res is not None:
+        ref = ref + res
+    w_d = _up(w)
+    if rng.integers(0, 2):
+        w_d = ob.ouro_lmhead_pack_w(w_d)
+    out = ob.ouro_linear(_up(x), w_d, residual=None if res is None else _up(res), swiglu=swiglu, rms_eps=eps if rms else 0.0)
+    torch.cuda.synchronize()
+    assert np.abs(to_np64(out) - ref).max() <= np.abs(ref).max() * BF16_EPS + 1e-4

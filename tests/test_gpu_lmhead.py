@@ -132,3 +132,15 @@ def test_workspace_is_reusable_across_shapes_and_calls():
             arg = ob.ouro_lmhead_argmax(h_d, w_d, workspace=ws).cpu().numpy()
             bad = [r for r in range(R) if arg[r] != ref["argmax"][r] and ref["margin"][r] >= MARGIN]
             assert not bad
+
+
+@pytest.mark.parametrize("case", range(20))
+def test_bf16_seeded_random_shapes(case):
+    """A seeded sweep over shapes nobody picked by hand: row counts on both sides of the 64 / 128 / 256 boundaries that
+    select the kernel and its tiles, hidden sizes from one k-tile up, vocabularies with ragged last slabs, either layout."""
+    rng = np.random.default_rng(9000 + case)
+    R = int(rng.choice([1, 2, 31, 63, 64, 65, 100, 127, 128, 129, 200, 255, 256, 257, 300, 513]))
+    Hd = 64 * int(rng.integers(1, 9))
+    V = int(rng.choice([1, 7, 127, 128, 129, 255, 256, 257, 700, 1537]))
+    cfg = W.scaled(W.CONFIGS[2], B=1, Hq=Hd // 64, Hkv=Hd // 64, D=64, V=V)
+    _check(cfg, W.make_hidden(cfg, 50 + case, rows=R), W.make_lmhead_weight(cfg, 50 + case), tiled=bool(rng.integers(0, 2)))
