@@ -3,16 +3,19 @@
 
 A step = one pass of the whole hot path over one batch of synthetic input:
 ouro_verify_attn -> ouro_lmhead_argmax -> ouro_accept, enqueued back to back on one
-stream with inputs resident in HBM.  The default workload is the Llama-2-7B-shaped
-config (batch 1, 32 heads x 128, KV length 2048, draft block 64, vocabulary 32000).
+stream with inputs resident in HBM.  The headline workload is the largest single-GPU one,
+the batched Llama-2-7B-shaped verification (16 sequences with cached lengths in [512, 8192],
+draft blocks of 32 tokens, vocabulary 32000: 512 rows, 1.15 GB of K/V per step).
 
 Prints ONE JSON line: whole-job throughput in draft tokens verified per second, the
-roofline of the dominant kernel (measured with HIP events on the launch stream inside
-the timed region), and the CPU oracle timed on the host as a reported baseline.
+roofline of the kernel that takes the largest share of the step (measured with HIP events
+on the launch stream), the other main kernel beside it, one record per workload
+(``per_config``), and the CPU oracle timed on the host as a reported baseline.
 """
 from __future__ import annotations
 
 import argparse
+import ctypes as C
 import json
 import os
 import sys
@@ -22,8 +25,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+FP32_VALU_PEAK_TFLOPS = 157.3    # MI355X fp32 vector
+MACHINE_BALANCE = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # flop per byte above which bf16 work is MFMA-bound
 
 
 def parse_args():
@@ -31,15 +36,20 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (default 2: Llama-2-7B-shaped layer)")
+    ap.add_argument("--config", type=int, default=5,
+                    help="headline workload id 1..5 (default 5: batched Llama-2-7B-shaped verification, the largest)")
     ap.add_argument("--rotate", type=int, default=0, help="copies of KV cache and LM-head weight cycled through "
                     "(0: enough copies to exceed 1 GB, so that the 256 MB last-level cache cannot hold them)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU-oracle baseline leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the records of the other workloads")
     ap.add_argument("--branch", default="uniform", choices=["uniform", "last"])
     ap.add_argument("--event-every", type=int, default=8,
-                    help="record the per-call and per-kernel HIP events on every Nth timed step (each record is a "
-                         "packet on the stream and costs launch time; 1: every step)")
+                    help="inside the timed region, record the per-call and per-kernel HIP events on every Nth step only "
+                         "(each record is a packet on the stream and costs launch time); the kernel durations quoted "
+                         "come from a separate block of instrumented steps after it")
+    ap.add_argument("--instrumented-steps", type=int, default=64,
+                    help="untimed steps after the timed region with events around every call and main kernel (>= 50)")
     ap.add_argument("--with-layer", action="store_true",
                     help="also time the rest of one verifying layer around the attention (RMSNorm, fused QKV projection, "
                          "rotary embedding at the draft positions, attention, output projection, RMSNorm, SwiGLU MLP) and "
@@ -123,10 +133,74 @@ def cpu_baseline(cfg, inp, w, draws, budget_s):
     }
 
 
+class Hip:
+    """Raw HIP events: the library records them right around the main kernel of a call, on the launch stream."""
+
+    def __init__(self):
+        self.lib = C.CDLL("libamdhip64.so")
+        self.lib.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.lib.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.lib.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.lib.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def event(self):
+        e = C.c_void_p()
+        if self.lib.hipEventCreate(C.byref(e)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        return e
+
+    def record(self, e, stream):
+        if self.lib.hipEventRecord(e, stream) != 0:
+            raise RuntimeError("hipEventRecord failed")
+
+    def elapsed_us(self, e0, e1):
+        ms = C.c_float()
+        if self.lib.hipEventElapsedTime(C.byref(ms), e0, e1) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return ms.value * 1e3
+
+    def destroy(self, events):
+        for e in events:
+            self.lib.hipEventDestroy(e)
+
+
+def measured_peaks(ob, torch, hip):
+    """What a plain streaming read of 2 GiB and a bare bf16 matrix-core loop reach on this GPU (the library's probes)."""
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+    hs = stream.cuda_stream or None
+    nbytes = 2 << 30
+    buf = torch.ones(nbytes // 4, dtype=torch.int32, device=dev)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    e0, e1 = hip.event(), hip.event()
+    out = {}
+
+    def timed(call, iters, warm):
+        for _ in range(warm):
+            call()
+        hip.record(e0, hs)
+        for _ in range(iters):
+            if call() != 0:
+                raise RuntimeError("probe failed")
+        hip.record(e1, hs)
+        torch.cuda.synchronize()
+        return hip.elapsed_us(e0, e1) / iters
+
+    us = timed(lambda: ob.lib.ouro_probe_stream_read(buf.data_ptr(), nbytes, sink.data_ptr(), hs), 20, 5)
+    out["hbm_stream_read_GBs"] = nbytes / us / 1e3
+    out["hbm_stream_read"] = "2 GiB, 16-byte loads, 16 KB per wave in flight, 2048 workgroups; %.1f us" % us
+    wgs, rounds = 1024, 2048
+    us = timed(lambda: ob.lib.ouro_probe_mfma_bf16(wgs, rounds, sink.data_ptr(), hs), 10, 3)
+    out["mfma_bf16_loop_TFLOPs"] = wgs * 4 * rounds * 16 * 32768.0 / us / 1e6
+    out["mfma_bf16_loop"] = "%d workgroups x 4 waves x %d x 16 v_mfma_f32_32x32x16_bf16 on register operands; %.1f us" % (wgs, rounds, us)
+    hip.destroy([e0, e1])
+    del buf
+    return out
+
+
 def time_lmhead_rows(cfg, ob, torch, ws, rows_list, iters=60, warm=60):
     """ouro_lmhead_argmax alone at large row counts R (hidden ~ N(0,1)), the weight copies cycled through as in the
     step.  Returns one record per R: microseconds per call (whole call, both kernels) and the bf16 MFMA fraction."""
-    import ctypes as C
     dev = torch.device("cuda:0")
     out = []
     stream = torch.cuda.current_stream()
@@ -219,22 +293,52 @@ def load_traffic(workload_key):
         return None
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus %d is not supported (use --gpus 1)." % args.gpus,
-              file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
-    import torch
-    from paper_2402_13720_amd import binding as ob, workloads as W
+def attn_kernel_name(cfg):
+    if cfg.dtype != "bf16":
+        return "attn_f32_kernel"
+    return "attn_bf16_kernel" if cfg.T * (cfg.Hq // cfg.Hkv) <= 64 else "attn_bf16_rows_kernel"
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
+
+def lmhead_kernel_name(cfg):
+    if cfg.dtype != "bf16":
+        return "lmhead_f32_kernel"
+    return "lmhead_bf16_kernel" if cfg.R <= 128 else "lmhead_bf16_tile_kernel"
+
+
+def kernel_roofline(kind, cfg, kernel_us, call_us, bytes_, flops, traffic, peaks, extra=None):
+    """Roofline object of one main kernel.  The bound is the one its arithmetic intensity puts it under: HBM below the
+    machine balance (~312 flop/byte for bf16), the matrix cores above it (the fp32 workload: the vector ALU)."""
+    gbs = bytes_ / kernel_us / 1e3
+    tfl = flops / kernel_us / 1e6
+    intensity = flops / bytes_
+    if cfg.dtype == "bf16" and intensity >= MACHINE_BALANCE:
+        bound, achieved, peak, unit = "mfma", tfl, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+        measured = peaks.get("mfma_bf16_loop_TFLOPs") if peaks else None
+    else:
+        bound, achieved, peak, unit = "hbm", gbs, HBM_PEAK_GBS, "GB/s"
+        measured = peaks.get("hbm_stream_read_GBs") if peaks else None
+    r = {"kernel": "%s (main kernel of %s)" % (attn_kernel_name(cfg) if kind == "attn" else lmhead_kernel_name(cfg),
+                                               "ouro_verify_attn" if kind == "attn" else "ouro_lmhead_argmax"),
+         "bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+         "traffic": traffic, "kernel_us": kernel_us, "whole_call_us": call_us,
+         "frac_whole_call": achieved / peak * kernel_us / call_us,
+         "frac_of_measured_peak": (achieved / measured) if measured else None,
+         "algorithmic_bytes": bytes_, "flops": flops, "flop_per_byte": intensity,
+         "hbm_GBs": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
+         "mfma_TFLOPs": tfl if cfg.dtype == "bf16" else None,
+         "mfma_frac": tfl / MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else None}
+    if extra:
+        r.update(extra)
+    return r
+
+
+def run_config(cfg_id, args, ob, W, torch, hip, peaks, headline):
+    """Set one workload up on the device, run W warm-up + K timed steps (value), then the instrumented block (kernel and
+    call durations).  Returns the record of the workload; the headline also gets the graph replay and the options."""
+    import numpy as np
     dev = torch.device("cuda:0")
-    cfg = W.CONFIGS[args.config]
-    seed = W.seed_for(args.config)
+    cfg = W.CONFIGS[cfg_id]
+    seed = W.seed_for(cfg_id)
     dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
 
     inp = W.make_attention_inputs(cfg, seed, branch=args.branch)
@@ -245,7 +349,7 @@ def main():
     max_seqlen = int(seqlens.max())
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if headline and not args.no_cpu_baseline:
         cpu = cpu_baseline(cfg, inp, w, draws, args.cpu_seconds)
 
     # ---- device-resident inputs; KV cache and W in several copies that the steps cycle through ----
@@ -261,7 +365,8 @@ def main():
     kcs = [kc0] + [kc0.clone() for _ in range(nrot - 1)]
     vcs = [vc0] + [vc0.clone() for _ in range(nrot - 1)]
     ws = [w0] + [w0.clone() for _ in range(nrot - 1)]
-    if args.w_layout == "tiled" and cfg.dtype == "bf16":
+    tiled = args.w_layout == "tiled" and cfg.dtype == "bf16"
+    if tiled:
         ws = [ob.ouro_lmhead_pack_w(x) for x in ws]       # load-time step, outside the timed region
         torch.cuda.synchronize()
         del w0
@@ -276,28 +381,28 @@ def main():
     ws_lm = ob.alloc_workspace(ob.ouro_lmhead_argmax_workspace(hidden, ws[0]), dev)
     acc_out = ob.alloc_accept_outputs(cfg.B, cfg.gamma, cfg.K, cfg.beta_p, dev)
 
-    # draft ids: half of the block positions carry the token they will be compared with (the greedy
-    # token of their parent row); the other half are uniform.  Values do not affect timing.
+    # Draft ids: half of the block positions carry the token they will be compared with, the other half are uniform
+    # (values do not affect timing).  The token a position is compared with is taken from the library itself: a first
+    # acceptance call on the uniform draft returns, per phrase, the target's greedy token at each of its positions
+    # (the `repaired` by-product); the main draft is a plain sequence, position i follows position i-1.
     ob.ouro_verify_attn(q, kcs[0], vcs[0], cu, k_blk, v_blk, meta, max_seqlen, out=out, workspace=ws_attn,
                         head_major=head_major)
     ob.ouro_lmhead_argmax(hidden, ws[0], argmax_out=arg, workspace=ws_lm)
+    tok0 = torch.from_numpy(draws["tok"]).to(dev)
+    probe_out = dict(acc_out)
+    probe_out.update(ob.alloc_pool_outputs(cfg.B, cfg.gamma, cfg.K, cfg.beta_p, dev))
+    ob.ouro_accept(tok0, arg.view(cfg.B, cfg.T), meta, root, cfg.gamma, cfg.K, cfg.beta_p, outs=probe_out)
     torch.cuda.synchronize()
-    amax = arg.cpu().numpy().reshape(cfg.B, cfg.T)
-    exp = np.empty_like(amax)
-    for b in range(cfg.B):
-        for t in range(cfg.T):
-            if inp["pid"][b, t] == 0:
-                p = t - 1
-            elif t > 0 and inp["pid"][b, t - 1] == inp["pid"][b, t]:
-                p = t - 1
-            else:
-                p = int(inp["boff"][b, t])
-            exp[b, t] = draws["root_pred"][b] if p < 0 else amax[b, p]
-    tok = torch.from_numpy(W.plant_tokens(draws["tok"], draws["chosen"], exp)).to(dev)
+    amax = arg.view(cfg.B, cfg.T)
+    expected = torch.empty_like(amax)
+    expected[:, 0] = root
+    expected[:, 1:cfg.gamma] = amax[:, :cfg.gamma - 1]
+    if cfg.K:
+        expected[:, cfg.gamma:] = probe_out["repaired"][:, :, 1:].reshape(cfg.B, cfg.K * cfg.beta_p)
+    tok = torch.from_numpy(W.plant_tokens(draws["tok"], draws["chosen"], expected.cpu().numpy())).to(dev)
 
     stream = torch.cuda.current_stream()
     hs = stream.cuda_stream or None
-    import ctypes as C
     # descriptors are built once per rotated copy; a step is then three C-ABI calls
     d_attn = [ob.make_attn_desc(q, kcs[r], vcs[r], cu, k_blk, v_blk, meta, out, max_seqlen, None, ws_attn,
                                 head_major=head_major)
@@ -306,154 +411,194 @@ def main():
     d_acc = ob.make_accept_desc(tok, arg.view(cfg.B, cfg.T), meta, root, cfg.gamma, cfg.K, cfg.beta_p, acc_out)
     f_attn, f_lm, f_acc = ob.lib.ouro_verify_attn, ob.lib.ouro_lmhead_argmax, ob.lib.ouro_accept
 
-    # raw HIP events handed to the library: it records them right around the main kernel of a call,
-    # on the launch stream, so that kernel's duration is measured inside the timed region
-    hip = C.CDLL("libamdhip64.so")
-    hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
-    hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
-
-    def new_event():
-        e = C.c_void_p()
-        if hip.hipEventCreate(C.byref(e)) != 0:
-            raise RuntimeError("hipEventCreate failed")
-        return e
-
-    def elapsed_us(e0, e1):
-        ms = C.c_float()
-        if hip.hipEventElapsedTime(C.byref(ms), e0, e1) != 0:
-            raise RuntimeError("hipEventElapsedTime failed")
-        return ms.value * 1e3
-
-    every = max(1, args.event_every)
-    sampled = [i for i in range(args.steps) if i % every == 0]
-    kev = {i: [new_event() for _ in range(4)] for i in sampled}
-
     def step(i, ev=None, kv=None):
         r = i % nrot
         d_attn[r].ev_start, d_attn[r].ev_stop = (kv[0], kv[1]) if kv else (None, None)
         d_lm[r].ev_start, d_lm[r].ev_stop = (kv[2], kv[3]) if kv else (None, None)
         if ev is not None:
-            ev[0].record(stream)
+            hip.record(ev[0], hs)
         st = f_attn(C.byref(d_attn[r]), hs)
         if ev is not None:
-            ev[1].record(stream)
+            hip.record(ev[1], hs)
         st |= f_lm(C.byref(d_lm[r]), hs)
         if ev is not None:
-            ev[2].record(stream)
+            hip.record(ev[2], hs)
         st |= f_acc(C.byref(d_acc), hs)
         if ev is not None:
-            ev[3].record(stream)
+            hip.record(ev[3], hs)
         if st != 0:
             raise RuntimeError("a verification-step call failed (status bits %d)" % st)
 
-    for i in range(args.warmup):
+    steps, warmup = args.steps, args.warmup
+    every = max(1, args.event_every)
+    sampled = [i for i in range(steps) if i % every == 0]
+    ev_timed = {i: ([hip.event() for _ in range(4)], [hip.event() for _ in range(4)]) for i in sampled}
+    n_inst = max(50, args.instrumented_steps)
+    ev_inst = [([hip.event() for _ in range(4)], [hip.event() for _ in range(4)]) for _ in range(n_inst)]
+
+    # ---- W warm-up steps, then exactly K timed steps ----
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
-    events = {i: [torch.cuda.Event(enable_timing=True) for _ in range(4)] for i in sampled}
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i, events.get(i), kev.get(i))
+    for i in range(steps):
+        pair = ev_timed.get(i)
+        step(warmup + i, pair[0] if pair else None, pair[1] if pair else None)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # ---- untimed: a block of instrumented steps (events around every call and around both main kernels) ----
+    for i in range(n_inst):
+        step(warmup + steps + i, ev_inst[i][0], ev_inst[i][1])
+    torch.cuda.synchronize()
 
-    # ---- extra: the same steps replayed from a HIP graph (launch gaps removed); not the headline value ----
+    def durations(pairs):
+        calls = np.array([[hip.elapsed_us(c[j], c[j + 1]) for j in range(3)] for c, _ in pairs])
+        kern = np.array([[hip.elapsed_us(k[0], k[1]), hip.elapsed_us(k[2], k[3])] for _, k in pairs])
+        return calls, kern
+
+    calls_i, kern_i = durations(ev_inst)
+    calls_t, kern_t = durations(list(ev_timed.values()))
+    t_attn, t_lm, t_acc = (float(x) for x in calls_i.mean(axis=0))
+    k_attn, k_lm = (float(x) for x in kern_i.mean(axis=0))
+    for c, k in list(ev_timed.values()) + ev_inst:
+        hip.destroy(c + k)
+
+    # ---- extra (headline): the same steps replayed from a HIP graph (launch gaps removed); not the headline value ----
     graph_us = None
-    try:
-        side = torch.cuda.Stream()
-        side.wait_stream(stream)
-        with torch.cuda.stream(side):
-            hs_side = side.cuda_stream
+    if headline:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(stream)
+            with torch.cuda.stream(side):
+                hs_side = side.cuda_stream
 
-            def gstep(r):
-                d_attn[r].ev_start = d_attn[r].ev_stop = d_lm[r].ev_start = d_lm[r].ev_stop = None
-                return (f_attn(C.byref(d_attn[r]), hs_side) | f_lm(C.byref(d_lm[r]), hs_side)
-                        | f_acc(C.byref(d_acc), hs_side))
+                def gstep(r):
+                    d_attn[r].ev_start = d_attn[r].ev_stop = d_lm[r].ev_start = d_lm[r].ev_stop = None
+                    return (f_attn(C.byref(d_attn[r]), hs_side) | f_lm(C.byref(d_lm[r]), hs_side)
+                            | f_acc(C.byref(d_acc), hs_side))
 
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=side):
-                st = 0
-                for r in range(nrot):
-                    st |= gstep(r)
-            if st == 0:
-                reps = max(1, args.steps // nrot)
-                graph.replay()
-                torch.cuda.synchronize()
-                g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                g0.record(side)
-                for _ in range(reps):
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    st = 0
+                    for r in range(nrot):
+                        st |= gstep(r)
+                if st == 0:
+                    reps = max(1, steps // nrot)
                     graph.replay()
-                g1.record(side)
-                torch.cuda.synchronize()
-                graph_us = g0.elapsed_time(g1) * 1e3 / (reps * nrot)
-    except Exception as exc:      # graph capture is optional; report why it was skipped
-        graph_us = "unavailable: %s" % type(exc).__name__
+                    torch.cuda.synchronize()
+                    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    g0.record(side)
+                    for _ in range(reps):
+                        graph.replay()
+                    g1.record(side)
+                    torch.cuda.synchronize()
+                    graph_us = g0.elapsed_time(g1) * 1e3 / (reps * nrot)
+        except Exception as exc:      # graph capture is optional; report why it was skipped
+            graph_us = "unavailable: %s" % type(exc).__name__
 
     layer = None
-    if args.with_layer and cfg.dtype == "bf16":
-        us, wbytes, F = time_layer(cfg, ob, torch, q, k_blk, v_blk, kcs, vcs, cu, meta, max_seqlen, head_major,
-                                   args.steps)
+    if headline and args.with_layer and cfg.dtype == "bf16":
+        us, wbytes, F = time_layer(cfg, ob, torch, q, k_blk, v_blk, kcs, vcs, cu, meta, max_seqlen, head_major, steps)
         lbytes = wbytes + attn_algorithmic_bytes(cfg, total_rows)
         layer = {"us_per_layer": us, "mlp_width": F, "weight_bytes": wbytes, "algorithmic_bytes": lbytes,
                  "achieved_GBs": lbytes / us / 1e3, "frac_of_hbm_peak": lbytes / us / 1e3 / HBM_PEAK_GBS,
                  "how": "7 library calls (QKV with RMSNorm folded in, rotary + split, attention, o + residual, gate/up with RMSNorm folded in and the SwiGLU gate in its epilogue, down + residual), replayed from a HIP graph"}
-
     large_r = None
-    if args.lm_rows and cfg.dtype == "bf16":
+    if headline and args.lm_rows and cfg.dtype == "bf16":
         large_r = time_lmhead_rows(cfg, ob, torch, ws, [int(x) for x in args.lm_rows.split(",") if x])
 
-    ms_step = elapsed * 1e3 / args.steps
-    seg = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(3)] for ev in events.values()])   # ms
-    t_attn, t_lm, t_acc = (float(x) for x in seg.mean(axis=0))
-    tokens = cfg.R
-    # main-kernel durations (ms): attention split-KV kernel, LM-head weight-streaming kernel
-    k_attn = float(np.mean([elapsed_us(k[0], k[1]) for k in kev.values()])) * 1e-3
-    k_lm = float(np.mean([elapsed_us(k[2], k[3]) for k in kev.values()])) * 1e-3
-
-    lm_bytes = lmhead_algorithmic_bytes(cfg)
-    at_bytes = attn_algorithmic_bytes(cfg, total_rows)
-    lm_gbs = lm_bytes / (k_lm * 1e-3) / 1e9
-    at_gbs = at_bytes / (k_attn * 1e-3) / 1e9
-    lm_tflops = lmhead_flops(cfg) / (k_lm * 1e-3) / 1e12
-    at_tflops = attn_flops(cfg, seqlens) / (k_attn * 1e-3) / 1e12
+    ms_step = elapsed * 1e3 / steps
     workload = "cfg%d:%s" % (cfg.cfg_id, cfg.name)
-    lm_mfma_bound = cfg.R >= 312          # arithmetic intensity ~R flop/B against a machine balance of ~312
     traffic = load_traffic(workload) or {}
-    if lm_mfma_bound:
-        roofline = {"kernel": "lmhead_bf16_tile_kernel (main kernel of ouro_lmhead_argmax)", "bound": "mfma",
-                    "achieved": lm_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": lm_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic.get("lmhead_bytes"),
-                    "kernel_us": k_lm * 1e3, "algorithmic_bytes": lm_bytes}
-    else:
-        roofline = {"kernel": "lmhead_bf16_kernel (main kernel of ouro_lmhead_argmax)", "bound": "hbm",
-                    "achieved": lm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": lm_gbs / HBM_PEAK_GBS,
-                    "traffic": traffic.get("lmhead_bytes"), "kernel_us": k_lm * 1e3, "algorithmic_bytes": lm_bytes}
+    samples = {"kernel_us_from": "%d instrumented steps after the timed region (events around every call and main kernel)" % n_inst,
+               "kernel_us_std": None, "kernel_us_in_timed_region": None}
+    r_attn = kernel_roofline("attn", cfg, k_attn, t_attn, attn_algorithmic_bytes(cfg, total_rows), attn_flops(cfg, seqlens),
+                             traffic.get("attn_bytes"), peaks,
+                             {**samples, "kernel_us_std": float(kern_i[:, 0].std()),
+                              "kernel_us_in_timed_region": {"mean": float(kern_t[:, 0].mean()), "n": int(len(kern_t))},
+                              "combine_and_gaps_us": t_attn - k_attn,
+                              "whole_call_is": "main kernel + the launch that merges the chunk partials (when a sequence spans several chunks)"})
+    r_lm = kernel_roofline("lmhead", cfg, k_lm, t_lm, lmhead_algorithmic_bytes(cfg), lmhead_flops(cfg),
+                           traffic.get("lmhead_bytes"), peaks,
+                           {**samples, "kernel_us_std": float(kern_i[:, 1].std()),
+                            "kernel_us_in_timed_region": {"mean": float(kern_t[:, 1].mean()), "n": int(len(kern_t))},
+                            "whole_call_is": "main kernel + the cross-slab arg-max launch"})
+    rec = {
+        "workload": workload, "dtype": cfg.dtype, "rows": cfg.R, "step_us": ms_step * 1e3,
+        "tokens_per_s": cfg.R / (ms_step * 1e-3), "steps": steps, "warmup": warmup,
+        "call_us": {"ouro_verify_attn": t_attn, "ouro_lmhead_argmax": t_lm, "ouro_accept": t_acc},
+        "attn": r_attn, "lmhead": r_lm,
+        "accepted_per_sequence": acc_out["n_accept"].cpu().tolist()[:16],
+    }
+    extras = {"cfg": cfg, "ms_step": ms_step, "graph_us": graph_us, "layer": layer, "large_r": large_r, "cpu": cpu,
+              "total_rows": total_rows, "nrot": nrot, "every": every}
+    del kcs, vcs, ws, d_attn, d_lm
+    torch.cuda.empty_cache()
+    return rec, extras
+
+
+def brief(rec):
+    """The per_config form of a workload record: step time and both main kernels' fractions."""
+    def k(r):
+        return {"kernel": r["kernel"].split(" ")[0], "bound": r["bound"], "kernel_us": r["kernel_us"],
+                "whole_call_us": r["whole_call_us"], "frac": r["frac"], "frac_whole_call": r["frac_whole_call"],
+                "frac_of_measured_peak": r["frac_of_measured_peak"], "hbm_frac": r["hbm_frac"], "mfma_frac": r["mfma_frac"]}
+    return {"workload": rec["workload"], "dtype": rec["dtype"], "rows": rec["rows"], "step_us": rec["step_us"],
+            "tokens_per_s": rec["tokens_per_s"], "attn": k(rec["attn"]), "lmhead": k(rec["lmhead"]),
+            "accept_call_us": rec["call_us"]["ouro_accept"]}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (use --gpus 1)." % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2402_13720_amd import binding as ob, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    hip = Hip()
+    peaks = measured_peaks(ob, torch, hip)
+
+    # the other workloads first (their launches also bring the clocks up), the headline workload last
+    per_config = {}
+    if not args.no_per_config:
+        for cid in sorted(W.CONFIGS):
+            if cid != args.config:
+                rec, _ = run_config(cid, args, ob, W, torch, hip, peaks, headline=False)
+                per_config[cid] = brief(rec)
+    rec, x = run_config(args.config, args, ob, W, torch, hip, peaks, headline=True)
+    per_config[args.config] = brief(rec)
+    cfg = x["cfg"]
+
+    # the roofline object names the kernel that takes the largest share of the step; the other one sits beside it
+    dom, other = ("attn", "lmhead") if rec["attn"]["kernel_us"] >= rec["lmhead"]["kernel_us"] else ("lmhead", "attn")
     result = {
         "metric": "draft tokens verified per second (one verification step: attention + LM head/argmax + accept)",
-        "value": tokens / (ms_step * 1e-3),
+        "value": rec["tokens_per_s"],
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step,
-        "verify_step_latency_us": ms_step * 1e3,
-        "graph_replay_step_latency_us": graph_us,
+        "ms_per_step": x["ms_step"],
+        "verify_step_latency_us": x["ms_step"] * 1e3,
+        "graph_replay_step_latency_us": x["graph_us"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": workload, "B": cfg.B, "T": cfg.T, "gamma": cfg.gamma, "K": cfg.K, "beta": cfg.beta_p,
-                   "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D, "cache_rows": total_rows, "V": cfg.V,
-                   "branch": args.branch, "rotated_copies": nrot, "events_on_every_nth_step": every,
+        "config": {"workload": rec["workload"], "B": cfg.B, "T": cfg.T, "gamma": cfg.gamma, "K": cfg.K, "beta": cfg.beta_p,
+                   "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D, "cache_rows": x["total_rows"], "V": cfg.V,
+                   "branch": args.branch, "rotated_copies": x["nrot"], "events_on_every_nth_timed_step": x["every"],
                    "w_layout": args.w_layout if cfg.dtype == "bf16" else "row", "kv_layout": args.kv_layout},
-        "call_us": {"ouro_verify_attn": t_attn * 1e3, "ouro_lmhead_argmax": t_lm * 1e3, "ouro_accept": t_acc * 1e3},
-        "roofline": roofline,
-        "roofline_attn": {"kernel": "%s (main kernel of ouro_verify_attn)"
-                                    % ("attn_bf16_kernel" if cfg.T * (cfg.Hq // cfg.Hkv) <= 64 else "attn_bf16_rows_kernel"),
-                          "bound": "hbm",
-                          "achieved": at_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": at_gbs / HBM_PEAK_GBS,
-                          "traffic": traffic.get("attn_bytes"), "kernel_us": k_attn * 1e3,
-                          "algorithmic_bytes": at_bytes, "mfma_tflops": at_tflops},
-        "lmhead_mfma_frac": lm_tflops / MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else None,
-        "layer": layer,
-        "lmhead_large_R": large_r,
-        "cpu_baseline": cpu,
-        "accepted_per_sequence": acc_out["n_accept"].cpu().tolist()[:16],
+        "call_us": rec["call_us"],
+        "roofline": rec[dom],
+        "roofline_other_kernel": rec[other],
+        "measured_peaks": peaks,
+        "per_config": [per_config[c] for c in sorted(per_config)],
+        "layer": x["layer"],
+        "lmhead_large_R": x["large_r"],
+        "cpu_baseline": x["cpu"],
+        "accepted_per_sequence": rec["accepted_per_sequence"],
     }
     print(json.dumps(result))
 

@@ -21,8 +21,11 @@
  *     Descriptors themselves are HOST memory, read during the call only.
  *   - Calls only enqueue work on the given HIP stream (a hipStream_t passed as
  *     void*; NULL = the default stream).  They never allocate, free or
- *     synchronise, keep no state between calls, and may be called from several
- *     threads on different streams with disjoint outputs and workspaces.
+ *     synchronise, and may be called from several threads on different streams
+ *     with disjoint outputs and workspaces.  The library keeps nothing between
+ *     calls except, per device, the fact that the kernels' shared-memory limits
+ *     have been raised (done once, thread-safe, on the first launch on a device);
+ *     nothing is read from the process environment.
  *   - Return value: OURO_OK (0) or a negative OURO_E_* code.  On an error nothing
  *     has been enqueued, except OURO_E_HIP which reports a failed launch (the
  *     hipError_t is kept per thread for ouro_last_hip_error()).
@@ -40,7 +43,7 @@
 extern "C" {
 #endif
 
-#define OURO_VERSION 200 /* major*10000 + minor*100 + patch */
+#define OURO_VERSION 210 /* major*10000 + minor*100 + patch */
 
 /* Exported from libouro.so (everything else in the library has hidden visibility). */
 #define OURO_API __attribute__((visibility("default")))
@@ -97,7 +100,10 @@ typedef struct {
   int32_t Hq;                  /* query heads */
   int32_t Hkv;                 /* key/value heads, divides Hq */
   int32_t D;                   /* head dim: 128 (bf16) ; 64 or 128 (f32) */
-  int32_t max_seqlen;          /* host-side upper bound on every L_b (sizes the launch; no device read-back) */
+  int32_t max_seqlen;          /* host-side upper bound on every L_b (sizes the launch; no device read-back).  A
+                                  sequence whose device-side length exceeds it is attended over its first
+                                  max_seqlen cached tokens only: a stale bound gives a contained result, never an
+                                  access outside the workspace or the sequence's region */
   const void* q;               /* [B, T, Hq, D] */
   const void* k_cache;         /* [rows, Hkv, D] (or head-major, see kv_layout); sequence b in the region of rows
                                   cu_seqlens[b] .. cu_seqlens[b+1]-1 */
@@ -118,7 +124,10 @@ typedef struct {
                                   is room for tokens accepted later (ouro_kv_commit).  NULL: packed regions */
   int32_t kv_layout;           /* OURO_KV_ROW_MAJOR: caches are [rows, Hkv, D].  OURO_KV_HEAD_MAJOR: [Hkv, cache_rows, D],
                                   every (sequence, KV head) stream contiguous in memory, which HBM delivers fastest */
-  int32_t reserved0;           /* 0 */
+  int32_t plan_override;       /* 0: the library chooses the launch shape.  Tests and tuning runs may force it (bf16
+                                  only): bits 0..7 = 32-row query blocks per workgroup (1, 2 or 4; 0 = library's
+                                  choice), bits 8..31 = keys per workgroup / 128 (0 = library's choice).  The same
+                                  value must be given to the workspace query */
   int64_t cache_rows;          /* OURO_KV_HEAD_MAJOR: rows per KV head of the cache allocation (>= cu_seqlens[B]) */
 } ouro_attn_desc;
 
@@ -178,6 +187,11 @@ OURO_API int ouro_lmhead_pack_w(const void* w_row_major, void* w_tiled, int32_t 
 /* then yields b_j + 1 + Ahat'_j accepted tokens; the longest candidate wins, the main      */
 /* draft first and then the lowest phrase id on ties.  bonus = the prediction of the last   */
 /* accepted row (root_pred if nothing is accepted, -1 if root_pred is NULL as well).        */
+/* Every accepted token must equal a prediction of the target (the lossless property,       */
+/* Eq. (4)).  The one exception is declared by the caller: with root_pred NULL, main token   */
+/* 0 is the sequence's last, already accepted token and counts as accepted unchecked.  A     */
+/* phrase that hangs off the cached prefix (b_j = -1) then has nothing its first token       */
+/* could be checked against: that token counts as a mismatch and the phrase is never used.   */
 /* ------------------------------------------------------------------------------------ */
 typedef struct {
   uint32_t struct_size;        /* sizeof(ouro_accept_desc) */
@@ -189,8 +203,8 @@ typedef struct {
   const int32_t* draft_tok;    /* [B, T] */
   const int32_t* argmax;       /* [B, T] greedy token of every block row */
   const ouro_tok_meta* meta;   /* [B, T] */
-  const int32_t* root_pred;    /* [B] target's prediction after the cached prefix; NULL: positions that follow
-                                  the prefix directly (main token 0) count as accepted without a check */
+  const int32_t* root_pred;    /* [B] target's prediction after the cached prefix; NULL: main token 0 counts as
+                                  accepted without a check (see above) */
   int32_t* n_accept;           /* [B] number of accepted block tokens */
   int32_t* path;               /* [B] 0 = main draft only, j = main draft up to b_j then phrase j */
   int32_t* bonus;              /* [B] */
@@ -201,7 +215,7 @@ typedef struct {
                                   prediction, accepted or not (#Match, Eq. (10)) */
   /* Optional by-products for the phrase pool (Sec. 3.3, the two paragraphs after Eq. (10)); NULL to skip. */
   uint8_t* match_out;          /* [B, T]: 1 where the block token equals the target's greedy token at its position
-                                  (the indicator summed by Eq. (10)); unchecked positions count as 1 */
+                                  (the indicator summed by Eq. (10)); main token 0 without root_pred counts as 1 */
   int32_t* n_seg;              /* [B]: number of matching sub-segments of the discarded draft: maximal runs of
                                   matches among main positions > A.  n_seg, seg_start, seg_len: all or none */
   int32_t* seg_start;          /* [B, max(1, (gamma+1)/2)]: first main index of each run, ascending, -1 padded */
@@ -315,7 +329,11 @@ typedef struct {
   int32_t epilogue;            /* OURO_EPI_NONE or OURO_EPI_SWIGLU_PAIRS */
   float rms_eps;               /* > 0: the product's row r is scaled by 1 / sqrt(mean_k x[r, k]^2 + rms_eps) before the
                                   epilogue and the residual: RMSNorm of the input with its gain folded into w
-                                  (w[n, k] * gain[k], done by the caller at load time), in the same launch; <= 0: off */
+                                  (w[n, k] * gain[k]: ouro_fold_rmsnorm_gain, at load time), in the same launch; <= 0: off */
+  int32_t ksplit_override;     /* 0: the library chooses over how many workgroups the k range is split.  Tests and
+                                  tuning runs may force a count (clamped to K / 64); the same value must be given to
+                                  the workspace query */
+  int32_t reserved0;           /* 0 */
   const void* x;               /* [R, K] */
   const void* w;               /* [N, K] or tiled */
   const void* residual;        /* optional [R, N]; may alias out */
@@ -328,6 +346,16 @@ typedef struct {
 OURO_API size_t ouro_linear_workspace(const ouro_linear_desc* desc);   /* host-only; 0 if invalid or none needed */
 OURO_API int ouro_linear(const ouro_linear_desc* desc, void* hip_stream);
 
+/* Load-time re-layouts of projection weights (bf16, DEVICE pointers, 16-byte aligned, K a multiple of 8; out must  */
+/* not overlap the inputs).  Both are one pass over the weight and are meant to run once per weight, like            */
+/* ouro_lmhead_pack_w; the result may then be packed into the tiled form.                                            */
+/*   ouro_fold_rmsnorm_gain:   out[n, k] = bf16(w[n, k] * gain[k]) (fp32 product, one rounding): the weight that      */
+/*                             ouro_linear with rms_eps > 0 expects.                                                 */
+/*   ouro_interleave_gate_up:  out[2j, :] = w_gate[j, :], out[2j+1, :] = w_up[j, :] (j < F): the row order that       */
+/*                             OURO_EPI_SWIGLU_PAIRS expects.                                                        */
+OURO_API int ouro_fold_rmsnorm_gain(const void* w, const void* gain, void* out, int32_t N, int32_t K, void* hip_stream);
+OURO_API int ouro_interleave_gate_up(const void* w_gate, const void* w_up, void* out, int32_t F, int32_t K, void* hip_stream);
+
 /* out[r, f] = silu(gate_up[r, f]) * gate_up[r, F + f], silu(z) = z / (1 + exp(-z)) */
 typedef struct {
   uint32_t struct_size;
@@ -337,6 +365,18 @@ typedef struct {
   void* out;                   /* [R, F] */
 } ouro_silu_mul_desc;
 OURO_API int ouro_silu_mul(const ouro_silu_mul_desc* desc, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------ */
+/* Measurement aids (not part of the verification path; used by the benchmark to state    */
+/* every kernel's rate against what the machine at hand delivers, next to the datasheet).  */
+/* ------------------------------------------------------------------------------------ */
+/* One streaming read of `bytes` (>= 1 MiB; whole 16 KB blocks are read, 16-byte loads, 2048 workgroups) of the DEVICE
+ * buffer buf; sink: 4 writable DEVICE bytes (never written for ordinary data).  HBM rate = bytes / kernel time when
+ * the buffer exceeds the last-level cache. */
+OURO_API int ouro_probe_stream_read(const void* buf, size_t bytes, void* sink, void* hip_stream);
+/* A bare loop of bf16 32x32x16 matrix-core instructions on register operands: `workgroups` x 4 waves x `rounds` x 16
+ * instructions of 32768 flop each; sink as above. */
+OURO_API int ouro_probe_mfma_bf16(int32_t workgroups, int32_t rounds, void* sink, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------ */
 /* Host-side helpers                                                                     */

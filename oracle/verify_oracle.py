@@ -21,7 +21,9 @@ by-products against a hand-worked example, a regular-expression scan of the matc
 string and the definition of Eq. (10); the commit of accepted
 tokens against a hand-worked example (tests/golden), a concatenation written
 with library routines, and the property that a committed cache gives the next
-step the context of the accepted draft.  No function here is "parity unpinned".
+step the context of the accepted draft; the chained step (verify_step) against
+planted greedy tokens computed through a library attention routine and against
+the all-correct-draft invariant.  No function here is "parity unpinned".
 
 Conventions (readings of points the paper leaves open):
   * Block token t carries (pid[t], boff[t]).  pid 0 = main draft, main token i
@@ -214,7 +216,10 @@ def accept_one(tok: np.ndarray, argmax: np.ndarray, pid: np.ndarray, boff: np.nd
     accepted run (bonus) is the prediction of the last accepted row.
 
     root_pred None: main token 0 is the already-accepted last token of the sequence
-    (no check; it always counts as accepted), and so does any other child of the prefix.
+    (no check; it counts as accepted).  Nothing else is accepted without a check: Eq. (4)
+    needs every accepted token to equal a prediction of the target.  A phrase that hangs
+    off the prefix (b_j = -1) then has no prediction its first token could be compared
+    with; that token counts as a mismatch, so the phrase's run is empty and it never wins.
     """
     tok = np.asarray(tok).astype(np.int64)
     argmax = np.asarray(argmax).astype(np.int64)
@@ -225,7 +230,7 @@ def accept_one(tok: np.ndarray, argmax: np.ndarray, pid: np.ndarray, boff: np.nd
 
     def matches(t: int) -> bool:
         if par[t] == ROOT and root_pred is None:
-            return True                      # child of the prefix with no prediction to check against
+            return t == 0                    # no prediction to check against: only main token 0 is pre-accepted
         return bool(tok[t] == v[t])
 
     A = 0
@@ -289,7 +294,8 @@ def pool_byproducts_one(tok: np.ndarray, argmax: np.ndarray, pid: np.ndarray, bo
 
     match[t] = [tok[t] == v[t]] for every block position, v[t] being the target's greedy token at that
     position (the prediction of the row of t's parent); its sum over the main draft is #Match of Eq. (10).
-    A child of the prefix with no root_pred counts as a match, as in accept_one.
+    With no root_pred, main token 0 counts as a match and the first token of a phrase that hangs off the
+    prefix as a mismatch, as in accept_one.
 
     Segments: the maximal runs of consecutive matching positions inside the discarded part of the main
     draft, d_{A+1..gamma} (0-based positions >= A; position A itself is the first mismatch), as
@@ -307,7 +313,10 @@ def pool_byproducts_one(tok: np.ndarray, argmax: np.ndarray, pid: np.ndarray, bo
     par = parents(pid, boff)
     match = np.zeros(T, dtype=np.uint8)
     for t in range(T):
-        match[t] = 1 if (par[t] == ROOT and root_pred is None) or tok[t] == v[t] else 0
+        if par[t] == ROOT and root_pred is None:
+            match[t] = 1 if t == 0 else 0
+        else:
+            match[t] = 1 if tok[t] == v[t] else 0
     A = 0
     while A < gamma and match[A]:
         A += 1
@@ -395,13 +404,17 @@ def kv_commit(k_cache: np.ndarray, v_cache: np.ndarray, cu_seqlens: np.ndarray, 
 # --------------------------------------------------------------------------- #
 # The whole verification step, chained
 # --------------------------------------------------------------------------- #
-def verify_step(inp: Dict[str, np.ndarray], w: np.ndarray, tok: np.ndarray,
+def verify_step(inp: Dict[str, np.ndarray], w: np.ndarray, tok,
                 root_pred: Optional[np.ndarray], gamma: int, K: int, beta_p: int,
                 hidden_round=None) -> Dict[str, np.ndarray]:
-    """attention -> LM head -> argmax -> acceptance on one batch of inputs.
+    """attention -> LM head -> argmax -> acceptance on one batch of inputs (Sec. 3.2: one forward of the
+    target over the whole block, then Eq. (3) / Eq. (9)).
 
-    ``hidden_round`` optionally maps the fp64 attention output to the values the LM head
-    is fed (e.g. rounding to bf16, which is what the attention's bf16 output stores).
+    The hidden state of block row (b, t) is its attention output with the heads side by side,
+    hidden[b*T + t, h*D + d] = out[b, t, h, d].  ``hidden_round`` optionally maps that fp64 array to the values
+    the LM head is fed (e.g. rounding to bf16, which is what a bf16 attention output stores).
+    ``tok`` is the draft, int [B, T], or a function that builds it from the chain's own greedy tokens
+    [B, T] (workloads whose drafts are partly "the token the target will predict" need those first).
     """
     att = verify_attention(inp["q"], inp["k_cache"], inp["v_cache"], inp["cu_seqlens"],
                            inp["k_blk"], inp["v_blk"], inp["pid"], inp["boff"])
@@ -410,5 +423,8 @@ def verify_step(inp: Dict[str, np.ndarray], w: np.ndarray, tok: np.ndarray,
     if hidden_round is not None:
         hidden = hidden_round(hidden)
     lm = lmhead_argmax(hidden, w)
-    acc = accept(tok, lm["argmax"].reshape(B, T), inp["pid"], inp["boff"], root_pred, gamma, K, beta_p)
-    return {"attn": att, "lm": lm, "accept": acc}
+    amax = lm["argmax"].reshape(B, T)
+    if callable(tok):
+        tok = tok(amax)
+    acc = accept(tok, amax, inp["pid"], inp["boff"], root_pred, gamma, K, beta_p)
+    return {"attn": att, "hidden": hidden, "lm": lm, "tok": tok, "accept": acc}

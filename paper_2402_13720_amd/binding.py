@@ -31,7 +31,7 @@ class ouro_attn_desc(C.Structure):
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
         ("ev_start", C.c_void_p), ("ev_stop", C.c_void_p),
         ("seq_len", C.c_void_p),
-        ("kv_layout", C.c_int32), ("reserved0", C.c_int32), ("cache_rows", C.c_int64),
+        ("kv_layout", C.c_int32), ("plan_override", C.c_int32), ("cache_rows", C.c_int64),
     ]
 
 
@@ -89,6 +89,7 @@ class ouro_linear_desc(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32), ("dtype", C.c_int32), ("R", C.c_int32), ("K", C.c_int32), ("N", C.c_int32),
         ("w_layout", C.c_int32), ("epilogue", C.c_int32), ("rms_eps", C.c_float),
+        ("ksplit_override", C.c_int32), ("reserved0", C.c_int32),
         ("x", C.c_void_p), ("w", C.c_void_p), ("residual", C.c_void_p), ("out", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
@@ -127,8 +128,15 @@ def _load() -> C.CDLL:
                        ("ouro_linear", ouro_linear_desc), ("ouro_silu_mul", ouro_silu_mul_desc)):
         getattr(lib, name).restype = C.c_int
         getattr(lib, name).argtypes = [C.POINTER(desc), C.c_void_p]
+    for name in ("ouro_fold_rmsnorm_gain", "ouro_interleave_gate_up"):
+        getattr(lib, name).restype = C.c_int
+        getattr(lib, name).argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     lib.ouro_linear_workspace.restype = C.c_size_t
     lib.ouro_linear_workspace.argtypes = [C.POINTER(ouro_linear_desc)]
+    lib.ouro_probe_stream_read.restype = C.c_int
+    lib.ouro_probe_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.ouro_probe_mfma_bf16.restype = C.c_int
+    lib.ouro_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.ouro_validate_meta_host.restype = C.c_int
     lib.ouro_validate_meta_host.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.ouro_status_string.restype = C.c_char_p
@@ -184,10 +192,18 @@ def alloc_workspace(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
+def plan_override(row_blocks: int = 0, chunk_keys: int = 0) -> int:
+    """The descriptor field that forces the bf16 attention's launch shape in tests and tuning runs: row blocks per
+    workgroup (1, 2, 4; 0 = the library's choice) and keys per workgroup (a multiple of 128; 0 = the library's choice)."""
+    assert row_blocks in (0, 1, 2, 4) and chunk_keys % 128 == 0
+    return row_blocks | ((chunk_keys // 128) << 8)
+
+
 def make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen,
                    lse=None, workspace=None, softmax_scale: float = 0.0, seq_len=None,
-                   head_major: bool = False) -> ouro_attn_desc:
-    """head_major: k_cache / v_cache are [Hkv, cache_rows, D] tensors instead of [rows, Hkv, D]."""
+                   head_major: bool = False, plan: int = 0) -> ouro_attn_desc:
+    """head_major: k_cache / v_cache are [Hkv, cache_rows, D] tensors instead of [rows, Hkv, D].
+    plan: a plan_override() value (0: the library's heuristic)."""
     B, T, Hq, D = q.shape
     d = ouro_attn_desc()
     d.struct_size = C.sizeof(ouro_attn_desc)
@@ -201,25 +217,27 @@ def make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max
     d.workspace = _ptr(workspace)
     d.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     d.seq_len = _ptr(seq_len)
+    d.plan_override = int(plan)
     if head_major:
         d.kv_layout = OURO_KV_HEAD_MAJOR
         d.cache_rows = 0 if k_cache is None else k_cache.shape[1]
     return d
 
 
-def ouro_verify_attn_workspace(q, k_blk, max_seqlen: int) -> int:
+def ouro_verify_attn_workspace(q, k_blk, max_seqlen: int, plan: int = 0) -> int:
     """Workspace bytes for a call with these shapes (host-only query)."""
     B, T, Hq, D = q.shape
     d = ouro_attn_desc()
     d.struct_size = C.sizeof(ouro_attn_desc)
     d.dtype = _dtype_code(q)
     d.B, d.T, d.Hq, d.Hkv, d.D, d.max_seqlen = B, T, Hq, k_blk.shape[2], D, int(max_seqlen)
+    d.plan_override = int(plan)
     return int(lib.ouro_verify_attn_workspace(C.byref(d)))
 
 
 def ouro_verify_attn(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, max_seqlen: int,
                      out=None, lse=None, workspace=None, softmax_scale: float = 0.0, stream=None, seq_len=None,
-                     head_major: bool = False):
+                     head_major: bool = False, plan: int = 0):
     """Masked draft-block attention.  Tensors are device tensors laid out as in include/ouro.h.
     Allocates out/workspace with torch when not given; returns out."""
     assert seq_len is None or (seq_len.dtype == torch.int32 and seq_len.is_contiguous())
@@ -229,11 +247,11 @@ def ouro_verify_attn(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, max_se
     if out is None:
         out = torch.empty_like(q)
     if workspace is None:
-        need = ouro_verify_attn_workspace(q, k_blk, max_seqlen)
+        need = ouro_verify_attn_workspace(q, k_blk, max_seqlen, plan)
         if need:
             workspace = alloc_workspace(need, q.device)
     d = make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen, lse, workspace,
-                       softmax_scale, seq_len, head_major)
+                       softmax_scale, seq_len, head_major, plan)
     _check(lib.ouro_verify_attn(C.byref(d), _stream(stream)), "ouro_verify_attn")
     return out
 
@@ -415,22 +433,34 @@ def ouro_rmsnorm(x, gain, eps: float, out=None, stream=None):
 OURO_EPI_NONE, OURO_EPI_SWIGLU_PAIRS = 0, 1
 
 
-def interleave_gate_up(w_gate: torch.Tensor, w_up: torch.Tensor) -> torch.Tensor:
+def ouro_interleave_gate_up(w_gate: torch.Tensor, w_up: torch.Tensor, stream=None) -> torch.Tensor:
     """[F, K] gate and up weights -> [2F, K] with rows (gate_0, up_0, gate_1, up_1, ..): the layout the
-    swiglu epilogue of ouro_linear expects.  A load-time step."""
-    assert w_gate.shape == w_up.shape
-    return torch.stack([w_gate, w_up], dim=1).reshape(2 * w_gate.shape[0], w_gate.shape[1]).contiguous()
+    swiglu epilogue of ouro_linear expects.  A load-time step (one library launch)."""
+    assert w_gate.shape == w_up.shape and w_gate.dtype == w_up.dtype == torch.bfloat16
+    assert w_gate.is_contiguous() and w_up.is_contiguous()
+    F, K = w_gate.shape
+    out = torch.empty(2 * F, K, dtype=w_gate.dtype, device=w_gate.device)
+    _check(lib.ouro_interleave_gate_up(_ptr(w_gate), _ptr(w_up), _ptr(out), F, K, _stream(stream)),
+           "ouro_interleave_gate_up")
+    return out
 
 
-def fold_rmsnorm_gain(w: torch.Tensor, gain: torch.Tensor) -> torch.Tensor:
-    """w[n, k] * gain[k] in fp32, rounded once to w's dtype: the weight ouro_linear(rms_eps=...) expects.  Load time."""
-    return (w.float() * gain.float()[None, :]).to(w.dtype).contiguous()
+def ouro_fold_rmsnorm_gain(w: torch.Tensor, gain: torch.Tensor, stream=None) -> torch.Tensor:
+    """bf16(w[n, k] * gain[k]): the weight ouro_linear(rms_eps=...) expects.  A load-time step (one library launch)."""
+    assert w.dtype == gain.dtype == torch.bfloat16 and w.is_contiguous() and gain.is_contiguous()
+    N, K = w.shape
+    assert gain.shape == (K,)
+    out = torch.empty_like(w)
+    _check(lib.ouro_fold_rmsnorm_gain(_ptr(w), _ptr(gain), _ptr(out), N, K, _stream(stream)), "ouro_fold_rmsnorm_gain")
+    return out
 
 
-def ouro_linear(x, w, residual=None, out=None, stream=None, workspace=None, swiglu: bool = False, rms_eps: float = 0.0):
+def ouro_linear(x, w, residual=None, out=None, stream=None, workspace=None, swiglu: bool = False, rms_eps: float = 0.0,
+                ksplit: int = 0):
     """out = x . w^T (+ residual); w is a [N, K] bf16 tensor or a TiledWeight.  swiglu: w holds interleaved
     (gate, up) rows and out [R, N/2] = silu(gate) * up.  rms_eps > 0: rows of the product scaled by
-    1/sqrt(mean(x^2) + rms_eps) (RMSNorm of x with the gain folded into w)."""
+    1/sqrt(mean(x^2) + rms_eps) (RMSNorm of x with the gain folded into w).  ksplit > 0 forces the number of
+    workgroups the k range is split over (tests, tuning)."""
     assert x.is_contiguous() and x.dtype == torch.bfloat16
     tiled = isinstance(w, TiledWeight)
     N, K = (w.V, w.Hd) if tiled else tuple(w.shape)
@@ -444,6 +474,7 @@ def ouro_linear(x, w, residual=None, out=None, stream=None, workspace=None, swig
     d.w_layout = OURO_W_TILED if tiled else OURO_W_ROW_MAJOR
     d.epilogue = OURO_EPI_SWIGLU_PAIRS if swiglu else OURO_EPI_NONE
     d.rms_eps = float(rms_eps)
+    d.ksplit_override = int(ksplit)
     d.x, d.w, d.residual, d.out = _ptr(x), _ptr(w.data if tiled else w), _ptr(residual), _ptr(out)
     if workspace is None:
         need = int(lib.ouro_linear_workspace(C.byref(d)))

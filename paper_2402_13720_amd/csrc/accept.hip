@@ -47,7 +47,9 @@ __global__ __launch_bounds__(64) void accept_kernel(ouro_accept_desc d) {
       parent = within == 0 ? static_cast<int>(meta[t].branch_off) : t - 1;
     }
     bool m;
-    if (parent < 0) m = have_root ? (tok[t] == root) : true;
+    // a position right after the prefix: checked against root_pred; without one, only main token 0 (declared
+    // accepted by the caller) passes, a phrase hanging off the prefix has nothing to be checked against and fails
+    if (parent < 0) m = have_root ? (tok[t] == root) : (t == 0);
     else m = tok[t] == arg[parent];
     match[t] = m ? 1 : 0;
   }

@@ -81,6 +81,8 @@ struct AttnArgs {
   int T, Hq, Hkv, G, M;
   int nrb, nch, chunk;
   int rows_wg;         // query rows per workgroup (32 x row blocks per workgroup)
+  int max_seqlen;      // the host's bound on every length: grid, chunk slots and workspace were sized from it, so a
+                       // longer device-side length is cut to it (a stale bound must not reach past any of them)
   float scale_log2;
 };
 
@@ -271,7 +273,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   asm volatile("" : "+v"(c0lo), "+v"(c0hi), "+v"(c1lo), "+v"(len_v));   // first use of the loaded values: here, not earlier
   const long cu0 = (static_cast<long>(__builtin_amdgcn_readfirstlane(c0hi)) << 32) |
                    static_cast<unsigned>(__builtin_amdgcn_readfirstlane(c0lo));
-  const int L = __builtin_amdgcn_readfirstlane(a.len ? len_v : c1lo - c0lo);   // a length fits 32 bits
+  const int L = min(__builtin_amdgcn_readfirstlane(a.len ? len_v : c1lo - c0lo), a.max_seqlen);   // a length fits 32 bits
 
   const int n = L + T;
   const int k_begin = chunk * a.chunk;
@@ -528,7 +530,7 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
   asm volatile("" : "+v"(c0lo), "+v"(c0hi), "+v"(c1lo), "+v"(len_v));   // first use of the loaded values: here, not earlier
   const long cu0 = (static_cast<long>(__builtin_amdgcn_readfirstlane(c0hi)) << 32) |
                    static_cast<unsigned>(__builtin_amdgcn_readfirstlane(c0lo));
-  const int L = __builtin_amdgcn_readfirstlane(a.len ? len_v : c1lo - c0lo);
+  const int L = min(__builtin_amdgcn_readfirstlane(a.len ? len_v : c1lo - c0lo), a.max_seqlen);
 
   const int n = L + T;
   const int k_begin = chunk * a.chunk;
@@ -764,8 +766,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
   // The first batch is addressed without the sequence length (the workspace holds a.nch slots per
   // group, so every slot is readable), which puts its loads in flight together with the length's.
   load4(0, a.nch - 1);
-  const int n = (a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - a.cu[b])) + a.T;
-  const int nchb = (n + a.chunk - 1) / a.chunk;
+  const int n = min(a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - a.cu[b]), a.max_seqlen) + a.T;
+  const int nchb = (n + a.chunk - 1) / a.chunk;   // <= a.nch: the length is cut to the bound a.nch was sized from
   if (nchb == 1) return;                            // written directly by the main kernel
   merge4(0, nchb);
   for (int ch0 = 4; ch0 < nchb; ch0 += 4) {
@@ -810,9 +812,10 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
   a.n_x = d.B * d.Hkv * plan.nch;
   a.scale_log2 = scale * 1.4426950408889634f;
   a.rows_wg = plan.rows_wg;
+  a.max_seqlen = d.max_seqlen;
   const unsigned grid = static_cast<unsigned>((a.n_x + 7) / 8) * 8u * plan.nrb;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static DeviceOnce once;
+  const int ready = device_once(once, [] {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e == hipSuccess)
@@ -821,9 +824,9 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
     if (e == hipSuccess)
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_rows_kernel<4>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds_bytes<4>());
-    if (e != hipSuccess) return hip_failed(e);
-    attr_set = true;
-  }
+    return e == hipSuccess ? static_cast<int>(OURO_OK) : hip_failed(e);
+  });
+  if (ready != OURO_OK) return ready;
   if (d.ev_start && hipEventRecord(static_cast<hipEvent_t>(d.ev_start), stream) != hipSuccess) return hip_failed(hipGetLastError());
   if (plan.rw == 4)
     hipLaunchKernelGGL(attn_bf16_rows_kernel<4>, dim3(grid), dim3(256), rows_lds_bytes<4>(), stream, a);

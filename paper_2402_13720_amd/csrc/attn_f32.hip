@@ -25,7 +25,8 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(ouro_attn_desc d, float sc
   const int T = d.T, Hq = d.Hq, Hkv = d.Hkv;
   const int g = h / (Hq / Hkv);
   const long cu0 = d.cu_seqlens[b];
-  const int L = d.seq_len ? d.seq_len[b] : static_cast<int>(d.cu_seqlens[b + 1] - cu0);
+  // (cut to the host's bound like the bf16 kernels, so that both precisions treat a stale bound alike)
+  const int L = min(d.seq_len ? d.seq_len[b] : static_cast<int>(d.cu_seqlens[b + 1] - cu0), d.max_seqlen);
   const int n = L + T;
   const float* q = static_cast<const float*>(d.q) + ((static_cast<size_t>(b) * T + t) * Hq + h) * D;
   // cache addressing: [rows, Hkv, D] or [Hkv, rows, D]

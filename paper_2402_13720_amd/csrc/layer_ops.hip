@@ -183,7 +183,47 @@ __global__ __launch_bounds__(256) void silu_mul_kernel(ouro_silu_mul_desc d) {
   }
 }
 
+// ---- load-time re-layouts of projection weights (run once per weight; 16 bytes = 8 bf16 per thread) ----
+typedef __bf16 wvec8 __attribute__((ext_vector_type(8)));
+
+// out[n, k] = bf16(w[n, k] * gain[k]): the gain of an RMSNorm folded into the projection that follows it
+__global__ __launch_bounds__(256) void fold_gain_kernel(const __bf16* __restrict__ w, const __bf16* __restrict__ gain,
+                                                        __bf16* __restrict__ out, size_t n8, int k8) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= n8) return;
+  const wvec8 x = reinterpret_cast<const wvec8*>(w)[i];
+  const wvec8 g = reinterpret_cast<const wvec8*>(gain)[i % k8];
+  wvec8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(static_cast<float>(x[e]) * static_cast<float>(g[e]));
+  reinterpret_cast<wvec8*>(out)[i] = o;
+}
+
+// out[2j] = gate[j], out[2j+1] = up[j]: a lane of the projection kernel then holds both pre-activations of feature j
+__global__ __launch_bounds__(256) void interleave_rows_kernel(const __bf16* __restrict__ gate, const __bf16* __restrict__ up,
+                                                              __bf16* __restrict__ out, size_t n8, int k8) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;   // index into out, in 16-byte units
+  if (i >= n8) return;
+  const size_t row = i / k8, c = i - row * k8;
+  const __bf16* src = (row & 1) ? up : gate;
+  reinterpret_cast<wvec8*>(out)[i] = reinterpret_cast<const wvec8*>(src)[(row >> 1) * k8 + c];
+}
+
 }  // namespace
+
+int launch_fold_rmsnorm_gain(const void* w, const void* gain, void* out, int N, int K, hipStream_t stream) {
+  const size_t n8 = static_cast<size_t>(N) * K / 8;
+  hipLaunchKernelGGL(fold_gain_kernel, dim3(static_cast<unsigned>((n8 + 255) / 256)), dim3(256), 0, stream,
+                     static_cast<const __bf16*>(w), static_cast<const __bf16*>(gain), static_cast<__bf16*>(out), n8, K / 8);
+  return check_launch();
+}
+
+int launch_interleave_gate_up(const void* w_gate, const void* w_up, void* out, int F, int K, hipStream_t stream) {
+  const size_t n8 = static_cast<size_t>(2) * F * K / 8;
+  hipLaunchKernelGGL(interleave_rows_kernel, dim3(static_cast<unsigned>((n8 + 255) / 256)), dim3(256), 0, stream,
+                     static_cast<const __bf16*>(w_gate), static_cast<const __bf16*>(w_up), static_cast<__bf16*>(out), n8, K / 8);
+  return check_launch();
+}
 
 int launch_rope_block(const ouro_rope_desc& d, hipStream_t stream) {
   const float log2_base = log2f(d.base > 0.f ? d.base : 10000.0f);

@@ -23,7 +23,6 @@
 //     slower: store acknowledgement, ticket and reload are three device-scope round trips
 //     that every workgroup pays at the very end, when nothing is left to overlap them with.
 #include <math.h>
-#include <stdlib.h>
 
 #include <algorithm>
 
@@ -417,13 +416,13 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const u32x4* __restrict__ s
 template <int MT, int NT, bool kStore, bool kTiled>
 int launch_instance(const LmArgs& a, const LmPlan& plan, hipStream_t stream) {
   using C = LmCfg<MT, NT>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_bf16_kernel<MT, NT, kStore, kTiled>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-    if (e != hipSuccess) return hip_failed(e);
-    attr_set = true;
-  }
+  static DeviceOnce once;                                   // one per kernel instance
+  const int ready = device_once(once, [] {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_bf16_kernel<MT, NT, kStore, kTiled>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+    return e == hipSuccess ? static_cast<int>(OURO_OK) : hip_failed(e);
+  });
+  if (ready != OURO_OK) return ready;
   const unsigned grid = static_cast<unsigned>((plan.nslab + 7) / 8) * 8u * plan.nrtile * (kStore ? a.ksplit : 1);
   hipLaunchKernelGGL((lmhead_bf16_kernel<MT, NT, kStore, kTiled>), dim3(grid), dim3(256), C::kLdsBytes, stream, a);
   return check_launch();
@@ -461,18 +460,18 @@ int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_
 }
 
 // Split of the k range of a projection over workgroups: enough of them to occupy the chip, at least 8 k-tiles each.
-int linear_ksplit(int R, int K, int N) {
+// (`forced` > 0: a count given by the caller for tests and tuning runs.)
+int linear_ksplit(int R, int K, int N, int forced) {
   const int nrtile = R <= 64 ? 1 : (R + 127) / 128;
   const long wgs = static_cast<long>((N + 127) / 128) * nrtile;
   long ks = std::max<long>(1, 256 / std::max<long>(wgs, 1));
   ks = std::min<long>(ks, std::max(1, K / 64 / 8));
-  const char* env = std::getenv("OURO_LINEAR_KSPLIT");
-  if (env && *env) ks = std::max(1L, std::min<long>(std::atol(env), K / 64));
+  if (forced > 0) ks = std::max(1L, std::min<long>(forced, K / 64));
   return static_cast<int>(ks);
 }
 
-size_t linear_workspace_bytes(int R, int K, int N) {
-  const int ks = linear_ksplit(R, K, N);
+size_t linear_workspace_bytes(int R, int K, int N, int ksplit_override) {
+  const int ks = linear_ksplit(R, K, N, ksplit_override);
   return ks > 1 ? static_cast<size_t>(ks) * R * (static_cast<size_t>(N) + 1) * sizeof(float) : 0;   // partial sums + row shares
 }
 
@@ -486,7 +485,7 @@ int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream) {
   a.tiled = d.w_layout == OURO_W_TILED;
   a.out = static_cast<__bf16*>(d.out);
   a.residual = static_cast<const __bf16*>(d.residual);
-  a.ksplit = linear_ksplit(d.R, d.K, d.N);
+  a.ksplit = linear_ksplit(d.R, d.K, d.N, d.ksplit_override);
   a.part_f32 = static_cast<float*>(d.workspace);
   a.swiglu = d.epilogue == OURO_EPI_SWIGLU_PAIRS;
   a.rms_eps = d.rms_eps > 0.f ? d.rms_eps : 0.f;

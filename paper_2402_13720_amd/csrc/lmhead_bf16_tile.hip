@@ -230,13 +230,13 @@ int launch_lmhead_bf16_tile(const ouro_lmhead_desc& d, const LmPlan& plan, hipSt
   a.nslab = plan.nslab;
   a.nrtile = plan.nrtile;
   a.tiled = d.w_layout == OURO_W_TILED;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_bf16_tile_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return hip_failed(e);
-    attr_set = true;
-  }
+  static DeviceOnce once;
+  const int ready = device_once(once, [] {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lmhead_bf16_tile_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    return e == hipSuccess ? static_cast<int>(OURO_OK) : hip_failed(e);
+  });
+  if (ready != OURO_OK) return ready;
   const unsigned grid = static_cast<unsigned>((plan.nslab + 7) / 8) * 8u * plan.nrtile;
   hipLaunchKernelGGL(lmhead_bf16_tile_kernel, dim3(grid), dim3(kThreads), kLdsBytes, stream, a);
   return check_launch();

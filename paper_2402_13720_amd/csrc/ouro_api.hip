@@ -15,11 +15,6 @@ int hip_failed(hipError_t e) {
   return OURO_E_HIP;
 }
 
-static long env_long(const char* name, long dflt) {
-  const char* v = std::getenv(name);
-  return v && *v ? std::atol(v) : dflt;
-}
-
 // Launch plan of the bf16 attention.  A workgroup streams `chunk` keys of one (sequence,
 // KV head) for its query rows and, when the sequence spans several chunks, leaves one fp32
 // partial.  Small chunks fill the 256 compute units; large chunks keep the partial traffic
@@ -30,15 +25,15 @@ static long env_long(const char* name, long dflt) {
 // best where per-workgroup prologue/epilogue latency dominates).  More rows (long drafts, grouped-query
 // heads): the workgroup keeps 4 row blocks and its waves share the staged tiles; one workgroup per compute
 // unit, and the chunk count is the largest that still lets every workgroup be resident at once (no second
-// round of workgroups).  OURO_ATTN_CHUNK (keys) and OURO_ATTN_RW (1, 2, 4) override the heuristic for
-// tuning runs.
+// round of workgroups).  The descriptor's plan_override (row blocks per workgroup, keys per chunk) replaces the
+// heuristic in tests and tuning runs.
 AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
   AttnPlan p{};
   const int G = d.Hq / d.Hkv;
   const int M = d.T * G;
   p.rw = M <= 64 ? 1 : 4;                            // (2 is built as well; measured no faster than 1 at 64 rows)
-  const long rw_env = env_long("OURO_ATTN_RW", 0);
-  if (rw_env == 1 || rw_env == 2 || rw_env == 4) p.rw = static_cast<int>(rw_env);
+  const int rw_forced = d.plan_override & 0xff;
+  if (rw_forced == 1 || rw_forced == 2 || rw_forced == 4) p.rw = rw_forced;
   p.rows_wg = 32 * p.rw;
   p.nrb = (M + p.rows_wg - 1) / p.rows_wg;
   const long maxn = static_cast<long>(d.max_seqlen) + d.T;
@@ -55,8 +50,8 @@ AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
     const long want = std::max<long>(1, std::min(resident / groups, stages));
     tiles_per_chunk = (stages + want - 1) / want * 4;
   }
-  const long chunk_env = env_long("OURO_ATTN_CHUNK", 0);
-  if (chunk_env >= 128) tiles_per_chunk = chunk_env / 128 * 4;
+  const long chunk_forced = static_cast<long>(static_cast<unsigned>(d.plan_override) >> 8);   // in units of 128 keys
+  if (chunk_forced >= 1) tiles_per_chunk = chunk_forced * 4;
   p.chunk = static_cast<int>(tiles_per_chunk * 32);
   p.nch = static_cast<int>((maxn + p.chunk - 1) / p.chunk);
   if (p.nch > 1) {
@@ -102,6 +97,7 @@ static int validate_attn(const ouro_attn_desc* d, bool need_pointers) {
   if (static_cast<long>(d->T) * (d->Hq / d->Hkv) > 32768) return OURO_E_BAD_SHAPE;
   if (d->kv_layout != OURO_KV_ROW_MAJOR && d->kv_layout != OURO_KV_HEAD_MAJOR) return OURO_E_BAD_SHAPE;
   if (d->kv_layout == OURO_KV_HEAD_MAJOR && (d->cache_rows < 0 || d->cache_rows > (1LL << 40))) return OURO_E_BAD_SHAPE;
+  if (d->plan_override < 0) return OURO_E_BAD_SHAPE;
   if (!need_pointers || d->B == 0) return OURO_OK;
   if (!d->q || !d->cu_seqlens || !d->k_blk || !d->v_blk || !d->meta || !d->out) return OURO_E_NULLPTR;
   if (d->max_seqlen > 0 && (!d->k_cache || !d->v_cache)) return OURO_E_NULLPTR;
@@ -264,12 +260,13 @@ static int validate_linear(const ouro_linear_desc* d) {
   if (d->w_layout != OURO_W_ROW_MAJOR && d->w_layout != OURO_W_TILED) return OURO_E_BAD_SHAPE;
   if (d->epilogue != OURO_EPI_NONE && d->epilogue != OURO_EPI_SWIGLU_PAIRS) return OURO_E_BAD_SHAPE;
   if (d->epilogue == OURO_EPI_SWIGLU_PAIRS && (d->N % 16 != 0 || d->residual)) return OURO_E_BAD_SHAPE;
+  if (d->ksplit_override < 0) return OURO_E_BAD_SHAPE;
   return OURO_OK;
 }
 
 size_t ouro_linear_workspace(const ouro_linear_desc* d) {
   if (validate_linear(d) != OURO_OK || d->R == 0) return 0;
-  return linear_workspace_bytes(d->R, d->K, d->N);
+  return linear_workspace_bytes(d->R, d->K, d->N, d->ksplit_override);
 }
 
 int ouro_linear(const ouro_linear_desc* d, void* hip_stream) {
@@ -279,12 +276,31 @@ int ouro_linear(const ouro_linear_desc* d, void* hip_stream) {
   if (!d->x || !d->w || !d->out) return OURO_E_NULLPTR;
   if (!aligned16(d->x) || !aligned16(d->w) || !aligned16(d->out) || !aligned16(d->residual) || !aligned16(d->workspace))
     return OURO_E_MISALIGNED;
-  const size_t need = linear_workspace_bytes(d->R, d->K, d->N);
+  const size_t need = linear_workspace_bytes(d->R, d->K, d->N, d->ksplit_override);
   if (need > 0) {
     if (!d->workspace) return OURO_E_NULLPTR;
     if (d->workspace_bytes < need) return OURO_E_WORKSPACE_TOO_SMALL;
   }
   return launch_linear_bf16(*d, static_cast<hipStream_t>(hip_stream));
+}
+
+static int validate_weight_relayout(const void* a, const void* b, const void* out, int32_t rows, int32_t K) {
+  if (!a || !b || !out) return OURO_E_NULLPTR;
+  if (rows < 1 || K < 8 || K % 8 != 0) return OURO_E_BAD_SHAPE;
+  if (!aligned16(a) || !aligned16(b) || !aligned16(out)) return OURO_E_MISALIGNED;
+  return OURO_OK;
+}
+
+int ouro_fold_rmsnorm_gain(const void* w, const void* gain, void* out, int32_t N, int32_t K, void* hip_stream) {
+  const int st = validate_weight_relayout(w, gain, out, N, K);
+  if (st != OURO_OK) return st;
+  return launch_fold_rmsnorm_gain(w, gain, out, N, K, static_cast<hipStream_t>(hip_stream));
+}
+
+int ouro_interleave_gate_up(const void* w_gate, const void* w_up, void* out, int32_t F, int32_t K, void* hip_stream) {
+  const int st = validate_weight_relayout(w_gate, w_up, out, F, K);
+  if (st != OURO_OK) return st;
+  return launch_interleave_gate_up(w_gate, w_up, out, F, K, static_cast<hipStream_t>(hip_stream));
 }
 
 int ouro_silu_mul(const ouro_silu_mul_desc* d, void* hip_stream) {

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "ouro.h"
 
 namespace ouro {
@@ -14,6 +16,24 @@ int hip_failed(hipError_t e);
 inline int check_launch() {
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? OURO_OK : hip_failed(e);
+}
+
+// One-time set-up per device, thread-safe: a kernel's dynamic shared-memory limit is an attribute of the function on
+// one device, so it is raised on the first launch on each device and never again.  `init` returns an OURO status;
+// a failed set-up is reported by every later call on that device as well.
+constexpr int kMaxDevices = 64;
+struct DeviceOnce {
+  std::once_flag flag[kMaxDevices];
+  int status[kMaxDevices];
+};
+template <typename F>
+int device_once(DeviceOnce& s, F&& init) {
+  int dev = 0;
+  const hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_failed(e);
+  if (dev < 0 || dev >= kMaxDevices) return init();        // beyond the table: set the attributes on every call
+  std::call_once(s.flag[dev], [&] { s.status[dev] = init(); });
+  return s.status[dev];
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -63,6 +83,8 @@ int launch_rope_block(const ouro_rope_desc& d, hipStream_t stream);
 int launch_rmsnorm(const ouro_rmsnorm_desc& d, hipStream_t stream);
 int launch_silu_mul(const ouro_silu_mul_desc& d, hipStream_t stream);
 int launch_linear_bf16(const ouro_linear_desc& d, hipStream_t stream);
-size_t linear_workspace_bytes(int R, int K, int N);
+size_t linear_workspace_bytes(int R, int K, int N, int ksplit_override);
+int launch_fold_rmsnorm_gain(const void* w, const void* gain, void* out, int N, int K, hipStream_t stream);
+int launch_interleave_gate_up(const void* w_gate, const void* w_up, void* out, int F, int K, hipStream_t stream);
 
 }  // namespace ouro

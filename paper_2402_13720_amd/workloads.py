@@ -98,7 +98,9 @@ def make_block_meta(cfg: VerifyConfig, rng: np.random.Generator,
     """Per-token (phrase_id, branch_off), each int16 [B, T].
 
     branch = "uniform": b_j drawn uniformly from {0..gamma-1} per phrase;
-    branch = "last":    b_j = gamma-1 for every phrase (the paper's own layout).
+    branch = "last":    b_j = gamma-1 for every phrase (the paper's own layout);
+    branch = "any":     b_j drawn uniformly from {-1, 0..gamma-1}: -1 is a phrase that hangs off the last
+                        cached token and sees no main token (parity sweeps only).
     """
     B, T, g, K, bp = cfg.B, cfg.T, cfg.gamma, cfg.K, cfg.beta_p
     pid = np.zeros((B, T), dtype=np.int16)
@@ -111,6 +113,8 @@ def make_block_meta(cfg: VerifyConfig, rng: np.random.Generator,
                 bj = int(rng.integers(0, g))
             elif branch == "last":
                 bj = g - 1
+            elif branch == "any":
+                bj = int(rng.integers(-1, g))
             else:
                 raise ValueError(branch)
             pid[b, lo:lo + bp] = j

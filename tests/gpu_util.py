@@ -1,4 +1,6 @@
 """Helpers shared by the GPU parity tests: upload seeded host inputs, call the C ABI through the binding."""
+import functools
+
 import numpy as np
 import torch
 
@@ -27,15 +29,28 @@ def upload_attention(cfg, inp, head_major=False):
     return t
 
 
-def run_attention(cfg, inp, want_lse=True, max_seqlen=None, head_major=False):
+def run_attention(cfg, inp, want_lse=True, max_seqlen=None, head_major=False, rw=0, chunk=0):
+    """rw, chunk: force the bf16 kernel variant (row blocks per workgroup) and the keys per workgroup (0: heuristic)."""
     from paper_2402_13720_amd import binding as ob
     t = upload_attention(cfg, inp, head_major)
     lse = torch.full((cfg.B, cfg.Hq, cfg.T), float("nan"), dtype=torch.float32, device=DEV) if want_lse else None
     out = ob.ouro_verify_attn(t["q"], t["k_cache"], t["v_cache"], t["cu_seqlens"], t["k_blk"], t["v_blk"], t["meta"],
                               max_seqlen=t["max_seqlen"] if max_seqlen is None else max_seqlen, lse=lse,
-                              head_major=head_major)
+                              head_major=head_major, plan=ob.plan_override(rw, chunk))
     torch.cuda.synchronize()
     return out, lse, t
+
+
+@functools.lru_cache(maxsize=2)
+def full_size_attention_case(cfg_id):
+    """(inputs, oracle result on every head) of a workload at full size; kept so that tests of the same workload in
+    several layouts pay for the inputs and the oracle once."""
+    from oracle import verify_oracle as O
+    cfg = W.CONFIGS[cfg_id]
+    inp = W.make_attention_inputs(cfg, W.seed_for(cfg_id))
+    ref = O.verify_attention(inp["q"], inp["k_cache"], inp["v_cache"], inp["cu_seqlens"], inp["k_blk"], inp["v_blk"],
+                             inp["pid"], inp["boff"])
+    return inp, ref
 
 
 def to_np64(x):

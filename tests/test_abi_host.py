@@ -22,14 +22,15 @@ def test_every_declared_symbol_is_exported():
     names = _declared_functions()
     assert {"ouro_verify_attn", "ouro_lmhead_argmax", "ouro_accept", "ouro_verify_attn_workspace",
             "ouro_lmhead_argmax_workspace", "ouro_lmhead_packed_w_bytes", "ouro_lmhead_pack_w", "ouro_kv_commit",
-            "ouro_rope_block", "ouro_rmsnorm", "ouro_linear", "ouro_silu_mul",
+            "ouro_rope_block", "ouro_rmsnorm", "ouro_linear", "ouro_silu_mul", "ouro_fold_rmsnorm_gain",
+            "ouro_interleave_gate_up",
             "ouro_validate_meta_host", "ouro_status_string", "ouro_last_hip_error", "ouro_version"} <= set(names)
     for n in names:
         assert hasattr(ob.lib, n), n
 
 
 def test_version_and_status_strings():
-    assert ob.lib.ouro_version() == 200
+    assert ob.lib.ouro_version() == 210
     assert ob.lib.ouro_status_string(0) == b"ok"
     for code in range(-8, 0):
         assert ob.lib.ouro_status_string(code) not in (b"ok", b"unknown status")
@@ -63,6 +64,7 @@ def test_attn_descriptor_validation_runs_before_any_hip_call():
     assert f(C.byref(_attn_desc(Hq=32, Hkv=5)), None) == -2
     assert f(C.byref(_attn_desc(D=64)), None) == -2                      # bf16 needs D = 128
     assert f(C.byref(_attn_desc(max_seqlen=-1)), None) == -2
+    assert f(C.byref(_attn_desc(plan_override=-1)), None) == -2
     assert f(C.byref(_attn_desc()), None) == -1                          # data pointers are NULL
     assert f(C.byref(_attn_desc(B=0)), None) == 0                        # nothing to do
     ok = dict(q=256, k_cache=256, v_cache=256, cu_seqlens=256, k_blk=256, v_blk=256, meta=256, out=256)
@@ -81,6 +83,37 @@ def test_attn_workspace_query():
     assert ws(C.byref(_attn_desc(max_seqlen=0, T=16))) == 0              # single chunk: no partials
     assert ws(C.byref(_attn_desc(B=1, max_seqlen=65536, T=32))) > 0
     assert ws(C.byref(_attn_desc(B=16, max_seqlen=8192, T=32))) == 0    # enough sequences: one chunk each
+    # a forced launch shape changes the plan, and with it the workspace: 17 chunks of 128 keys, 4 row blocks per workgroup
+    forced = ws(C.byref(_attn_desc(plan_override=ob.plan_override(4, 128))))
+    assert forced == 32 * 17 * 128 * (2 + 128) * 4 + (256 - 32 * 17 * 128 * 2 * 4 % 256) % 256
+    assert ws(C.byref(_attn_desc(plan_override=ob.plan_override(1, 4096)))) == 0   # one chunk covers the sequence
+
+
+def test_no_call_reads_the_process_environment(monkeypatch):
+    """Tuning goes through descriptor fields; environment variables of the earlier interface are ignored."""
+    ws = ob.lib.ouro_verify_attn_workspace
+    before = ws(C.byref(_attn_desc()))
+    monkeypatch.setenv("OURO_ATTN_CHUNK", "128")
+    monkeypatch.setenv("OURO_ATTN_RW", "4")
+    monkeypatch.setenv("OURO_LINEAR_KSPLIT", "7")
+    assert ws(C.byref(_attn_desc())) == before
+    d = ob.ouro_linear_desc()
+    d.struct_size = C.sizeof(ob.ouro_linear_desc)
+    d.dtype, d.R, d.K, d.N = ob.OURO_BF16, 64, 4096, 4096
+    auto = ob.lib.ouro_linear_workspace(C.byref(d))
+    assert auto == 8 * 64 * (4096 + 1) * 4                                # the heuristic: 32 slabs -> 8 shares of the k range
+    d.ksplit_override = 3
+    assert ob.lib.ouro_linear_workspace(C.byref(d)) == 3 * 64 * (4096 + 1) * 4
+    d.ksplit_override = -1
+    assert ob.lib.ouro_linear_workspace(C.byref(d)) == 0 and ob.lib.ouro_linear(C.byref(d), None) == -2
+
+
+def test_weight_relayout_validation():
+    for f in (ob.lib.ouro_fold_rmsnorm_gain, ob.lib.ouro_interleave_gate_up):
+        assert f(None, 256, 512, 8, 64, None) == -1
+        assert f(256, 512, 1024, 0, 64, None) == -2
+        assert f(256, 512, 1024, 8, 60, None) == -2                       # K must be a multiple of 8
+        assert f(256, 520, 1024, 8, 64, None) == -5
 
 
 def _lm_desc(**kw):
@@ -191,7 +224,7 @@ def test_layer_descriptor_validation():
     d.epilogue = 7
     assert ob.lib.ouro_linear(C.byref(d), None) == -2                     # unknown epilogue
     d.epilogue = ob.OURO_EPI_NONE
-    assert C.sizeof(ob.ouro_linear_desc) == 32 + 5 * 8 + 8
+    assert C.sizeof(ob.ouro_linear_desc) == 40 + 5 * 8 + 8
     assert ob.lib.ouro_linear(C.byref(d), None) == -1                     # pointers missing
     d.R = 0
     assert ob.lib.ouro_linear(C.byref(d), None) == 0

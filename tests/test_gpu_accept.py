@@ -80,7 +80,7 @@ def test_handworked_pool_byproducts():
 def test_config_shapes_random_drafts(cfg_id, p_correct):
     cfg = W.scaled(W.CONFIGS[cfg_id], B=max(W.CONFIGS[cfg_id].B, 7))
     rng = np.random.default_rng(cfg_id * 10 + int(p_correct * 10))
-    for branch in ("uniform", "last"):
+    for branch in ("uniform", "last", "any"):
         pid, boff = W.make_block_meta(cfg, rng, branch)
         argmax = rng.integers(0, cfg.V, size=(cfg.B, cfg.T)).astype(np.int32)
         root = rng.integers(0, cfg.V, size=cfg.B).astype(np.int32)

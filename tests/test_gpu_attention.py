@@ -15,8 +15,8 @@ def _oracle(inp, heads=None):
                               inp["pid"], inp["boff"], heads=heads)
 
 
-def _check(cfg, inp, heads=None, lse_tol=None, head_major=False):
-    out, lse, _ = run_attention(cfg, inp, head_major=head_major)
+def _check(cfg, inp, heads=None, lse_tol=None, head_major=False, rw=0, chunk=0):
+    out, lse, _ = run_attention(cfg, inp, head_major=head_major, rw=rw, chunk=chunk)
     ref = _oracle(inp, heads)
     got = to_np64(out)
     got_lse = to_np64(lse)
@@ -74,15 +74,12 @@ def test_bf16_small_shapes(kw, branch):
     (dict(B=4, Hq=2, Hkv=1, L=(30, 2000), gamma=8, K=4, beta_p=6), 512),      # uneven lengths, empty chunk slots
     (dict(B=1, Hq=1, Hkv=1, L=95, gamma=1, K=0, beta_p=0), 0),                # a single row
 ])
-def test_bf16_every_kernel_variant(monkeypatch, kw, chunk, rw, head_major):
+def test_bf16_every_kernel_variant(kw, chunk, rw, head_major):
     """The launch heuristic picks the row blocks per workgroup (1: waves split the keys; 2, 4: waves split the
     rows and share staged tiles) and the chunk length; force each combination so that all three kernels see
     several stages, several chunks and a ragged tail, with the cache in either layout."""
-    monkeypatch.setenv("OURO_ATTN_RW", str(rw))
-    if chunk:
-        monkeypatch.setenv("OURO_ATTN_CHUNK", str(chunk))
     cfg = W.scaled(W.CONFIGS[2], **kw)
-    _check(cfg, W.make_attention_inputs(cfg, 4321), head_major=head_major)
+    _check(cfg, W.make_attention_inputs(cfg, 4321), head_major=head_major, rw=rw, chunk=chunk)
 
 
 def test_fp32_head_major_cache():
@@ -122,26 +119,43 @@ def test_bf16_mask_probe_through_the_kernel():
     assert np.allclose(nvis, want.sum(1), atol=1e-3)
 
 
-@pytest.mark.parametrize("cfg_id", [2, 3, 4])
-def test_full_size_configs(cfg_id):
+@pytest.mark.parametrize("head_major", [False, True])
+@pytest.mark.parametrize("cfg_id", [2, 3, 4, 5])
+def test_full_size_configs_every_head_and_row(cfg_id, head_major):
+    """Every output element of the workload at its full size against the oracle (no sampling), in both cache layouts,
+    in the launch configuration the benchmark times; plus run-to-run determinism (fixed merge order, no float atomics)."""
+    from gpu_util import full_size_attention_case
     cfg = W.CONFIGS[cfg_id]
-    inp = W.make_attention_inputs(cfg, W.seed_for(cfg_id))
-    heads = None if cfg_id == 2 else [(0, h) for h in range(0, cfg.Hq, 5)]
-    out = _check(cfg, inp, heads)
-    # run-to-run determinism (fixed merge order, no float atomics)
-    out2, _, _ = run_attention(cfg, inp)
+    inp, ref = full_size_attention_case(cfg_id)
+    out, lse, _ = run_attention(cfg, inp, head_major=head_major)
+    got, got_lse = to_np64(out), to_np64(lse)
+    assert np.isfinite(got).all()
+    err, lerr = np.abs(got - ref["out"]).max(), np.abs(got_lse - ref["lse"]).max()
+    print("%s: %d x %d x %d rows, max-abs err %.3g, lse err %.3g" % (cfg.name, cfg.B, cfg.T, cfg.Hq, err, lerr), flush=True)
+    assert err <= attn_tol(cfg) and lerr <= 1e-2
+    out2, _, _ = run_attention(cfg, inp, head_major=head_major)
     assert torch.equal(out, out2)
 
 
-@pytest.mark.parametrize("head_major", [False, True])
-def test_full_size_config5_sampled_heads(head_major):
-    cfg = W.CONFIGS[5]
-    inp = W.make_attention_inputs(cfg, W.seed_for(5))
+@pytest.mark.parametrize("cfg_id, kw, rw", [
+    (2, dict(B=3, Hq=4, Hkv=2, L=(300, 1500)), 1),               # key-split kernel; the hint cuts chunk slots away
+    (2, dict(B=2, Hq=16, Hkv=2, L=(300, 1500)), 4),              # row-split kernel
+    (1, dict(B=2, L=(100, 300)), 0),                             # fp32 kernel
+])
+def test_length_beyond_the_hint_is_cut_to_the_hint(cfg_id, kw, rw):
+    """max_seqlen sizes the grid, the chunk slots and the workspace.  A device-side length above it (a stale hint: the
+    commit advances lengths on the device) must not reach past any of them: such a sequence is attended over its first
+    max_seqlen cached tokens, which is what the oracle computes when told that length."""
+    cfg = W.scaled(W.CONFIGS[cfg_id], **kw)
+    inp = W.make_attention_inputs(cfg, 31 + cfg_id)
     lens = np.diff(inp["cu_seqlens"])
-    order = np.argsort(lens)
-    seqs = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]       # shortest, median, longest sequence
-    heads = [(b, h) for b in seqs for h in (0, 13, 31)]
-    _check(cfg, inp, heads, head_major=head_major)
+    hint = int(lens.min()) + 7                                                 # below the longest sequence
+    assert lens.max() > hint
+    out, lse, _ = run_attention(cfg, inp, max_seqlen=hint, rw=rw)
+    ref = O.verify_attention(inp["q"], inp["k_cache"], inp["v_cache"], inp["cu_seqlens"], inp["k_blk"], inp["v_blk"],
+                             inp["pid"], inp["boff"], seq_len=np.minimum(lens, hint))
+    assert np.abs(to_np64(out) - ref["out"]).max() <= attn_tol(cfg)
+    assert np.abs(to_np64(lse) - ref["lse"]).max() <= (1e-2 if cfg.dtype == "bf16" else 1e-5)
 
 
 def test_workspace_is_reusable_across_shapes_and_calls():
@@ -190,9 +204,10 @@ def test_softmax_scale_given_by_the_caller(cfg_id, kw, scale):
 
 
 @pytest.mark.parametrize("case", range(24))
-def test_bf16_seeded_random_shapes(monkeypatch, case):
+def test_bf16_seeded_random_shapes(case):
     """A seeded sweep over shapes nobody picked by hand: batch, head grouping, draft layout, cache lengths from empty to
-    a few tiles, the kernel variant, the chunk length and the cache layout all drawn per case."""
+    a few tiles, the kernel variant, the chunk length, the cache layout and the branch rule (including phrases that hang
+    off the cached prefix, branch offset -1) all drawn per case."""
     rng = np.random.default_rng(7000 + case)
     Hkv = int(rng.choice([1, 2, 3]))
     G = int(rng.choice([1, 1, 2, 4]))
@@ -202,9 +217,7 @@ def test_bf16_seeded_random_shapes(monkeypatch, case):
     lo = int(rng.choice([0, 1, 31, 64, 200]))
     hi = lo + int(rng.choice([0, 1, 33, 250, 700]))
     cfg = W.scaled(W.CONFIGS[2], B=int(rng.integers(1, 5)), Hq=Hkv * G, Hkv=Hkv, L=(lo, hi), gamma=gamma, K=K, beta_p=bp)
-    monkeypatch.setenv("OURO_ATTN_RW", str(int(rng.choice([1, 2, 4]))))
+    rw = int(rng.choice([1, 2, 4]))
     chunk = int(rng.choice([0, 128, 256, 384]))
-    if chunk:
-        monkeypatch.setenv("OURO_ATTN_CHUNK", str(chunk))
-    inp = W.make_attention_inputs(cfg, 8000 + case, branch=str(rng.choice(["uniform", "last"])))
-    _check(cfg, inp, head_major=bool(rng.integers(0, 2)))
+    inp = W.make_attention_inputs(cfg, 8000 + case, branch=str(rng.choice(["uniform", "last", "any"])))
+    _check(cfg, inp, head_major=bool(rng.integers(0, 2)), rw=rw, chunk=chunk)

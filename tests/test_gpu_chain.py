@@ -1,56 +1,18 @@
-"""GPU parity of the chained verification step: attention -> LM head + arg-max -> acceptance, each stage
-fed by the previous GPU stage, each checked against the oracle on identical inputs; plus the end-to-end
-comparison with the oracle's own chain, with the rows that differ reported together with their margins."""
-import numpy as np
+"""GPU parity of the chained verification step: attention -> LM head + arg-max -> acceptance at the full size of
+every workload, each stage checked against the oracle on identical inputs, and the whole chain against the oracle's
+own chain with every differing row accounted for (see chain_util)."""
 import pytest
-import torch
 
-from oracle import verify_oracle as O
-from paper_2402_13720_amd import binding as ob, workloads as W
-from gpu_util import DEV, attn_tol, run_attention, to_np64, torch_dtype
+from paper_2402_13720_amd import workloads as W
+from chain_util import format_report, run_chain
 
 pytestmark = pytest.mark.gpu
 
 
-def _chain(cfg, seed):
-    inp = W.make_attention_inputs(cfg, seed)
-    w = W.make_lmhead_weight(cfg, seed)
-    draws = W.make_token_draws(cfg, seed)
-    # --- stage 1
-    out, _, t = run_attention(cfg, inp, want_lse=False)
-    ref_att = O.verify_attention(inp["q"], inp["k_cache"], inp["v_cache"], inp["cu_seqlens"], inp["k_blk"],
-                                 inp["v_blk"], inp["pid"], inp["boff"])
-    err = np.abs(to_np64(out) - ref_att["out"]).max()
-    assert err <= attn_tol(cfg), err
-    # --- stage 2 on the GPU's own hidden states
-    hidden = out.reshape(cfg.R, cfg.hidden)
-    w_d = torch.from_numpy(w).to(DEV).to(torch_dtype(cfg))
-    arg = ob.ouro_lmhead_argmax(hidden, w_d)
-    torch.cuda.synchronize()
-    arg_h = arg.cpu().numpy()
-    ref_lm = O.lmhead_argmax(hidden.float().cpu().numpy(), w)
-    bad = [(r, float(ref_lm["margin"][r])) for r in range(cfg.R) if arg_h[r] != ref_lm["argmax"][r]]
-    assert all(m < 1e-3 for _, m in bad), bad
-    # --- draft ids: half of the positions carry the token they will be compared with
-    amax = arg_h.reshape(cfg.B, cfg.T)
-    exp = np.stack([O.expected_tokens(amax[b], inp["pid"][b], inp["boff"][b], int(draws["root_pred"][b]))
-                    for b in range(cfg.B)])
-    tok = W.plant_tokens(draws["tok"], draws["chosen"], exp)
-    # --- stage 3
-    got = ob.ouro_accept(torch.from_numpy(tok).to(DEV), arg.view(cfg.B, cfg.T), t["meta"],
-                         torch.from_numpy(draws["root_pred"]).to(DEV), cfg.gamma, cfg.K, cfg.beta_p)
-    torch.cuda.synchronize()
-    ref_acc = O.accept(tok, amax, inp["pid"], inp["boff"], draws["root_pred"], cfg.gamma, cfg.K, cfg.beta_p)
-    for k in ("n_accept", "path", "bonus", "accept_idx", "main_A", "phrase_A", "n_match"):
-        assert np.array_equal(got[k].cpu().numpy(), ref_acc[k]), k
-    # --- the oracle's own chain (its hidden = fp64 attention rounded the way the stored dtype rounds)
-    rnd = (lambda h: W.round_to_bf16(h.astype(np.float32))) if cfg.dtype == "bf16" else (lambda h: h.astype(np.float32))
-    ref_chain_lm = O.lmhead_argmax(rnd(ref_att["out"].reshape(cfg.R, cfg.hidden)), w)
-    diff = [(r, float(ref_chain_lm["margin"][r])) for r in range(cfg.R) if arg_h[r] != ref_chain_lm["argmax"][r]]
-    print("%s chain: attn err %.3g; stage-wise argmax exempt rows %s; rows differing from the oracle chain "
-          "(margin): %s; n_accept %s" % (cfg.name, err, bad, diff, ref_acc["n_accept"].tolist()), flush=True)
-    # a one-ulp bf16 difference in a few hidden values moves a logit by far less than this
-    assert all(m < 5e-2 for _, m in diff), diff
+def _chain(cfg, seed, **kw):
+    rep = run_chain(cfg, seed, **kw)
+    print(format_report(rep), flush=True)
+    return rep
 
 
 def test_config1_chain():
@@ -58,10 +20,16 @@ def test_config1_chain():
         _chain(W.CONFIGS[1], W.seed_for(1, trial))
 
 
-def test_config2_chain():
-    _chain(W.CONFIGS[2], W.seed_for(2))
+@pytest.mark.parametrize("cfg_id", [2, 3, 4, 5])
+def test_full_size_chain(cfg_id):
+    _chain(W.CONFIGS[cfg_id], W.seed_for(cfg_id))
+
+
+def test_config2_chain_paper_layout_row_major_operands():
+    """Every phrase hanging off the last main token (the paper's own layout), caches token-major, W row-major."""
+    _chain(W.CONFIGS[2], W.seed_for(2, 1), branch="last", tiled=False, head_major=False)
 
 
 def test_small_batched_varlen_chain():
     cfg = W.scaled(W.CONFIGS[5], B=4, Hq=4, Hkv=4, L=(100, 900), V=3000)
-    _chain(cfg, 99)
+    _chain(cfg, 99, branch="any")

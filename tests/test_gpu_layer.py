@@ -131,20 +131,18 @@ def test_linear(R, K, N, tiled, with_res):
     (70, 320, 136, True, 3),        # k range split: the activation is applied by the reduction kernel
     (1, 64, 8, False, 0),
 ])
-def test_linear_swiglu_epilogue(monkeypatch, R, K, F, tiled, ksplit):
+def test_linear_swiglu_epilogue(R, K, F, tiled, ksplit):
     """Gate and up projection with the gate applied in the epilogue: interleaved (gate_j, up_j) weight rows in, [R, F] out,
     against the oracle's projection followed by its SiLU gate (no bf16 rounding of the pre-activations in between)."""
-    if ksplit:
-        monkeypatch.setenv("OURO_LINEAR_KSPLIT", str(ksplit))
     rng = np.random.default_rng(R + K + F)
     x = _bf(rng.standard_normal((R, K)))
     wg, wu = _bf(rng.standard_normal((F, K)) * 0.08), _bf(rng.standard_normal((F, K)) * 0.08)
     ref = LO.silu_mul(np.concatenate([LO.linear(x, wg), LO.linear(x, wu)], axis=1))
-    w_d = ob.interleave_gate_up(_up(wg), _up(wu))
+    w_d = ob.ouro_interleave_gate_up(_up(wg), _up(wu))
     assert torch.equal(w_d[0::2], _up(wg)) and torch.equal(w_d[1::2], _up(wu))
     if tiled:
         w_d = ob.ouro_lmhead_pack_w(w_d)
-    out = ob.ouro_linear(_up(x), w_d, swiglu=True)
+    out = ob.ouro_linear(_up(x), w_d, swiglu=True, ksplit=ksplit)
     torch.cuda.synchronize()
     assert tuple(out.shape) == (R, F)
     # fp32 product and gate, one bf16 rounding; the gate's slope is at most 1.1, so the product's error carries over
@@ -160,20 +158,21 @@ def test_linear_swiglu_epilogue(monkeypatch, R, K, F, tiled, ksplit):
     (33, 192, 48, False, 0, False, True),
     (1, 64, 8, False, 0, False, False),
 ])
-def test_linear_with_rmsnorm_folded_in(monkeypatch, R, K, N, tiled, ksplit, with_res, swiglu):
+def test_linear_with_rmsnorm_folded_in(R, K, N, tiled, ksplit, with_res, swiglu):
     """RMSNorm of the input inside the projection: rows of the product scaled by 1/sqrt(mean(x^2) + eps), the gain folded
     into the weight at load time.  Reference: the oracle's RMSNorm followed by its projection, with the folded weight
-    the GPU gets (so that the comparison isolates the kernel), and separately the unfolded chain at a looser bound."""
-    if ksplit:
-        monkeypatch.setenv("OURO_LINEAR_KSPLIT", str(ksplit))
+    the GPU gets (so that the comparison isolates the kernel), and separately the unfolded chain at a looser bound.
+    The folded weight itself (a load-time library call) must equal the product rounded once to bf16, bit for bit."""
     rng = np.random.default_rng(R * 3 + K + N)
     eps = 1e-5
     x = _bf(rng.standard_normal((R, K)) * 1.7)
     w = _bf(rng.standard_normal((N, K)) * 0.05)
     g = _bf(1 + 0.2 * rng.standard_normal(K))
     res = _bf(rng.standard_normal((R, N))) if with_res else None
-    w_fold_d = ob.fold_rmsnorm_gain(_up(w), _up(g))
+    w_fold_d = ob.ouro_fold_rmsnorm_gain(_up(w), _up(g))
     w_fold = w_fold_d.float().cpu().numpy().astype(np.float64)
+    # the product of two bf16 values is exact in fp32 (8 + 8 significant bits), so one rounding defines the result
+    assert np.array_equal(w_fold_d.float().cpu().numpy(), W.round_to_bf16(w.astype(np.float32) * g.astype(np.float32)[None, :]))
     ones = np.ones(K)
     pre = LO.linear(LO.rmsnorm(x, ones, eps), w_fold)                   # = rinv * (x . w_fold^T), fp64
     pre_unfolded = LO.linear(LO.rmsnorm(x, g, eps), w)
@@ -181,7 +180,8 @@ def test_linear_with_rmsnorm_folded_in(monkeypatch, R, K, N, tiled, ksplit, with
     ref = post(pre) + (0 if res is None else res)
     ref_unfolded = post(pre_unfolded) + (0 if res is None else res)
     w_use = ob.ouro_lmhead_pack_w(w_fold_d) if tiled else w_fold_d
-    out = ob.ouro_linear(_up(x), w_use, residual=None if res is None else _up(res), swiglu=swiglu, rms_eps=eps)
+    out = ob.ouro_linear(_up(x), w_use, residual=None if res is None else _up(res), swiglu=swiglu, rms_eps=eps,
+                         ksplit=ksplit)
     torch.cuda.synchronize()
     got = to_np64(out)
     tol = np.abs(ref).max() * BF16_EPS + 1e-4
@@ -191,14 +191,13 @@ def test_linear_with_rmsnorm_folded_in(monkeypatch, R, K, N, tiled, ksplit, with
 
 
 @pytest.mark.parametrize("ksplit", [2, 3, 5])
-def test_linear_uneven_k_split(monkeypatch, ksplit):
+def test_linear_uneven_k_split(ksplit):
     """The k range split over workgroups, including splits that do not divide the 5 k-tiles evenly (one share empty)."""
-    monkeypatch.setenv("OURO_LINEAR_KSPLIT", str(ksplit))
     rng = np.random.default_rng(ksplit)
     x, w, res = _bf(rng.standard_normal((70, 320))), _bf(rng.standard_normal((264, 320)) * 0.05), _bf(rng.standard_normal((70, 264)))
     ref = LO.linear(x, w, res)
     ws = torch.full((ksplit * 70 * (264 + 1) * 4,), 0xA5, dtype=torch.uint8, device=DEV)   # contents must not matter
-    out = ob.ouro_linear(_up(x), _up(w), residual=_up(res), workspace=ws)
+    out = ob.ouro_linear(_up(x), _up(w), residual=_up(res), workspace=ws, ksplit=ksplit)
     torch.cuda.synchronize()
     assert np.abs(to_np64(out) - ref).max() <= np.abs(ref).max() * BF16_EPS + 1e-4
 
@@ -263,7 +262,7 @@ def test_one_verifying_layer_chained_on_the_gpu():
     att2 = ob.ouro_verify_attn(q2, _up(inp["k_cache"]), _up(inp["v_cache"]), cu_d, k2, v2, meta, int(lens.max()))
     x1b = ob.ouro_linear(att2.view(R, Hd), ob.ouro_lmhead_pack_w(_up(wo)), residual=x_d)
     h2b = ob.ouro_rmsnorm(x1b, _up(g2), 1e-5)
-    w_pairs = ob.ouro_lmhead_pack_w(ob.interleave_gate_up(_up(wgu[:F]), _up(wgu[F:])))
+    w_pairs = ob.ouro_lmhead_pack_w(ob.ouro_interleave_gate_up(_up(wgu[:F]), _up(wgu[F:])))
     act2 = ob.ouro_linear(h2b, w_pairs, swiglu=True)
     out2 = ob.ouro_linear(act2, ob.ouro_lmhead_pack_w(_up(wd)), residual=x1b)
     torch.cuda.synchronize()
@@ -273,8 +272,8 @@ def test_one_verifying_layer_chained_on_the_gpu():
     assert err2 <= 8 * BF16_EPS * scale
 
     # ---- and with both RMSNorms folded into the projections that follow them: 7 calls for the layer
-    wqkv_f = ob.ouro_lmhead_pack_w(ob.fold_rmsnorm_gain(_up(wqkv), _up(g1)))
-    wgu_f = ob.ouro_lmhead_pack_w(ob.fold_rmsnorm_gain(ob.interleave_gate_up(_up(wgu[:F]), _up(wgu[F:])), _up(g2)))
+    wqkv_f = ob.ouro_lmhead_pack_w(ob.ouro_fold_rmsnorm_gain(_up(wqkv), _up(g1)))
+    wgu_f = ob.ouro_lmhead_pack_w(ob.ouro_fold_rmsnorm_gain(ob.ouro_interleave_gate_up(_up(wgu[:F]), _up(wgu[F:])), _up(g2)))
     qkv3 = ob.ouro_linear(x_d, wqkv_f, rms_eps=1e-5)
     q3, k3, v3 = torch.empty_like(q_d), torch.empty_like(k_d), torch.empty_like(v_d)
     ob.ouro_rope_block(q3, k3, meta, cu_d, qkv=qkv3, v_blk=v3)
@@ -339,7 +338,7 @@ def test_layer_ops_edge_shapes():
 
 
 @pytest.mark.parametrize("case", range(16))
-def test_linear_seeded_random_options(monkeypatch, case):
+def test_linear_seeded_random_options(case):
     """A seeded sweep over ouro_linear's options together: rows on both sides of the 64-row instance boundary, ragged last
     slabs, k splits that the heuristic would not pick, residual, the SwiGLU epilogue and the folded RMSNorm."""
     rng = np.random.default_rng(600 + case)
@@ -350,8 +349,6 @@ def test_linear_seeded_random_options(monkeypatch, case):
     rms = bool(rng.integers(0, 2))
     with_res = (not swiglu) and bool(rng.integers(0, 2))
     ksplit = int(rng.choice([0, 0, 2, 3]))
-    if ksplit:
-        monkeypatch.setenv("OURO_LINEAR_KSPLIT", str(ksplit))
     eps = 1e-5
     x = _bf(rng.standard_normal((R, K)) * 1.3)
     w = _bf(rng.standard_normal((N, K)) * 0.06)
@@ -363,6 +360,7 @@ def test_linear_seeded_random_options(monkeypatch, case):
     w_d = _up(w)
     if rng.integers(0, 2):
         w_d = ob.ouro_lmhead_pack_w(w_d)
-    out = ob.ouro_linear(_up(x), w_d, residual=None if res is None else _up(res), swiglu=swiglu, rms_eps=eps if rms else 0.0)
+    out = ob.ouro_linear(_up(x), w_d, residual=None if res is None else _up(res), swiglu=swiglu, rms_eps=eps if rms else 0.0,
+                         ksplit=ksplit)
     torch.cuda.synchronize()
     assert np.abs(to_np64(out) - ref).max() <= np.abs(ref).max() * BF16_EPS + 1e-4
