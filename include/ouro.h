@@ -57,7 +57,8 @@ enum {
   OURO_E_MISALIGNED = -5,          /* a pointer is not 16-byte aligned */
   OURO_E_HIP = -6,                 /* a HIP call failed; see ouro_last_hip_error() */
   OURO_E_BAD_STRUCT = -7,          /* struct_size does not match this header */
-  OURO_E_BAD_META = -8             /* ouro_validate_meta_host only */
+  OURO_E_BAD_META = -8,            /* ouro_validate_meta_host only */
+  OURO_E_STATIC_SCRATCH_TOO_SMALL = -9   /* ouro_lmhead_argmax_static only: the size needs more than the built-in buffer */
 };
 
 typedef enum { OURO_F32 = 0, OURO_BF16 = 1 } ouro_dtype;
@@ -169,6 +170,19 @@ enum { OURO_W_ROW_MAJOR = 0, OURO_W_TILED = 1 };
 
 OURO_API size_t ouro_lmhead_argmax_workspace(const ouro_lmhead_desc* desc);
 OURO_API int ouro_lmhead_argmax(const ouro_lmhead_desc* desc, void* hip_stream);
+
+/* For callers that cannot allocate device memory or hand a workspace over (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): ouro_lmhead_argmax with the cross-slab partials kept in a buffer that is
+ * part of the library's own device image (OURO_LMHEAD_STATIC_SCRATCH_BYTES per GPU, held until the process ends).
+ * Same descriptor, same kernels, same results; desc->workspace and workspace_bytes are ignored.  The call allocates
+ * nothing and calls no allocating routine.  A size whose partials (ouro_lmhead_argmax_workspace bytes) exceed the
+ * buffer is rejected with OURO_E_STATIC_SCRATCH_TOO_SMALL before anything is enqueued (with V = 32000 the limit is
+ * 2097 rows).  All calls on one GPU share that GPU's buffer:
+ * calls that may overlap on one GPU (different streams, several threads) race on it and must be serialised by the
+ * caller; calls on different GPUs are independent.  Nothing in the buffer has to be cleared between calls: every
+ * partial a call reads it has written before. */
+#define OURO_LMHEAD_STATIC_SCRATCH_BYTES (2u << 20)
+OURO_API int ouro_lmhead_argmax_static(const ouro_lmhead_desc* desc, void* hip_stream);
 
 /* Bytes of the OURO_W_TILED form of a bf16 [V, Hd] weight (Hd a multiple of 64); 0 if the shape is invalid. */
 OURO_API size_t ouro_lmhead_packed_w_bytes(int32_t V, int32_t Hd);

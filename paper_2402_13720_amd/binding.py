@@ -116,6 +116,8 @@ def _load() -> C.CDLL:
     lib.ouro_lmhead_argmax_workspace.argtypes = [C.POINTER(ouro_lmhead_desc)]
     lib.ouro_lmhead_argmax.restype = C.c_int
     lib.ouro_lmhead_argmax.argtypes = [C.POINTER(ouro_lmhead_desc), C.c_void_p]
+    lib.ouro_lmhead_argmax_static.restype = C.c_int
+    lib.ouro_lmhead_argmax_static.argtypes = [C.POINTER(ouro_lmhead_desc), C.c_void_p]
     lib.ouro_lmhead_packed_w_bytes.restype = C.c_size_t
     lib.ouro_lmhead_packed_w_bytes.argtypes = [C.c_int32, C.c_int32]
     lib.ouro_lmhead_pack_w.restype = C.c_int
@@ -313,6 +315,15 @@ def ouro_lmhead_argmax(hidden, w, argmax_out=None, max_out=None, workspace=None,
         workspace = alloc_workspace(ouro_lmhead_argmax_workspace(hidden, w), hidden.device)
     d = make_lmhead_desc(hidden, w, argmax_out, max_out, workspace)
     _check(lib.ouro_lmhead_argmax(C.byref(d), _stream(stream)), "ouro_lmhead_argmax")
+    return argmax_out
+
+
+def ouro_lmhead_argmax_static(hidden, w, argmax_out, max_out=None, stream=None):
+    """ouro_lmhead_argmax with the partials in the library's built-in buffer: no workspace, nothing allocated by the
+    call (the outputs are the caller's).  Returns argmax_out."""
+    assert hidden.is_contiguous() and w.is_contiguous() and hidden.dtype == w.dtype
+    d = make_lmhead_desc(hidden, w, argmax_out, max_out, None)
+    _check(lib.ouro_lmhead_argmax_static(C.byref(d), _stream(stream)), "ouro_lmhead_argmax_static")
     return argmax_out
 
 

@@ -107,7 +107,7 @@ static int validate_attn(const ouro_attn_desc* d, bool need_pointers) {
   return OURO_OK;
 }
 
-static int validate_lmhead(const ouro_lmhead_desc* d, bool need_pointers) {
+int validate_lmhead(const ouro_lmhead_desc* d, bool need_pointers) {
   if (!d) return OURO_E_NULLPTR;
   if (d->struct_size != sizeof(ouro_lmhead_desc)) return OURO_E_BAD_STRUCT;
   if (d->dtype != OURO_F32 && d->dtype != OURO_BF16) return OURO_E_UNSUPPORTED_DTYPE;
@@ -155,6 +155,18 @@ static int validate_kv_commit(const ouro_kv_commit_desc* d) {
   return OURO_OK;
 }
 
+// The two launches of the LM head (main kernel, cross-slab arg-max) on a validated descriptor whose workspace holds
+// at least plan.total() bytes.
+int enqueue_lmhead(const ouro_lmhead_desc& d, const LmPlan& p, hipStream_t stream) {
+  if (d.ev_start && hipEventRecord(static_cast<hipEvent_t>(d.ev_start), stream) != hipSuccess)
+    return hip_failed(hipGetLastError());
+  const int st = d.dtype == OURO_BF16 ? launch_lmhead_bf16(d, p, stream) : launch_lmhead_f32(d, p, stream);
+  if (st != OURO_OK) return st;
+  if (d.ev_stop && hipEventRecord(static_cast<hipEvent_t>(d.ev_stop), stream) != hipSuccess)
+    return hip_failed(hipGetLastError());
+  return launch_lmhead_final(d, p, stream);
+}
+
 }  // namespace ouro
 
 using namespace ouro;
@@ -194,14 +206,7 @@ int ouro_lmhead_argmax(const ouro_lmhead_desc* desc, void* hip_stream) {
   LmPlan p = plan_lmhead(*desc);
   if (!desc->workspace) return OURO_E_NULLPTR;
   if (desc->workspace_bytes < p.total()) return OURO_E_WORKSPACE_TOO_SMALL;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (desc->ev_start && hipEventRecord(static_cast<hipEvent_t>(desc->ev_start), stream) != hipSuccess)
-    return hip_failed(hipGetLastError());
-  st = desc->dtype == OURO_BF16 ? launch_lmhead_bf16(*desc, p, stream) : launch_lmhead_f32(*desc, p, stream);
-  if (st != OURO_OK) return st;
-  if (desc->ev_stop && hipEventRecord(static_cast<hipEvent_t>(desc->ev_stop), stream) != hipSuccess)
-    return hip_failed(hipGetLastError());
-  return launch_lmhead_final(*desc, p, stream);
+  return enqueue_lmhead(*desc, p, static_cast<hipStream_t>(hip_stream));
 }
 
 size_t ouro_lmhead_packed_w_bytes(int32_t V, int32_t Hd) {
@@ -340,6 +345,7 @@ const char* ouro_status_string(int status) {
     case OURO_E_HIP: return "a HIP call failed";
     case OURO_E_BAD_STRUCT: return "struct_size does not match the header";
     case OURO_E_BAD_META: return "block metadata violates the layout rules";
+    case OURO_E_STATIC_SCRATCH_TOO_SMALL: return "the size needs more scratch than the library's built-in buffer holds";
     default: return "unknown status";
   }
 }

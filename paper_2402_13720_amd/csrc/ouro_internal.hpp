@@ -68,6 +68,8 @@ struct LmPlan {
 };
 
 LmPlan plan_lmhead(const ouro_lmhead_desc& d);
+int validate_lmhead(const ouro_lmhead_desc* d, bool need_pointers);
+int enqueue_lmhead(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
 int launch_lmhead_bf16(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
 int launch_lmhead_bf16_tile(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);
 int launch_lmhead_f32(const ouro_lmhead_desc& d, const LmPlan& plan, hipStream_t stream);

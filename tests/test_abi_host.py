@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported():
 def test_version_and_status_strings():
     assert ob.lib.ouro_version() == 210
     assert ob.lib.ouro_status_string(0) == b"ok"
-    for code in range(-8, 0):
+    for code in range(-9, 0):
         assert ob.lib.ouro_status_string(code) not in (b"ok", b"unknown status")
     assert ob.lib.ouro_status_string(-99) == b"unknown status"
 
@@ -139,6 +139,22 @@ def test_lmhead_descriptor_validation():
     assert f(C.byref(_lm_desc(**ok, workspace=512, workspace_bytes=8)), None) == -4
     need = ob.lib.ouro_lmhead_argmax_workspace(C.byref(_lm_desc()))
     assert need >= 250 * 64 * 8
+
+
+def test_static_scratch_entry_point_rejects_what_its_buffer_cannot_hold():
+    """ouro_lmhead_argmax_static needs no workspace; sizes beyond its built-in 2 MiB are refused before any HIP call."""
+    f = ob.lib.ouro_lmhead_argmax_static
+    assert f(None, None) == -1
+    assert f(C.byref(_lm_desc(struct_size=4)), None) == -7
+    assert f(C.byref(_lm_desc(V=0)), None) == -2
+    assert f(C.byref(_lm_desc()), None) == -1                                       # data pointers missing
+    assert f(C.byref(_lm_desc(R=0)), None) == 0
+    ok = dict(hidden=512, w=512, argmax_out=512)
+    need = lambda **kw: ob.lib.ouro_lmhead_argmax_workspace(C.byref(_lm_desc(**kw)))
+    assert need(R=2097) <= (2 << 20) < need(R=2098)
+    assert f(C.byref(_lm_desc(R=2098, **ok)), None) == -9                           # 125 slabs x 2098 rows x 8 bytes > 2 MiB
+    assert f(C.byref(_lm_desc(R=64, V=5_000_000, **ok)), None) == -9
+    assert ob.lib.ouro_status_string(-9) not in (b"ok", b"unknown status")
 
 
 def test_packed_weight_helpers():
