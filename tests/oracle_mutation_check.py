@@ -26,6 +26,11 @@ MUTATIONS = [
     ("oracle/verify_oracle.py", "out = (e / den) @ v", "out = e @ v"),
     ("oracle/verify_oracle.py", "elif t > 0 and pid[t - 1] == pid[t]:", "elif t > 0 and pid[t - 1] != 0:"),
     ("oracle/verify_oracle.py", "hi = lo + int(seq_len[b])", "hi = lo + int(seq_len[b]) + 1"),
+    ("oracle/verify_oracle.py", "return t == 0                    # no prediction", "return True                      # no prediction"),
+    ("oracle/verify_oracle.py", "match[t] = 1 if t == 0 else 0", "match[t] = 1"),
+    # the chained step
+    ("oracle/verify_oracle.py", "hidden = att[\"out\"].reshape(B * T, Hq * D)", "hidden = att[\"out\"].transpose(0, 1, 3, 2).reshape(B * T, Hq * D)"),
+    ("oracle/verify_oracle.py", "amax = lm[\"argmax\"].reshape(B, T)", "amax = lm[\"argmax\"].reshape(T, B).T"),
     # commit of accepted tokens
     ("oracle/verify_oracle.py", "k_new[start + have + i] = k_blk[b, t]", "k_new[start + have + i] = k_blk[b, i]"),
     ("oracle/verify_oracle.py", "v_new[start + have + i] = v_blk[b, t]", "v_new[start + have + i] = k_blk[b, t]"),
