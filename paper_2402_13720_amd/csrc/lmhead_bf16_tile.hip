@@ -10,10 +10,10 @@
 //     registers of the lane), so that 8 operand fragments feed 16 MFMAs per 16-wide k step;
 //   * with one wave per SIMD nothing else hides latency, so the loop is software-pipelined by hand and the
 //     order is pinned with scheduling barriers: the fragments of k step s+1 are read from LDS between the
-//     MFMAs of step s (two fragment register sets), and the staging work of the next k-tile (registers ->
-//     the other LDS buffer, each staging register re-armed at once with the k-tile after next from global
-//     memory) sits between the MFMAs of steps 1 and 2; one barrier per k-tile, before step 3 prefetches the
-//     first fragments of the next k-tile;
+//     MFMAs of step s (two fragment register sets), and the staging work (registers -> the LDS buffer that
+//     is not being read, each staging register re-armed at once from global memory) is spread evenly over
+//     the four k steps of a k-tile, four registers each; one barrier per k-tile, before step 3 prefetches
+//     the first fragments of the next k-tile;
 //   * LDS tiles have 128-byte rows with XOR-swizzled 16-byte chunks (conflict-free fragment reads and
 //     staging writes);
 //   * epilogue: arg-max lane -> wave -> workgroup with the total order (larger value, then
@@ -123,39 +123,60 @@ __global__ __launch_bounds__(kThreads) void lmhead_bf16_tile_kernel(TileArgs a) 
     fa[SET][(Q) & 3] = *reinterpret_cast<const bf16x8*>(lds + (BUF) * kBufBytes + wave_w + ((Q) & 3) * 4096 + rd[S]); \
   else                                                                                                         \
     fb[SET][(Q) & 3] = *reinterpret_cast<const bf16x8*>(lds + (BUF) * kBufBytes + wave_h + ((Q) & 3) * 4096 + rd[S]);
-// One 16-wide k step: 16 MFMAs on register set SET; between them, the 8 fragment reads of the next k step
-// (step NS of buffer NBUF, into the other register set) and, when STAGE is 1 / 2, the W / hidden half of the
-// staging work (registers -> other LDS buffer, then the same register is re-armed with the k-tile after next).
-// The scheduling barriers pin this interleaving: one wave per SIMD, so all latency hiding is in this order.
+// One 16-wide k step: 16 MFMAs on register set SET; between the first eight, the 8 fragment reads of the next k step
+// (step NS of buffer NBUF, into the other register set); between the last eight, a quarter of the staging work: four
+// staging registers go to LDS and each is re-armed at once from global memory.  The scheduling barriers pin this
+// interleaving: one wave per SIMD, so all latency hiding is in this order.
+//   STAGE 1: W rows 128.. (registers 4-7) of k-tile kt+1 -> the other buffer, re-armed with k-tile kt+2
+//   STAGE 2, 3: hidden rows (registers 0-3, 4-7) of k-tile kt+1 -> the other buffer, re-armed with k-tile kt+2
+//   STAGE 4 (the step after the barrier): W rows 0..127 (registers 0-3) of k-tile kt+2 -> the buffer just read out,
+//            re-armed with k-tile kt+3
+// so that every k step carries the same 4 LDS stores and 4 global loads: all four waves run in lock step, and with the
+// staging bunched into two of the four steps their 64 loads met in the address unit in one burst that held the
+// matrix instructions behind them back.
 #define OURO_KSTEP(SET, NS, NBUF, STAGE)                                                                       \
   _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                                             \
     acc[j >> 2][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[SET][j >> 2], fb[SET][j & 3], acc[j >> 2][j & 3], 0, 0, 0); \
     if (j < 8) {                                                                                               \
       const int q_ = j == 0 ? 0 : j < 5 ? j + 3 : j - 4;   /* order: W0, H0..H3, W1..W3 */                     \
       OURO_FRAG(q_, NS, NBUF, (SET) ^ 1)                                                                       \
-    } else if ((STAGE) == 1) {                                                                                 \
-      OURO_STORE_W(j - 8, cur ^ 1)                                                                             \
-      OURO_GLOAD_W(j - 8, ktl)                                                                                 \
-    } else if ((STAGE) == 2) {                                                                                 \
-      OURO_STORE_H(j - 8, cur ^ 1)                                                                             \
-      OURO_GLOAD_H(j - 8, ktl)                                                                                 \
+    } else if ((j & 1) == 0) {                                                                                 \
+      const int p_ = (j - 8) >> 1;                                                                             \
+      if ((STAGE) == 1) { OURO_STORE_W(4 + p_, cur ^ 1) OURO_GLOAD_W(4 + p_, ktl) }                            \
+      if ((STAGE) == 2) { OURO_STORE_H(p_, cur ^ 1) OURO_GLOAD_H(p_, ktl) }                                    \
+      if ((STAGE) == 3) { OURO_STORE_H(4 + p_, cur ^ 1) OURO_GLOAD_H(4 + p_, ktl) }                            \
+      if ((STAGE) == 4) { OURO_STORE_W(p_, cur) OURO_GLOAD_W(p_, ktl3) }                                       \
     }                                                                                                          \
     __builtin_amdgcn_sched_barrier(0);                                                                         \
   }
 
   const int nkt = Hd / kBK;
-  // prologue: k-tile 0 -> LDS buffer 0, k-tile 1 -> registers, first fragments -> register set 0
-  // (loads in the order the loop re-arms them, so that its counted waits are exact from the first iteration)
-#pragma unroll
-  for (int p = 0; p < 8; ++p) { OURO_GLOAD_W(p, 0) }
-#pragma unroll
-  for (int p = 0; p < 8; ++p) { OURO_GLOAD_H(p, 0) }
+  // prologue: k-tile 0 -> LDS buffer 0; W rows 0..127 of k-tile 1 -> buffer 1; registers: W 0-3 <- k-tile 2, W 4-7 and
+  // the hidden rows <- k-tile 1; first fragments -> register set 0.  (The last loads are issued in the order in which
+  // the loop re-arms them, so that its counted waits are exact from the first iteration.)
   {
-    const int kt1 = min(1, nkt - 1);
+    const int kt1 = min(1, nkt - 1), kt2 = min(2, nkt - 1);
+    u32x4 w1[4];
 #pragma unroll
-    for (int p = 0; p < 8; ++p) { OURO_STORE_W(p, 0) OURO_GLOAD_W(p, kt1) __builtin_amdgcn_sched_barrier(0); }
+    for (int p = 0; p < 8; ++p) { OURO_GLOAD_W(p, 0) }
 #pragma unroll
-    for (int p = 0; p < 8; ++p) { OURO_STORE_H(p, 0) OURO_GLOAD_H(p, kt1) __builtin_amdgcn_sched_barrier(0); }
+    for (int p = 0; p < 8; ++p) { OURO_GLOAD_H(p, 0) }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) w1[p] = *reinterpret_cast<const u32x4*>(wbase + static_cast<size_t>(kt1) * wstep + woff[p]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int p = 0; p < 8; ++p) { OURO_STORE_W(p, 0) }
+#pragma unroll
+    for (int p = 0; p < 8; ++p) { OURO_STORE_H(p, 0) }
+#pragma unroll
+    for (int p = 4; p < 8; ++p) { OURO_GLOAD_W(p, kt1) }
+#pragma unroll
+    for (int p = 0; p < 8; ++p) { OURO_GLOAD_H(p, kt1) }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) { OURO_GLOAD_W(p, kt2) }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) *reinterpret_cast<u32x4*>(lds + kBufBytes + p * 4096 + wr0) = w1[p];
   }
   __syncthreads();
 #pragma unroll
@@ -164,13 +185,14 @@ __global__ __launch_bounds__(kThreads) void lmhead_bf16_tile_kernel(TileArgs a) 
   for (int kt = 0; kt < nkt; ++kt) {
     const int cur = kt & 1;
     const int ktl = min(kt + 2, nkt - 1);     // past the end: a harmless reload of the last k-tile
-    OURO_KSTEP(0, 1, cur, 0)
-    OURO_KSTEP(1, 2, cur, 1)
-    OURO_KSTEP(0, 3, cur, 2)
-    // every wave has read the last fragments of buffer cur^1's previous contents before the previous
-    // barrier and has now written its share of k-tile kt+1 there
+    const int ktl3 = min(kt + 3, nkt - 1);
+    OURO_KSTEP(0, 1, cur, 1)
+    OURO_KSTEP(1, 2, cur, 2)
+    OURO_KSTEP(0, 3, cur, 3)
+    // Every wave has read the last fragments of buffer cur before this barrier (they are in its registers), and has
+    // written its share of k-tile kt+1 to buffer cur^1: after it, cur^1 is complete and cur may be overwritten.
     __syncthreads();
-    OURO_KSTEP(1, 0, cur ^ 1, 0)
+    OURO_KSTEP(1, 0, cur ^ 1, 4)
   }
 #undef OURO_GLOAD_W
 #undef OURO_GLOAD_H
