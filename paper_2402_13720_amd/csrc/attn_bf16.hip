@@ -81,6 +81,8 @@ struct AttnArgs {
   int T, Hq, Hkv, G, M;
   int nrb, nch, chunk;
   int rows_wg;         // query rows per workgroup (32 x row blocks per workgroup)
+  int nbg;             // B * Hkv
+  FastDiv div_per, div_nbg, div_hkv, div_g, div_nrb, div_chunk;   // by 8 * nrb, B * Hkv, Hkv, G, nrb, chunk
   int max_seqlen;      // the host's bound on every length: grid, chunk slots and workspace were sized from it, so a
                        // longer device-side length is cut to it (a stale bound must not reach past any of them)
   float scale_log2;
@@ -92,9 +94,9 @@ constexpr int kRows = 32;                                  // query rows per wor
 constexpr int kQBytes = kRows * 256;                       // Q tile shared by the 4 waves, same swizzle as the K tile
 constexpr int kStateBytes = 16 * 64 * 16;                  // O accumulators of one wave, lane-major
 constexpr int kMergeBytes = 4 * kRows * (kStageRow * 4 + 8);   // the four wave states, row-major, + their (max, sum) pairs
-constexpr int kPidBytes = 128 * 2;                         // phrase ids of the block keys (T <= 128)
+constexpr int kClassBytes = 128 * 16;                      // per phrase id 0..127: 128-bit set of the block keys that carry it
 constexpr int kMainLds = cmax(kQBytes + 4 * kWaveLds, kMergeBytes);   // the merge reuses the tiles' space
-constexpr int kLdsBytes = kMainLds + kPidBytes;            // 72 KB: two workgroups per CU
+constexpr int kLdsBytes = kMainLds + kClassBytes;          // 74 KB: two workgroups per CU
 
 // Slot (16 bytes = 8 keys of one head-dim element d) of the transposed V tile.
 // d = 8*a + j, c = key group (0..3).  Writers (fixed j, c; a = 0..15) and readers
@@ -114,10 +116,54 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Maximum over the two 32-lane halves of the wave (lanes l and l ^ 32), returned in both: one register swap between the
+// halves on the vector ALU (v_permlane32_swap) instead of a round trip through the LDS crossbar, which sat in the
+// dependent chain of every tile (scores -> maximum -> exponentials).
+__device__ __forceinline__ float max_across_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// ---- the block part of the mask as bit sets ----------------------------------------------------------------------
+// Row q sees block key k iff  pid[k] == 0 ? k <= boff[q] : (pid[k] == pid[q] && k <= q)  (Eq. (2) / Eq. (8)).  Per
+// workgroup, a small LDS table holds for every phrase id the 128-bit set of block keys that carry it (built with one
+// LDS atomic per key); a lane then forms the set its own query row sees with a few word operations,
+//   vis = class[0] & low(boff_q + 1)  |  (pid_q != 0 ? class[pid_q] & low(q + 1) : 0),
+// once, and a tile step that touches block keys masks its 16 scores with bit tests on a 32-bit window of that set:
+// no memory access and no data-dependent branch per score.
+__device__ __forceinline__ u32x4 low_bits(int n) {        // the n lowest of 128 bits (n <= 0: none; n >= 128: all)
+  u32x4 r;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const int m = n - 32 * w;
+    r[w] = m >= 32 ? ~0u : m <= 0 ? 0u : ((1u << m) - 1u);
+  }
+  return r;
+}
+__device__ __forceinline__ u32x4 row_visibility(const u32x4* cls, int pidq, int boffq, int tq) {
+  u32x4 vis = cls[0] & low_bits(boffq + 1);
+  const u32x4 own = cls[pidq & 127] & low_bits(tq + 1);
+  if (pidq != 0) vis |= own;
+  return vis;
+}
+// Scores S (accumulator layout: register i of a lane of half h holds key 16*((i/4)%2) + 4*(i%4) + 2*(i/8) + h of the
+// tile) of the tile at key TILE: keys before the block are cached tokens, visible to every row; block key kb is bit kb
+// of vis; keys past the block are not there.  [32 ones | vis | zeros] shifted to the tile's first key is the window.
+#define OURO_ATTN_MASK_TILE(TILE, S)                                                                               \
+  if ((TILE) + 32 > L) {                                                                                           \
+    const int e_ = (TILE) - L + 32;               /* >= 1; wave-uniform */                                         \
+    const int wi_ = e_ >> 5;                                                                                       \
+    const unsigned lo_ = wi_ == 0 ? ~0u : wi_ == 1 ? vis.x : wi_ == 2 ? vis.y : wi_ == 3 ? vis.z : wi_ == 4 ? vis.w : 0u; \
+    const unsigned hi_ = wi_ == 0 ? vis.x : wi_ == 1 ? vis.y : wi_ == 2 ? vis.z : wi_ == 3 ? vis.w : 0u;           \
+    const unsigned win_ = __builtin_amdgcn_alignbit(hi_, lo_, static_cast<unsigned>(e_ & 31)) >> half;             \
+    _Pragma("unroll") for (int i = 0; i < 16; ++i)                                                                 \
+        S[i] = (win_ & (1u << (16 * ((i >> 2) & 1) + 4 * (i & 3) + 2 * (i >> 3)))) ? S[i] : -INFINITY;             \
+  }
+
 // ---- building blocks shared by the two kernels (macros rather than functions: the register arrays they
 // ---- work on must stay in registers) ---------------------------------------------------------------------
 // Names they expect in scope: a, b, g, T, L, k_end, fast_end, cu0, Hkv, kq, c16, row_base, loff0, kstride (staging);
-// col, half, tq, pidq, boffq, o, m_run, l_run (the wave's flash state); kpid (phrase ids of the block keys, in LDS).
+// col, half, o, m_run, l_run (the wave's flash state); vis (the block keys this lane's query row sees, one bit per key).
 
 // Issue the global loads of the 32-key tile that starts at key TILE of the sequence's [cache | block] axis into
 // the staging registers (8 K loads, then 8 V loads: always, so that counted waits stay exact); a tile wholly
@@ -171,26 +217,44 @@ __device__ __forceinline__ void wave_lds_fence() {
 // rescale of O is skipped on almost every tile.  l_run is a per-half partial sum; halves are added at the end.
 //
 // O^T += V^T . P^T with P^T = the S^T accumulator registers rounded to bf16.
+#define OURO_ATTN_KFRAG(KL, S) *reinterpret_cast<const bf16x8*>((KL) + k_slot(col, 2 * (S) + half) * 16)
+#define OURO_ATTN_VFRAG(VL, DT, C) *reinterpret_cast<const bf16x8*>((VL) + vt_slot(4 * (DT) + (col >> 3), col & 7, (C)) * 16)
+// Order of a tile step (two waves per SIMD and 256 registers each, so the fragment registers are few and the order in
+// which LDS reads are issued decides how much of their latency the wave sits out): the (K, Q) fragment pairs of
+// S^T = K . Q^T are read four k steps ahead of the MFMA that uses them (a rolling set of 8 fragment registers; read
+// one pair at a time right before its MFMA, every MFMA of the chain waited for a full LDS round trip); the 8 V^T
+// fragments are then read into the same registers before the softmax arithmetic, which hides their latency, so
+// that the O^T += V^T . P^T MFMAs find their operands waiting.
 #define OURO_ATTN_COMPUTE_TILE(TILE, KL, VL, QL)                                                                   \
   {                                                                                                                \
     f32x16 sacc;                                                                                                   \
-    _Pragma("unroll") for (int i = 0; i < 16; ++i) sacc[i] = 0.f;                                                  \
-    _Pragma("unroll") for (int s = 0; s < 8; ++s) {                                                                \
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>((KL) + k_slot(col, 2 * s + half) * 16);                   \
-      const bf16x8 qf = *reinterpret_cast<const bf16x8*>((QL) + k_slot(col, 2 * s + half) * 16);                   \
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf, sacc, 0, 0, 0);                                       \
+    bf16x8 fr[8];                                                                                                  \
+    _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                                                \
+      fr[2 * s] = OURO_ATTN_KFRAG(KL, s);                                                                          \
+      fr[2 * s + 1] = OURO_ATTN_KFRAG(QL, s);                                                                      \
     }                                                                                                              \
-    if ((TILE) + 32 > L) {                                                                                         \
-      _Pragma("unroll") for (int i = 0; i < 16; ++i) {                                                             \
-        const int kb = (TILE) + 16 * ((i >> 2) & 1) + 4 * (i & 3) + 2 * (i >> 3) + half - L;                       \
-        const int pidk = kpid[min(max(kb, 0), T - 1)];                                                             \
-        const bool blk_vis = pidk == 0 ? kb <= boffq : (pidk == pidq && kb <= tq);                                 \
-        sacc[i] = (kb < 0 || (kb < T && blk_vis)) ? sacc[i] : -INFINITY;                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                                             \
+    {                                                                                                              \
+      const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};      \
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[0], fr[1], zero16, 0, 0, 0);                               \
+    }                                                                                                              \
+    _Pragma("unroll") for (int s = 1; s < 8; ++s) {                                                                \
+      if (s + 3 < 8) {                                                                                             \
+        fr[2 * ((s + 3) & 3)] = OURO_ATTN_KFRAG(KL, s + 3);                                                        \
+        fr[2 * ((s + 3) & 3) + 1] = OURO_ATTN_KFRAG(QL, s + 3);                                                    \
       }                                                                                                            \
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[2 * (s & 3)], fr[2 * (s & 3) + 1], sacc, 0, 0, 0);         \
+      __builtin_amdgcn_sched_barrier(0);                                                                           \
     }                                                                                                              \
+    _Pragma("unroll") for (int dt = 0; dt < 4; ++dt) {                                                             \
+      fr[2 * dt] = OURO_ATTN_VFRAG(VL, dt, half);                                                                  \
+      fr[2 * dt + 1] = OURO_ATTN_VFRAG(VL, dt, 2 + half);                                                          \
+    }                                                                                                              \
+    __builtin_amdgcn_sched_barrier(0);                                                                             \
+    OURO_ATTN_MASK_TILE(TILE, sacc)                                                                                \
     float tmax = sacc[0];                                                                                          \
     _Pragma("unroll") for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sacc[i]);                                    \
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * a.scale_log2;                                                       \
+    tmax = max_across_halves(tmax) * a.scale_log2;                                                                 \
     if (__any(tmax > m_run + 8.0f)) {                                                                              \
       const float m_new = fmaxf(m_run, tmax);                                                                      \
       const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));                      \
@@ -211,10 +275,8 @@ __device__ __forceinline__ void wave_lds_fence() {
     const bf16x8 pf0 = __builtin_convertvector(p0, bf16x8);                                                        \
     const bf16x8 pf1 = __builtin_convertvector(p1, bf16x8);                                                        \
     _Pragma("unroll") for (int dt = 0; dt < 4; ++dt) {                                                             \
-      const bf16x8 vf0 = *reinterpret_cast<const bf16x8*>((VL) + vt_slot(4 * dt + (col >> 3), col & 7, half) * 16);     \
-      const bf16x8 vf1 = *reinterpret_cast<const bf16x8*>((VL) + vt_slot(4 * dt + (col >> 3), col & 7, 2 + half) * 16); \
-      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf0, pf0, o[dt], 0, 0, 0);                                   \
-      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf1, pf1, o[dt], 0, 0, 0);                                   \
+      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[2 * dt], pf0, o[dt], 0, 0, 0);                            \
+      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[2 * dt + 1], pf1, o[dt], 0, 0, 0);                        \
     }                                                                                                              \
   }
 
@@ -226,16 +288,16 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 
   // ---- workgroup id -> (x = (sequence, KV head, chunk), row block); same x => same id modulo 8 ----
   const int per = 8 * a.nrb;
-  const int blk = blockIdx.x / per, rem = blockIdx.x - blk * per;
+  const int blk = fdiv(blockIdx.x, a.div_per), rem = blockIdx.x - blk * per;
   const int rb = rem >> 3;
   const int x = blk * 8 + (rem & 7);
   if (x >= a.n_x) return;
   // chunk-major: the (sequence, KV head) pairs of one chunk index are consecutive, so every XCD (id modulo 8)
   // sees all chunk indices; pair-major order would give the rarely populated late chunks to a few XCDs
-  const int nbg = a.n_x / a.nch;
-  const int chunk = x / nbg;
+  const int nbg = a.nbg;
+  const int chunk = fdiv(x, a.div_nbg);
   const int bg = x - chunk * nbg;
-  const int b = bg / a.Hkv, g = bg - b * a.Hkv;
+  const int b = fdiv(bg, a.div_hkv), g = bg - b * a.Hkv;
   const int T = a.T;
   const int col = lane & 31, half = lane >> 5;
   const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
@@ -261,12 +323,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int p = tid + 256 * u;
     const int row = p >> 4, c = p & 15;
     const int rr = min(row0 + row, M - 1);        // rows past M are computed on a duplicate and never stored
-    const int t = rr / G, hh = rr - t * G;
+    const int t = fdiv(rr, a.div_g), hh = rr - t * G;
     qreg[u] = *reinterpret_cast<const u32x4*>(a.q + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD + 8 * c);
   }
   // this lane's query row (its column of S^T) and that row's metadata
   const int rq = min(row0 + col, M - 1);
-  const int tq = rq / G;
+  const int tq = fdiv(rq, a.div_g);
   const ouro_tok_meta mq = a.meta[static_cast<size_t>(b) * T + tq];
   __builtin_amdgcn_sched_barrier(0);              // keep the loads above ahead of the wait for the length below
   int c0lo = static_cast<int>(cu0_v), c0hi = static_cast<int>(cu0_v >> 32), c1lo = cu1_v;
@@ -279,13 +341,14 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   const int k_begin = chunk * a.chunk;
   if (k_begin >= n) return;                       // chunk slot beyond this sequence (uniform for the workgroup)
   const int k_end = min(n, k_begin + a.chunk);
-  const int nchb = (n + a.chunk - 1) / a.chunk;   // chunks this sequence really has
+  const bool whole = n <= a.chunk;                // the sequence has one chunk: this workgroup sees every key
   const int fast_end = min(L, k_end);             // tiles that end by here lie wholly in the cache part of the window
 
   unsigned char* ql = lds;                        // Q tile, shared
   unsigned char* kl = lds + kQBytes + wave * kWaveLds;
   unsigned char* vl = kl + kKBytes;
-  short* kpid = reinterpret_cast<short*>(lds + kMainLds);
+  u32x4* cls = reinterpret_cast<u32x4*>(lds + kMainLds);      // per phrase id: the set of block keys that carry it
+  if (tid < 128) cls[tid] = u32x4{0u, 0u, 0u, 0u};
 
   // ---- staging: lane (kq = lane/16, c16 = lane%16) loads 16 B of 8 key rows per tile ----
   // Load i of a lane fetches key 4*i + kq of the tile, so one load instruction covers 4 adjacent
@@ -301,26 +364,27 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   // plus these, no per-row address arithmetic in the loop).
   const unsigned kstride = a.kv_row_stride;        // elements between consecutive cache rows of one head
   const unsigned loff0 = static_cast<unsigned>(kq) * kstride + 8 * c16;
-  f32x16 o[4];
-  float m_run = -INFINITY, l_run = 0.f;
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
-
   // this wave's tiles: k_begin + 32*(wave + 4*i)
   int tile = k_begin + 32 * wave;
   if (tile < k_end) { OURO_ATTN_ISSUE_LOADS(tile, kr, vr) }
   // ---- Q tile and phrase-id table -> LDS (the Q tile is read back as the B operand of S^T = K . Q^T) ----
   __builtin_amdgcn_sched_barrier(0);              // keep the stores (and their waits) behind every load above
-  const int pidq = mq.phrase_id, boffq = mq.branch_off;
-  if (tid < T) kpid[tid] = my_kpid;
+  f32x16 o[4];                                    // (cleared here: nothing that can wait stands before the first loads)
+  float m_run = -INFINITY, l_run = 0.f;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+  __syncthreads();                                // the class table is cleared
+  if (tid < T) atomicOr(reinterpret_cast<unsigned*>(cls + (my_kpid & 127)) + (tid >> 5), 1u << (tid & 31));
 #pragma unroll
   for (int u = 0; u < kRows * 16 / 256; ++u) {
     const int p = tid + 256 * u;
     *reinterpret_cast<u32x4*>(ql + k_slot(p >> 4, p & 15) * 16) = qreg[u];
   }
-  __syncthreads();                                // Q tile complete
+  __syncthreads();                                // Q tile and class table complete
+  u32x4 vis = {0u, 0u, 0u, 0u};
+  if (k_end > L) vis = row_visibility(cls, mq.phrase_id, mq.branch_off, tq);   // the window reaches block keys
   for (; tile < k_end; tile += 128) {
     OURO_ATTN_STORE_TILE(kl, vl, kr, vr)
     if (tile + 128 < k_end) { OURO_ATTN_ISSUE_LOADS(tile + 128, kr, vr) }
@@ -375,11 +439,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
       lsum += f * l_w[w];
       acc += f * *reinterpret_cast<const f32x4*>(st_o + (w * kRows + row) * kStageRow + 4 * c);
     }
-    if (nchb == 1) {
+    if (whole) {
       // the workgroup saw every key of the sequence: normalise and write bf16
       const int r = row0 + row;
       if (r >= M) continue;
-      const int t = r / G, hh = r - t * G;
+      const int t = fdiv(r, a.div_g), hh = r - t * G;
       __bf16* op = a.out + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
       *reinterpret_cast<bf16x4*>(op + 4 * c) = __builtin_convertvector(acc * (1.0f / lsum), bf16x4);
       if (a.lse && c == 0)
@@ -430,17 +494,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 // mask + running-maximum update for the scores S of the tile at key TILE (see OURO_ATTN_COMPUTE_TILE) ...
 #define OURO_ATTN_SOFTMAX_MAX(TILE, S)                                                                             \
   {                                                                                                                \
-    if ((TILE) + 32 > L) {                                                                                         \
-      _Pragma("unroll") for (int i = 0; i < 16; ++i) {                                                             \
-        const int kb = (TILE) + 16 * ((i >> 2) & 1) + 4 * (i & 3) + 2 * (i >> 3) + half - L;                       \
-        const int pidk = kpid[min(max(kb, 0), T - 1)];                                                             \
-        const bool blk_vis = pidk == 0 ? kb <= boffq : (pidk == pidq && kb <= tq);                                 \
-        S[i] = (kb < 0 || (kb < T && blk_vis)) ? S[i] : -INFINITY;                                                 \
-      }                                                                                                            \
-    }                                                                                                              \
+    OURO_ATTN_MASK_TILE(TILE, S)                                                                                   \
     float tmax = S[0];                                                                                             \
     _Pragma("unroll") for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, S[i]);                                       \
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * a.scale_log2;                                                       \
+    tmax = max_across_halves(tmax) * a.scale_log2;                                                             \
     if (__any(tmax > m_run + 8.0f)) {                                                                              \
       const float m_new = fmaxf(m_run, tmax);                                                                      \
       const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));                      \
@@ -477,7 +534,7 @@ constexpr int rows_main_lds() {
   return cmax(2 * 4 * kWaveLds, cmax((4 / RW / 2) * RW * (kStateBytes + 64 * 8), 32 * RW * kStageRow * 4 + 32 * RW * 8));
 }
 template <int RW>
-constexpr int rows_lds_bytes() { return rows_main_lds<RW>() + kPidBytes; }
+constexpr int rows_lds_bytes() { return rows_main_lds<RW>() + kClassBytes; }
 
 template <int RW>
 __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
@@ -491,16 +548,16 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
 
   // ---- workgroup id -> (x = (sequence, KV head, chunk), row block); same x => same id modulo 8 ----
   const int per = 8 * a.nrb;
-  const int blk = blockIdx.x / per, rem = blockIdx.x - blk * per;
+  const int blk = fdiv(blockIdx.x, a.div_per), rem = blockIdx.x - blk * per;
   const int rb = rem >> 3;
   const int x = blk * 8 + (rem & 7);
   if (x >= a.n_x) return;
   // chunk-major: the (sequence, KV head) pairs of one chunk index are consecutive, so every XCD (id modulo 8)
   // sees all chunk indices; pair-major order would give the rarely populated late chunks to a few XCDs
-  const int nbg = a.n_x / a.nch;
-  const int chunk = x / nbg;
+  const int nbg = a.nbg;
+  const int chunk = fdiv(x, a.div_nbg);
   const int bg = x - chunk * nbg;
-  const int b = bg / a.Hkv, g = bg - b * a.Hkv;
+  const int b = fdiv(bg, a.div_hkv), g = bg - b * a.Hkv;
   const int T = a.T;
   const int col = lane & 31, half = lane >> 5;
   const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
@@ -517,7 +574,7 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
   if (a.len) len_v = a.len[b + vzero];
   const short my_kpid = tid < T ? a.meta[static_cast<size_t>(b) * T + tid].phrase_id : static_cast<short>(0);
   const int rq = min(row0 + col, M - 1);          // rows past M are computed on a duplicate and never stored
-  const int tq = rq / G;
+  const int tq = fdiv(rq, a.div_g);
   const ouro_tok_meta mq = a.meta[static_cast<size_t>(b) * T + tq];
   bf16x8 qf[8], kf[8], vf[8], pf0, pf1;
   {
@@ -536,12 +593,12 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
   const int k_begin = chunk * a.chunk;
   if (k_begin >= n) return;                       // chunk slot beyond this sequence (uniform for the workgroup)
   const int k_end = min(n, k_begin + a.chunk);
-  const int nchb = (n + a.chunk - 1) / a.chunk;   // chunks this sequence really has
+  const bool whole = n <= a.chunk;                // the sequence has one chunk: this workgroup sees every key
   const int fast_end = min(L, k_end);             // tiles that end by here lie wholly in the cache part of the window
 
   constexpr int kStageBytes4 = 4 * kWaveLds;      // one stage: 4 x (K tile, V^T tile)
-  short* kpid = reinterpret_cast<short*>(lds + rows_main_lds<RW>());
-  const int pidq = mq.phrase_id, boffq = mq.branch_off;
+  u32x4* cls = reinterpret_cast<u32x4*>(lds + rows_main_lds<RW>());   // per phrase id: the set of block keys that carry it
+  if (tid < 128) cls[tid] = u32x4{0u, 0u, 0u, 0u};
 
   const int kq = lane >> 4, c16 = lane & 15;      // staging roles, as in the kernel above
   const int row_base = 16 * (kq >> 1) + 4 * (kq & 1);
@@ -551,10 +608,6 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
 
   f32x16 o[4], sacc[2];
   float m_run = -INFINITY, l_run = 0.f;
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
 
   // staging piece PH (0..3) of a stage: registers -> this wave's tile in the buffer at NB, re-armed with tile NEXT
 #define OURO_ATTN_STAGING(PH, NB, NEXT)                                                                            \
@@ -568,7 +621,12 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
   // prologue: stage 0 -> buffer 0, stage 1 in flight (every prologue load is issued before anything waits)
   OURO_ATTN_ISSUE_LOADS(k_begin + 32 * wave, kr, vr)
   __builtin_amdgcn_sched_barrier(0);
-  if (tid < T) kpid[tid] = my_kpid;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)                  // (cleared here: nothing that can wait stands before the first loads)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+  __syncthreads();                                // the class table is cleared
+  if (tid < T) atomicOr(reinterpret_cast<unsigned*>(cls + (my_kpid & 127)) + (tid >> 5), 1u << (tid & 31));
   {
     unsigned char* kl = lds + wave * kWaveLds;
     OURO_ATTN_STORE_K(kl, kr)
@@ -577,6 +635,8 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
     OURO_ATTN_ISSUE_V(k_begin + 128 + 32 * wave, vr)
   }
   __syncthreads();
+  u32x4 vis = {0u, 0u, 0u, 0u};
+  if (k_end > L) vis = row_visibility(cls, mq.phrase_id, mq.branch_off, tq);   // the window reaches block keys
 
   int cur = 0;
   for (int sb = k_begin; sb < k_end; sb += 128, cur ^= 1) {
@@ -683,7 +743,7 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
   __syncthreads();
 
   const int group = bg * a.nrb + rb;
-  if (nchb == 1) {
+  if (whole) {
     // ---- the workgroup saw every key of the sequence: normalise and write bf16, 16 B per thread ----
     for (int p = tid; p < kRowsWg * 16; p += 256) {
       const int row = p >> 4, c = p & 15;
@@ -693,7 +753,7 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
       const f32x4 x0 = *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 8 * c);
       const f32x4 x1 = *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 8 * c + 4);
       f32x8 v8 = {x0[0] * inv, x0[1] * inv, x0[2] * inv, x0[3] * inv, x1[0] * inv, x1[1] * inv, x1[2] * inv, x1[3] * inv};
-      const int t = r / G, hh = r - t * G;
+      const int t = fdiv(r, a.div_g), hh = r - t * G;
       __bf16* op = a.out + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
       *reinterpret_cast<bf16x8*>(op + 8 * c) = __builtin_convertvector(v8, bf16x8);
       if (a.lse && c == 0)
@@ -722,12 +782,12 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
   const long p = static_cast<long>(blockIdx.x) * 256 + threadIdx.x;
   const int c = static_cast<int>(p & 15);
   const long rowg = p >> 4;
-  const int row = static_cast<int>(rowg % rows_wg);
-  const long group = rowg / rows_wg;
-  if (group >= static_cast<long>(a.n_x / a.nch) * a.nrb) return;
-  const int rb = static_cast<int>(group % a.nrb);
-  const int bg = static_cast<int>(group / a.nrb);
-  const int b = bg / a.Hkv, g = bg - b * a.Hkv;
+  const int row = static_cast<int>(rowg & (rows_wg - 1));      // rows_wg is 32, 64 or 128
+  const long group = rowg >> (rows_wg == 32 ? 5 : rows_wg == 64 ? 6 : 7);
+  if (group >= static_cast<long>(a.nbg) * a.nrb) return;
+  const int bg = fdiv(static_cast<int>(group), a.div_nrb);
+  const int rb = static_cast<int>(group) - bg * a.nrb;
+  const int b = fdiv(bg, a.div_hkv), g = bg - b * a.Hkv;
   const int r = rb * rows_wg + row;
   if (r >= a.M) return;
   const size_t gbase = static_cast<size_t>(group) * a.nch * rows_wg;
@@ -767,7 +827,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
   // group, so every slot is readable), which puts its loads in flight together with the length's.
   load4(0, a.nch - 1);
   const int n = min(a.len ? a.len[b] : static_cast<int>(a.cu[b + 1] - a.cu[b]), a.max_seqlen) + a.T;
-  const int nchb = (n + a.chunk - 1) / a.chunk;   // <= a.nch: the length is cut to the bound a.nch was sized from
+  const int nchb = fdiv(n + a.chunk - 1, a.div_chunk);   // <= a.nch: the length is cut to the bound a.nch was sized from
   if (nchb == 1) return;                            // written directly by the main kernel
   merge4(0, nchb);
   for (int ch0 = 4; ch0 < nchb; ch0 += 4) {
@@ -775,7 +835,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     merge4(ch0, nchb);
   }
   const float inv = 1.0f / lsum;
-  const int t = r / a.G, hh = r - t * a.G;
+  const int t = fdiv(r, a.div_g), hh = r - t * a.G;
   __bf16* op = a.out + ((static_cast<size_t>(b) * a.T + t) * a.Hq + g * a.G + hh) * kD;
   *reinterpret_cast<bf16x8*>(op + 8 * c) = __builtin_convertvector(acc * inv, bf16x8);
   if (a.lse && c == 0)
@@ -810,6 +870,13 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
   a.nch = plan.nch;
   a.chunk = plan.chunk;
   a.n_x = d.B * d.Hkv * plan.nch;
+  a.nbg = d.B * d.Hkv;
+  a.div_per = make_fastdiv(8u * plan.nrb);
+  a.div_nbg = make_fastdiv(static_cast<unsigned>(a.nbg));
+  a.div_hkv = make_fastdiv(static_cast<unsigned>(d.Hkv));
+  a.div_g = make_fastdiv(static_cast<unsigned>(a.G));
+  a.div_nrb = make_fastdiv(static_cast<unsigned>(plan.nrb));
+  a.div_chunk = make_fastdiv(static_cast<unsigned>(plan.chunk));
   a.scale_log2 = scale * 1.4426950408889634f;
   a.rows_wg = plan.rows_wg;
   a.max_seqlen = d.max_seqlen;

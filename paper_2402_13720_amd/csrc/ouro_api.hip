@@ -21,7 +21,7 @@ int hip_failed(hipError_t e) {
 // (rows * 512 bytes per workgroup) small against the K/V bytes of a chunk (chunk * 512 bytes).
 //
 // Up to 64 query rows per (sequence, KV head): one 32-row block per workgroup, the four waves split the
-// keys; the default aims at about 1.5 workgroups per compute unit (two are resident at a time; measured
+// keys; the default aims at about 1.25 workgroups per compute unit (two are resident at a time; measured
 // best where per-workgroup prologue/epilogue latency dominates).  More rows (long drafts, grouped-query
 // heads): the workgroup keeps 4 row blocks and its waves share the staged tiles; one workgroup per compute
 // unit, and the chunk count is the largest that still lets every workgroup be resident at once (no second
@@ -41,7 +41,7 @@ AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
   const long groups = std::max<long>(1, static_cast<long>(d.B) * d.Hkv * p.nrb);
   long tiles_per_chunk;
   if (p.rw == 1) {
-    long want = (384 + groups - 1) / groups;           // chunk slots per sequence
+    long want = (320 + groups - 1) / groups;           // chunk slots per sequence
     want = std::max<long>(1, std::min(want, (tiles + 3) / 4));
     tiles_per_chunk = ((tiles + want - 1) / want + 3) / 4 * 4;
   } else {
@@ -186,6 +186,7 @@ int ouro_verify_attn(const ouro_attn_desc* desc, void* hip_stream) {
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (desc->dtype == OURO_F32) return launch_attn_f32(*desc, scale, stream);
   AttnPlan p = plan_attn_bf16(*desc);
+  if (static_cast<long>(desc->B) * desc->Hkv * p.nch * p.nrb + 8L * p.nrb >= (1L << 31)) return OURO_E_BAD_SHAPE;   // grid size
   const size_t need = p.total();
   if (need > 0) {
     if (!desc->workspace) return OURO_E_NULLPTR;

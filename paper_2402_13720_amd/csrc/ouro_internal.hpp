@@ -39,6 +39,23 @@ int device_once(DeviceOnce& s, F&& init) {
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Division by a divisor the host knows: floor(n / d) = (mulhi(n, mul) + n) >> shift for every 0 <= n < 2^31 (the
+// multiply-and-shift form of division by an invariant integer; shift = ceil(log2 d)).  A kernel that decodes its
+// workgroup id into (sequence, head, chunk, row block) pays two instructions per division instead of the ~25 of the
+// generic expansion, all of which sat in front of its first memory access.
+struct FastDiv {
+  unsigned mul, shift;
+};
+inline FastDiv make_fastdiv(unsigned d) {
+  unsigned l = 0;
+  while ((1u << l) < d) ++l;
+  const unsigned long long m = ((1ull << 32) * ((1ull << l) - d)) / d + 1;
+  return FastDiv{static_cast<unsigned>(m), l};
+}
+__device__ __forceinline__ int fdiv(int n, FastDiv f) {
+  return static_cast<int>((__umulhi(static_cast<unsigned>(n), f.mul) + static_cast<unsigned>(n)) >> f.shift);
+}
+
 // ---- attention ------------------------------------------------------------------------
 // Launch plan of the bf16 split-KV kernel, derived on the host from shapes only.
 struct AttnPlan {
