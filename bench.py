@@ -293,9 +293,11 @@ def load_traffic(workload_key):
         return None
 
 
-def attn_kernel_name(cfg):
+def attn_kernel_name(cfg, plan=None):
     if cfg.dtype != "bf16":
         return "attn_f32_kernel"
+    if plan is not None:
+        return "attn_bf16_kernel" if plan["row_blocks_per_workgroup"] == 1 else "attn_bf16_rows_kernel"
     return "attn_bf16_kernel" if cfg.T * (cfg.Hq // cfg.Hkv) <= 64 else "attn_bf16_rows_kernel"
 
 
@@ -317,7 +319,7 @@ def kernel_roofline(kind, cfg, kernel_us, call_us, bytes_, flops, traffic, peaks
     else:
         bound, achieved, peak, unit = "hbm", gbs, HBM_PEAK_GBS, "GB/s"
         measured = peaks.get("hbm_stream_read_GBs") if peaks else None
-    r = {"kernel": "%s (main kernel of %s)" % (attn_kernel_name(cfg) if kind == "attn" else lmhead_kernel_name(cfg),
+    r = {"kernel": "%s (main kernel of %s)" % (attn_kernel_name(cfg, (extra or {}).get("launch")) if kind == "attn" else lmhead_kernel_name(cfg),
                                                "ouro_verify_attn" if kind == "attn" else "ouro_lmhead_argmax"),
          "bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
          "traffic": traffic, "kernel_us": kernel_us, "whole_call_us": call_us,
@@ -517,6 +519,7 @@ def run_config(cfg_id, args, ob, W, torch, hip, peaks, headline):
                              {**samples, "kernel_us_std": float(kern_i[:, 0].std()),
                               "kernel_us_in_timed_region": {"mean": float(kern_t[:, 0].mean()), "n": int(len(kern_t))},
                               "combine_and_gaps_us": t_attn - k_attn,
+                              "launch": ob.ouro_verify_attn_plan(q, k_blk, max_seqlen),
                               "whole_call_is": "main kernel + the launch that merges the chunk partials (when a sequence spans several chunks)"})
     r_lm = kernel_roofline("lmhead", cfg, k_lm, t_lm, lmhead_algorithmic_bytes(cfg), lmhead_flops(cfg),
                            traffic.get("lmhead_bytes"), peaks,

@@ -138,6 +138,12 @@ enum { OURO_KV_ROW_MAJOR = 0, OURO_KV_HEAD_MAJOR = 1 };
  * not read).  Returns 0 if the descriptor is invalid or no workspace is needed. */
 OURO_API size_t ouro_verify_attn_workspace(const ouro_attn_desc* desc);
 OURO_API int ouro_verify_attn(const ouro_attn_desc* desc, void* hip_stream);
+/* Host-only: the launch shape the call will use for this descriptor (data pointers are not read), for logs, benchmarks
+ * and tuning: plan[0] = 32-row query blocks per workgroup (1: the kernel whose waves split the keys; 2, 4: the kernel
+ * whose waves split the rows and share staged K/V tiles; 0: the fp32 kernel), plan[1] = keys per workgroup,
+ * plan[2] = chunk slots per sequence (> 1: partial results are merged by a second launch), plan[3] = workgroups of the
+ * main kernel.  Returns OURO_OK or the descriptor's validation error. */
+OURO_API int ouro_verify_attn_plan(const ouro_attn_desc* desc, int32_t plan[4]);
 
 /* ------------------------------------------------------------------------------------ */
 /* LM head fused with the greedy pick (Eq. (2) under greedy decoding).                   */

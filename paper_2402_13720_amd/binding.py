@@ -112,6 +112,8 @@ def _load() -> C.CDLL:
     lib.ouro_verify_attn_workspace.argtypes = [C.POINTER(ouro_attn_desc)]
     lib.ouro_verify_attn.restype = C.c_int
     lib.ouro_verify_attn.argtypes = [C.POINTER(ouro_attn_desc), C.c_void_p]
+    lib.ouro_verify_attn_plan.restype = C.c_int
+    lib.ouro_verify_attn_plan.argtypes = [C.POINTER(ouro_attn_desc), C.POINTER(C.c_int32)]
     lib.ouro_lmhead_argmax_workspace.restype = C.c_size_t
     lib.ouro_lmhead_argmax_workspace.argtypes = [C.POINTER(ouro_lmhead_desc)]
     lib.ouro_lmhead_argmax.restype = C.c_int
@@ -235,6 +237,20 @@ def ouro_verify_attn_workspace(q, k_blk, max_seqlen: int, plan: int = 0) -> int:
     d.B, d.T, d.Hq, d.Hkv, d.D, d.max_seqlen = B, T, Hq, k_blk.shape[2], D, int(max_seqlen)
     d.plan_override = int(plan)
     return int(lib.ouro_verify_attn_workspace(C.byref(d)))
+
+
+def ouro_verify_attn_plan(q, k_blk, max_seqlen: int, plan: int = 0) -> dict:
+    """The launch shape a call with these shapes will use (host-only query)."""
+    B, T, Hq, D = q.shape
+    d = ouro_attn_desc()
+    d.struct_size = C.sizeof(ouro_attn_desc)
+    d.dtype = _dtype_code(q)
+    d.B, d.T, d.Hq, d.Hkv, d.D, d.max_seqlen = B, T, Hq, k_blk.shape[2], D, int(max_seqlen)
+    d.plan_override = int(plan)
+    out = (C.c_int32 * 4)()
+    _check(lib.ouro_verify_attn_plan(C.byref(d), out), "ouro_verify_attn_plan")
+    return {"row_blocks_per_workgroup": out[0], "keys_per_workgroup": out[1], "chunks_per_sequence": out[2],
+            "workgroups": out[3]}
 
 
 def ouro_verify_attn(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, max_seqlen: int,

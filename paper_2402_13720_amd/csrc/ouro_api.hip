@@ -21,32 +21,51 @@ int hip_failed(hipError_t e) {
 // (rows * 512 bytes per workgroup) small against the K/V bytes of a chunk (chunk * 512 bytes).
 //
 // Up to 64 query rows per (sequence, KV head): one 32-row block per workgroup, the four waves split the
-// keys; the default aims at about 1.25 workgroups per compute unit (two are resident at a time; measured
-// best where per-workgroup prologue/epilogue latency dominates).  More rows (long drafts, grouped-query
-// heads): the workgroup keeps 4 row blocks and its waves share the staged tiles; one workgroup per compute
-// unit, and the chunk count is the largest that still lets every workgroup be resident at once (no second
-// round of workgroups).  The descriptor's plan_override (row blocks per workgroup, keys per chunk) replaces the
-// heuristic in tests and tuning runs.
+// keys ("key-split" kernel); the default aims at about 1.25 workgroups per compute unit (two are resident at a
+// time; measured best where per-workgroup prologue/epilogue latency dominates).
+// More rows (long drafts, grouped-query heads), two ways, chosen by a cost estimate fitted to measurements:
+//  * the "row-split" kernel: the workgroup keeps 4 row blocks and its waves share the staged tiles; one workgroup
+//    per compute unit, the chunk count the largest that still lets every workgroup be resident at once.  K/V crosses
+//    from L2 to a compute unit once per 128 rows, but a workgroup has only ~64 KB in flight and works through its
+//    stages at ~4.2 us each under load: about 12 + 4.2 * stages microseconds;
+//  * the key-split kernel with one workgroup per 32-row block: every row block stages the K/V window again, so K/V
+//    crosses L2 -> compute unit once per 32 rows (measured ~11 TB/s in aggregate), but two workgroups per compute
+//    unit keep twice the bytes in flight and hide each other's latencies: about 6 + 0.095 us per MB of (row blocks x
+//    K/V bytes).  It wins where the K/V of the launch is small (few KV heads, one sequence): e.g. 64 query / 8 KV
+//    heads x 64 block tokens over 4096 cached tokens, 29.5 us against 35.0 us.
+// The descriptor's plan_override (row blocks per workgroup, keys per chunk) replaces the estimate in tests and tuning.
 AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
   AttnPlan p{};
   const int G = d.Hq / d.Hkv;
   const int M = d.T * G;
-  p.rw = M <= 64 ? 1 : 4;                            // (2 is built as well; measured no faster than 1 at 64 rows)
+  const long maxn = static_cast<long>(d.max_seqlen) + d.T;
+  const long tiles = (maxn + 31) / 32;
+  const long stages = (tiles + 3) / 4;
+  const long pairs = std::max<long>(1, static_cast<long>(d.B) * d.Hkv);       // (sequence, KV head) pairs
+  // the row-split plan: workgroups, stages per workgroup
+  const long groups4 = pairs * ((M + 127) / 128);
+  const long want4 = std::max<long>(1, std::min(256 / groups4, stages));
+  const long stages_wg4 = (stages + want4 - 1) / want4;
+  p.rw = 1;
+  if (M > 64) {
+    const double kv_mb = 2.0 * static_cast<double>(maxn) * static_cast<double>(pairs) * 256.0 / 1.0e6;   // upper bound
+    const double rounds4 = static_cast<double>((groups4 + 255) / 256);
+    const double t_rows = 12.0 + 4.2 * static_cast<double>(stages_wg4) * rounds4;
+    const double t_keys = 6.0 + 0.095 * kv_mb * static_cast<double>((M + 31) / 32);
+    p.rw = t_keys < t_rows ? 1 : 4;                  // (2 is built as well; measured no faster than 1 at 64 rows)
+  }
   const int rw_forced = d.plan_override & 0xff;
   if (rw_forced == 1 || rw_forced == 2 || rw_forced == 4) p.rw = rw_forced;
   p.rows_wg = 32 * p.rw;
   p.nrb = (M + p.rows_wg - 1) / p.rows_wg;
-  const long maxn = static_cast<long>(d.max_seqlen) + d.T;
-  const long tiles = (maxn + 31) / 32;
-  const long groups = std::max<long>(1, static_cast<long>(d.B) * d.Hkv * p.nrb);
+  const long groups = pairs * p.nrb;
   long tiles_per_chunk;
   if (p.rw == 1) {
-    long want = (320 + groups - 1) / groups;           // chunk slots per sequence
+    long want = ((M <= 64 ? 320 : 256) + groups - 1) / groups;   // chunk slots per sequence
     want = std::max<long>(1, std::min(want, (tiles + 3) / 4));
     tiles_per_chunk = ((tiles + want - 1) / want + 3) / 4 * 4;
   } else {
     const long resident = 256;                         // workgroups the chip holds at once (one per compute unit)
-    const long stages = (tiles + 3) / 4;
     const long want = std::max<long>(1, std::min(resident / groups, stages));
     tiles_per_chunk = (stages + want - 1) / want * 4;
   }
@@ -176,6 +195,25 @@ extern "C" {
 size_t ouro_verify_attn_workspace(const ouro_attn_desc* desc) {
   if (validate_attn(desc, false) != OURO_OK || desc->dtype != OURO_BF16 || desc->B == 0) return 0;
   return plan_attn_bf16(*desc).total();
+}
+
+int ouro_verify_attn_plan(const ouro_attn_desc* desc, int32_t plan[4]) {
+  if (!plan) return OURO_E_NULLPTR;
+  const int st = validate_attn(desc, false);
+  if (st != OURO_OK) return st;
+  plan[0] = plan[1] = plan[2] = plan[3] = 0;
+  if (desc->dtype != OURO_BF16) {
+    plan[1] = desc->max_seqlen + desc->T;
+    plan[2] = 1;
+    plan[3] = desc->B * desc->Hq * desc->T;
+    return OURO_OK;
+  }
+  const AttnPlan p = plan_attn_bf16(*desc);
+  plan[0] = p.rw;
+  plan[1] = p.chunk;
+  plan[2] = p.nch;
+  plan[3] = static_cast<int32_t>((static_cast<long>(desc->B) * desc->Hkv * p.nch + 7) / 8 * 8 * p.nrb);
+  return OURO_OK;
 }
 
 int ouro_verify_attn(const ouro_attn_desc* desc, void* hip_stream) {

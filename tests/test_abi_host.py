@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported():
     assert {"ouro_verify_attn", "ouro_lmhead_argmax", "ouro_accept", "ouro_verify_attn_workspace",
             "ouro_lmhead_argmax_workspace", "ouro_lmhead_packed_w_bytes", "ouro_lmhead_pack_w", "ouro_kv_commit",
             "ouro_rope_block", "ouro_rmsnorm", "ouro_linear", "ouro_silu_mul", "ouro_fold_rmsnorm_gain",
-            "ouro_interleave_gate_up",
+            "ouro_interleave_gate_up", "ouro_verify_attn_plan",
             "ouro_validate_meta_host", "ouro_status_string", "ouro_last_hip_error", "ouro_version"} <= set(names)
     for n in names:
         assert hasattr(ob.lib, n), n
@@ -87,6 +87,28 @@ def test_attn_workspace_query():
     forced = ws(C.byref(_attn_desc(plan_override=ob.plan_override(4, 128))))
     assert forced == 32 * 17 * 128 * (2 + 128) * 4 + (256 - 32 * 17 * 128 * 2 * 4 % 256) % 256
     assert ws(C.byref(_attn_desc(plan_override=ob.plan_override(1, 4096)))) == 0   # one chunk covers the sequence
+
+
+def test_attn_launch_shape_query():
+    """The host-only plan query: which kernel, keys per workgroup, chunk slots, workgroups -- on the five workloads'
+    shapes and on shapes where the choice between the two bf16 kernels flips."""
+    f = ob.lib.ouro_verify_attn_plan
+    out = (C.c_int32 * 4)()
+    assert f(None, out) == -1 and f(C.byref(_attn_desc()), None) == -1
+    assert f(C.byref(_attn_desc(T=0)), out) == -2
+
+    def plan(**kw):
+        assert f(C.byref(_attn_desc(**kw)), out) == 0
+        return list(out)
+
+    assert plan() == [1, 512, 5, 320]                                               # 7B layer: key-split, 5 chunks x 64 groups
+    assert plan(T=128, Hq=40, Hkv=40, max_seqlen=4096) == [4, 768, 6, 240]          # 13B layer: row-split, one workgroup per CU
+    assert plan(T=64, Hq=64, Hkv=8, max_seqlen=4096) == [1, 2176, 2, 256]           # 70B GQA layer: little K/V, key-split wins
+    assert plan(B=16, T=32, max_seqlen=8192) == [1, 8320, 1, 512]                   # batched: one chunk (65 tiles x 4 waves) per sequence
+    assert plan(B=16, T=32, Hq=64, Hkv=8, max_seqlen=4096)[0] == 4                  # GQA batch: K/V too large to re-stage per row block
+    assert plan(T=128, Hq=40, Hkv=40, max_seqlen=8192)[0] == 4
+    assert plan(dtype=ob.OURO_F32, T=16, Hq=4, Hkv=4, D=64, max_seqlen=128) == [0, 144, 1, 64]
+    assert plan(plan_override=ob.plan_override(2, 256))[:3] == [2, 256, 9]
 
 
 def test_no_call_reads_the_process_environment(monkeypatch):
