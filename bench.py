@@ -56,6 +56,9 @@ def parse_args():
                          "report it as an extra 'layer' object; the headline value is unchanged")
     ap.add_argument("--lm-rows", default="", help="comma-separated row counts (e.g. 1024,2048,4096): also time the LM "
                     "head alone at these R on the workload's vocabulary x hidden (MFMA-bound regime); adds lmhead_large_R")
+    ap.add_argument("--attn-plan", default="", help="tuning: force the attention launch shape of the --config workload, "
+                    "as ROWBLOCKS,KEYS (row blocks per workgroup 1/2/4; keys per workgroup, multiple of 128; 0 = the "
+                    "library's choice)")
     ap.add_argument("--kv-layout", default="head", choices=["head", "row"],
                     help="KV-cache layout: [Hkv, rows, D] (every (sequence, KV head) stream contiguous; default) or "
                          "[rows, Hkv, D]")
@@ -342,6 +345,10 @@ def run_config(cfg_id, args, ob, W, torch, hip, peaks, headline):
     cfg = W.CONFIGS[cfg_id]
     seed = W.seed_for(cfg_id)
     dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    attn_plan = 0
+    if headline and args.attn_plan:
+        rb, keys = (int(x) for x in args.attn_plan.split(","))
+        attn_plan = ob.plan_override(rb, keys)
 
     inp = W.make_attention_inputs(cfg, seed, branch=args.branch)
     w = W.make_lmhead_weight(cfg, seed)
@@ -379,7 +386,8 @@ def run_config(cfg_id, args, ob, W, torch, hip, peaks, headline):
     out = torch.empty_like(q)
     hidden = out.view(cfg.R, cfg.hidden)
     arg = torch.empty(cfg.R, dtype=torch.int32, device=dev)
-    ws_attn = ob.alloc_workspace(ob.ouro_verify_attn_workspace(q, k_blk, max_seqlen), dev)
+    ws_attn = ob.alloc_workspace(max(ob.ouro_verify_attn_workspace(q, k_blk, max_seqlen, plan=attn_plan),
+                                     ob.ouro_verify_attn_workspace(q, k_blk, max_seqlen)), dev)
     ws_lm = ob.alloc_workspace(ob.ouro_lmhead_argmax_workspace(hidden, ws[0]), dev)
     acc_out = ob.alloc_accept_outputs(cfg.B, cfg.gamma, cfg.K, cfg.beta_p, dev)
 
@@ -407,7 +415,7 @@ def run_config(cfg_id, args, ob, W, torch, hip, peaks, headline):
     hs = stream.cuda_stream or None
     # descriptors are built once per rotated copy; a step is then three C-ABI calls
     d_attn = [ob.make_attn_desc(q, kcs[r], vcs[r], cu, k_blk, v_blk, meta, out, max_seqlen, None, ws_attn,
-                                head_major=head_major)
+                                head_major=head_major, plan=attn_plan)
               for r in range(nrot)]
     d_lm = [ob.make_lmhead_desc(hidden, ws[r], arg, None, ws_lm) for r in range(nrot)]
     d_acc = ob.make_accept_desc(tok, arg.view(cfg.B, cfg.T), meta, root, cfg.gamma, cfg.K, cfg.beta_p, acc_out)
@@ -519,7 +527,7 @@ def run_config(cfg_id, args, ob, W, torch, hip, peaks, headline):
                              {**samples, "kernel_us_std": float(kern_i[:, 0].std()),
                               "kernel_us_in_timed_region": {"mean": float(kern_t[:, 0].mean()), "n": int(len(kern_t))},
                               "combine_and_gaps_us": t_attn - k_attn,
-                              "launch": ob.ouro_verify_attn_plan(q, k_blk, max_seqlen),
+                              "launch": ob.ouro_verify_attn_plan(q, k_blk, max_seqlen, plan=attn_plan),
                               "whole_call_is": "main kernel + the launch that merges the chunk partials (when a sequence spans several chunks)"})
     r_lm = kernel_roofline("lmhead", cfg, k_lm, t_lm, lmhead_algorithmic_bytes(cfg), lmhead_flops(cfg),
                            traffic.get("lmhead_bytes"), peaks,

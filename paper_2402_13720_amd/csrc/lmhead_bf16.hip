@@ -13,7 +13,10 @@
 //     coalesced 16-byte buffer loads into registers, then into its private XOR-swizzled LDS
 //     region, and issues MT*NT v_mfma_f32_32x32x16_bf16 per 16-wide k step; every staging
 //     register is re-armed with its next load right after its LDS write (W two k-tiles
-//     ahead where the registers allow, the L2-resident hidden rows one);
+//     ahead where the registers allow, the L2-resident hidden rows one).  Within a k-tile the
+//     hidden rows are re-armed before W: loads complete in issue order, and the hidden tile
+//     is needed one k-tile from now, W two, so with W first the wait for the hidden tile
+//     would also wait for the W loads issued in front of it and empty the pipeline;
 //   * after the loop the 4 partial accumulator sets are summed through LDS (fixed order),
 //     and the arg-max epilogue reduces lane -> wave -> workgroup; one (value, index) pair
 //     per (slab, row) goes to the workspace, the logits never leave the chip;
@@ -192,19 +195,19 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
   const int last = first + 4 * max(nj - 1, 0);            // loads past the wave's share re-read this tile (harmless)
   const int kt_safe = min(last, nkt_all - 1);
 
-// One k-tile: staging registers (W set SET, hidden rows) -> this wave's LDS tiles, each register re-armed at once with
+// One k-tile: staging registers (hidden rows, then W set SET) -> this wave's LDS tiles, each register re-armed at once with
 // its next load (W: KT_W, the tile kWSets steps ahead; hidden: KT_H, the next tile), then the MFMAs.  Loads and stores
 // are unconditional so that the compiler's counted waits stay exact; only the MFMAs of a step past the end are skipped.
 #define OURO_LM_KTILE(SET, KT_W, KT_H, VALID)                                                         \
   {                                                                                                   \
-    _Pragma("unroll") for (int p = 0; p < MT * 4; ++p) {                                              \
-      *reinterpret_cast<u32x4*>(wl + OURO_LM_LDS_SLOT(p)) = wreg[SET][p];                             \
-      wreg[SET][p] = OURO_LM_WLOAD(p, KT_W);                                                          \
-      __builtin_amdgcn_sched_barrier(0);                                                              \
-    }                                                                                                 \
     _Pragma("unroll") for (int p = 0; p < NT * 4; ++p) {                                              \
       *reinterpret_cast<u32x4*>(hl + OURO_LM_LDS_SLOT(p)) = hreg[p];                                  \
       hreg[p] = __builtin_amdgcn_raw_buffer_load_b128(hbuf, hoff[p], (KT_H) * 128, 0);                \
+      __builtin_amdgcn_sched_barrier(0);                                                              \
+    }                                                                                                 \
+    _Pragma("unroll") for (int p = 0; p < MT * 4; ++p) {                                              \
+      *reinterpret_cast<u32x4*>(wl + OURO_LM_LDS_SLOT(p)) = wreg[SET][p];                             \
+      wreg[SET][p] = OURO_LM_WLOAD(p, KT_W);                                                          \
       __builtin_amdgcn_sched_barrier(0);                                                              \
     }                                                                                                 \
     wave_lds_fence();                                                                                 \
@@ -231,8 +234,8 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(LmArgs a) {
 
   if (nj > 0) {
     OURO_LM_LOAD_W(0, first)
-    if (kWSets == 2) { OURO_LM_LOAD_W(kWSets - 1, min(first + 4, kt_safe)) }
     OURO_LM_LOAD_H(first)
+    if (kWSets == 2) { OURO_LM_LOAD_W(kWSets - 1, min(first + 4, kt_safe)) }
     if (kWSets == 2) {
       for (int j = 0; j < nj; j += 2) {
         const int t0 = first + 4 * j;
