@@ -57,8 +57,8 @@ def parse_args():
     ap.add_argument("--lm-rows", default="", help="comma-separated row counts (e.g. 1024,2048,4096): also time the LM "
                     "head alone at these R on the workload's vocabulary x hidden (MFMA-bound regime); adds lmhead_large_R")
     ap.add_argument("--attn-plan", default="", help="tuning: force the attention launch shape of the --config workload, "
-                    "as ROWBLOCKS,KEYS (row blocks per workgroup 1/2/4; keys per workgroup, multiple of 128; 0 = the "
-                    "library's choice)")
+                    "as ROWBLOCKS,KEYS (row blocks per workgroup 1/2/4, 132 = 4 with the four-wave kernel; keys per "
+                    "workgroup, multiple of 128; 0 = the library's choice)")
     ap.add_argument("--kv-layout", default="head", choices=["head", "row"],
                     help="KV-cache layout: [Hkv, rows, D] (every (sequence, KV head) stream contiguous; default) or "
                          "[rows, Hkv, D]")
@@ -300,8 +300,10 @@ def attn_kernel_name(cfg, plan=None):
     if cfg.dtype != "bf16":
         return "attn_f32_kernel"
     if plan is not None:
-        return "attn_bf16_kernel" if plan["row_blocks_per_workgroup"] == 1 else "attn_bf16_rows_kernel"
-    return "attn_bf16_kernel" if cfg.T * (cfg.Hq // cfg.Hkv) <= 64 else "attn_bf16_rows_kernel"
+        if plan["row_blocks_per_workgroup"] == 1:
+            return "attn_bf16_kernel"
+        return "attn_bf16_rows8_kernel" if plan["waves_per_workgroup"] == 8 else "attn_bf16_rows_kernel"
+    return "attn_bf16_kernel" if cfg.T * (cfg.Hq // cfg.Hkv) <= 64 else "attn_bf16_rows8_kernel"
 
 
 def lmhead_kernel_name(cfg):
@@ -348,7 +350,7 @@ def run_config(cfg_id, args, ob, W, torch, hip, peaks, headline):
     attn_plan = 0
     if headline and args.attn_plan:
         rb, keys = (int(x) for x in args.attn_plan.split(","))
-        attn_plan = ob.plan_override(rb, keys)
+        attn_plan = ob.plan_override(rb & 0x7f, keys, bool(rb & 0x80))
 
     inp = W.make_attention_inputs(cfg, seed, branch=args.branch)
     w = W.make_lmhead_weight(cfg, seed)

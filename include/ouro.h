@@ -43,7 +43,7 @@
 extern "C" {
 #endif
 
-#define OURO_VERSION 210 /* major*10000 + minor*100 + patch */
+#define OURO_VERSION 211 /* major*10000 + minor*100 + patch */
 
 /* Exported from libouro.so (everything else in the library has hidden visibility). */
 #define OURO_API __attribute__((visibility("default")))
@@ -126,8 +126,9 @@ typedef struct {
   int32_t kv_layout;           /* OURO_KV_ROW_MAJOR: caches are [rows, Hkv, D].  OURO_KV_HEAD_MAJOR: [Hkv, cache_rows, D],
                                   every (sequence, KV head) stream contiguous in memory, which HBM delivers fastest */
   int32_t plan_override;       /* 0: the library chooses the launch shape.  Tests and tuning runs may force it (bf16
-                                  only): bits 0..7 = 32-row query blocks per workgroup (1, 2 or 4; 0 = library's
-                                  choice), bits 8..31 = keys per workgroup / 128 (0 = library's choice).  The same
+                                  only): bits 0..6 = 32-row query blocks per workgroup (1, 2 or 4; 0 = library's
+                                  choice), bit 7 = with 4 row blocks, the four-wave kernel instead of the eight-wave
+                                  one, bits 8..31 = keys per workgroup / 128 (0 = library's choice).  The same
                                   value must be given to the workspace query */
   int64_t cache_rows;          /* OURO_KV_HEAD_MAJOR: rows per KV head of the cache allocation (>= cu_seqlens[B]) */
 } ouro_attn_desc;
@@ -142,8 +143,9 @@ OURO_API int ouro_verify_attn(const ouro_attn_desc* desc, void* hip_stream);
  * and tuning: plan[0] = 32-row query blocks per workgroup (1: the kernel whose waves split the keys; 2, 4: the kernel
  * whose waves split the rows and share staged K/V tiles; 0: the fp32 kernel), plan[1] = keys per workgroup,
  * plan[2] = chunk slots per sequence (> 1: partial results are merged by a second launch), plan[3] = workgroups of the
- * main kernel.  Returns OURO_OK or the descriptor's validation error. */
-OURO_API int ouro_verify_attn_plan(const ouro_attn_desc* desc, int32_t plan[4]);
+ * main kernel, plan[4] = waves per workgroup (4; 8 for the four-row-block kernel in its eight-wave form; 0: the fp32
+ * kernel).  Returns OURO_OK or the descriptor's validation error. */
+OURO_API int ouro_verify_attn_plan(const ouro_attn_desc* desc, int32_t plan[5]);
 
 /* ------------------------------------------------------------------------------------ */
 /* LM head fused with the greedy pick (Eq. (2) under greedy decoding).                   */

@@ -196,11 +196,12 @@ def alloc_workspace(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
-def plan_override(row_blocks: int = 0, chunk_keys: int = 0) -> int:
+def plan_override(row_blocks: int = 0, chunk_keys: int = 0, four_waves: bool = False) -> int:
     """The descriptor field that forces the bf16 attention's launch shape in tests and tuning runs: row blocks per
-    workgroup (1, 2, 4; 0 = the library's choice) and keys per workgroup (a multiple of 128; 0 = the library's choice)."""
+    workgroup (1, 2, 4; 0 = the library's choice), keys per workgroup (a multiple of 128; 0 = the library's choice),
+    and, for 4 row blocks, the four-wave kernel instead of the eight-wave one."""
     assert row_blocks in (0, 1, 2, 4) and chunk_keys % 128 == 0
-    return row_blocks | ((chunk_keys // 128) << 8)
+    return row_blocks | (0x80 if four_waves else 0) | ((chunk_keys // 128) << 8)
 
 
 def make_attn_desc(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, out, max_seqlen,
@@ -247,10 +248,10 @@ def ouro_verify_attn_plan(q, k_blk, max_seqlen: int, plan: int = 0) -> dict:
     d.dtype = _dtype_code(q)
     d.B, d.T, d.Hq, d.Hkv, d.D, d.max_seqlen = B, T, Hq, k_blk.shape[2], D, int(max_seqlen)
     d.plan_override = int(plan)
-    out = (C.c_int32 * 4)()
+    out = (C.c_int32 * 5)()
     _check(lib.ouro_verify_attn_plan(C.byref(d), out), "ouro_verify_attn_plan")
     return {"row_blocks_per_workgroup": out[0], "keys_per_workgroup": out[1], "chunks_per_sequence": out[2],
-            "workgroups": out[3]}
+            "workgroups": out[3], "waves_per_workgroup": out[4]}
 
 
 def ouro_verify_attn(q, k_cache, v_cache, cu_seqlens, k_blk, v_blk, meta, max_seqlen: int,

@@ -773,6 +773,220 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
   for (int p = tid; p < kRowsWg * 2; p += 256) a.part_ml[pbase * 2 + p] = stage_ml[p];
 }
 
+// ---- row-split variant with eight waves: 128 query rows per workgroup, two waves per SIMD ---------------------------
+// The four-wave kernel above has one wave per SIMD, and a single wave runs its scores -> softmax -> P.V chain one link
+// at a time: while it is on the vector ALU the matrix pipe idles, and the other way round (a stage of 128 keys costs it
+// about 4 x (512 MFMA + 900 vector-ALU + LDS) cycles).  Here the workgroup has eight waves under 256 registers each:
+// wave (rw = wave % 4, kw = wave / 4) runs row block rw over tiles kw and kw + 2 of every four-tile stage, so each
+// SIMD holds the two key groups of one row block and one wave's MFMAs overlap the other's softmax with no hand-made
+// interleave.  To fit the registers the tile step is the key-split kernel's (Q tile in LDS, one rolling fragment
+// set) and a wave stages half a tile: waves 0..3 the K part of tile `wave` of the next stage, waves 4..7 the V part
+// of tile `wave - 4` (transposed), each re-armed at once with the stage after.  LDS: four Q tiles + two stage buffers =
+// 160 KB; the class table of the mask lives in the second stage buffer until the first stage is written over it.
+constexpr int kRows8Lds = 4 * kQBytes + 2 * 4 * kWaveLds;
+
+__global__ __launch_bounds__(512, 1) void attn_bf16_rows8_kernel(AttnArgs a) {
+  constexpr int RW = 4, KW = 2, kRowsWg = 32 * RW;
+  constexpr int kStageBytes4 = 4 * kWaveLds;      // one stage: 4 x (K tile, V^T tile)
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int rw = wave & 3, kw = wave >> 2;
+  const int st_tile = wave & 3;                   // staging role: part (K or V) of this tile of a stage
+  const bool st_v = wave >= 4;
+
+  // ---- workgroup id -> (x = (sequence, KV head, chunk), row block); same x => same id modulo 8 ----
+  const int per = 8 * a.nrb;
+  const int blk = fdiv(blockIdx.x, a.div_per), rem = blockIdx.x - blk * per;
+  const int rb = rem >> 3;
+  const int x = blk * 8 + (rem & 7);
+  if (x >= a.n_x) return;
+  const int nbg = a.nbg;
+  const int chunk = fdiv(x, a.div_nbg);           // chunk-major, as in the kernels above
+  const int bg = x - chunk * nbg;
+  const int b = fdiv(bg, a.div_hkv), g = bg - b * a.Hkv;
+  const int T = a.T;
+  const int col = lane & 31, half = lane >> 5;
+  const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
+  const int row0 = rb * kRowsWg + 32 * rw;        // first row of this wave's block (may lie past M: duplicates)
+
+  // ---- prologue loads that need nothing but the workgroup's indices (see the key-split kernel) ----
+  int vzero;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(vzero));
+  const long cu0_v = a.cu[b + vzero];
+  const int cu1_v = *reinterpret_cast<const int*>(a.cu + b + 1 + vzero);    // low word: a length fits 32 bits
+  int len_v = 0;
+  if (a.len) len_v = a.len[b + vzero];
+  const short my_kpid = tid < T ? a.meta[static_cast<size_t>(b) * T + tid].phrase_id : static_cast<short>(0);
+  u32x4 qreg[kRowsWg * 16 / 512];                 // the four Q tiles: 16 lanes per 256-byte row, 4 pieces per thread
+#pragma unroll
+  for (int u = 0; u < kRowsWg * 16 / 512; ++u) {
+    const int p = tid + 512 * u;
+    const int row = p >> 4, c = p & 15;
+    const int rr = min(rb * kRowsWg + row, M - 1); // rows past M are computed on a duplicate and never stored
+    const int t = fdiv(rr, a.div_g), hh = rr - t * G;
+    qreg[u] = *reinterpret_cast<const u32x4*>(a.q + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD + 8 * c);
+  }
+  const int rq = min(row0 + col, M - 1);          // this lane's query row (its column of S^T) and that row's metadata
+  const int tq = fdiv(rq, a.div_g);
+  const ouro_tok_meta mq = a.meta[static_cast<size_t>(b) * T + tq];
+  __builtin_amdgcn_sched_barrier(0);              // keep the loads above ahead of the wait for the length below
+  int c0lo = static_cast<int>(cu0_v), c0hi = static_cast<int>(cu0_v >> 32), c1lo = cu1_v;
+  asm volatile("" : "+v"(c0lo), "+v"(c0hi), "+v"(c1lo), "+v"(len_v));   // first use of the loaded values: here, not earlier
+  const long cu0 = (static_cast<long>(__builtin_amdgcn_readfirstlane(c0hi)) << 32) |
+                   static_cast<unsigned>(__builtin_amdgcn_readfirstlane(c0lo));
+  const int L = min(__builtin_amdgcn_readfirstlane(a.len ? len_v : c1lo - c0lo), a.max_seqlen);
+
+  const int n = L + T;
+  const int k_begin = chunk * a.chunk;
+  if (k_begin >= n) return;                       // chunk slot beyond this sequence (uniform for the workgroup)
+  const int k_end = min(n, k_begin + a.chunk);
+  const bool whole = n <= a.chunk;                // the sequence has one chunk: this workgroup sees every key
+  const int fast_end = min(L, k_end);             // tiles that end by here lie wholly in the cache part of the window
+
+  unsigned char* ql = lds + rw * kQBytes;         // this wave's Q tile
+  unsigned char* stage0 = lds + 4 * kQBytes;      // two stage buffers
+  u32x4* cls = reinterpret_cast<u32x4*>(stage0 + kStageBytes4);   // (in the second one, which the prologue leaves alone)
+  if (tid < 128) cls[tid] = u32x4{0u, 0u, 0u, 0u};
+
+  const int kq = lane >> 4, c16 = lane & 15;      // staging roles of the lanes, as in the kernels above
+  const int row_base = 16 * (kq >> 1) + 4 * (kq & 1);
+  u32x4 sr[8];
+  const unsigned kstride = a.kv_row_stride;        // elements between consecutive cache rows of one head
+  const unsigned loff0 = static_cast<unsigned>(kq) * kstride + 8 * c16;
+  const __bf16* const s_cache = st_v ? a.v_cache : a.k_cache;
+  const __bf16* const s_blk = st_v ? a.v_blk : a.k_blk;
+  // this wave's half tile: registers -> the stage buffer at NB, re-armed with the tile at key NEXT
+#define OURO_ATTN_STAGE_HALF(NB, NEXT)                                                                             \
+  {                                                                                                                \
+    unsigned char* nk_ = (NB) + st_tile * kWaveLds;                                                                \
+    if (st_v) { OURO_ATTN_STORE_V(nk_ + kKBytes, sr, 0, 8) } else { OURO_ATTN_STORE_K(nk_, sr) }                   \
+    OURO_ATTN_ISSUE_HALF(NEXT, sr, s_cache, s_blk)                                                                 \
+  }
+
+  OURO_ATTN_ISSUE_HALF(k_begin + 32 * st_tile, sr, s_cache, s_blk)
+  __builtin_amdgcn_sched_barrier(0);
+  f32x16 o[4];
+  float m_run = -INFINITY, l_run = 0.f;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)                  // (cleared here: nothing that can wait stands before the first loads)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+  __syncthreads();                                // the class table is cleared
+  if (tid < T) atomicOr(reinterpret_cast<unsigned*>(cls + (my_kpid & 127)) + (tid >> 5), 1u << (tid & 31));
+#pragma unroll
+  for (int u = 0; u < kRowsWg * 16 / 512; ++u) {
+    const int p = tid + 512 * u;
+    *reinterpret_cast<u32x4*>(lds + (p >> 9) * kQBytes + k_slot((p >> 4) & 31, p & 15) * 16) = qreg[u];
+  }
+  OURO_ATTN_STAGE_HALF(stage0, k_begin + 128 + 32 * st_tile)   // stage 0 -> buffer 0, stage 1 in flight
+  __syncthreads();                                // Q tiles, class table and stage 0 complete
+  u32x4 vis = {0u, 0u, 0u, 0u};
+  if (k_end > L) vis = row_visibility(cls, mq.phrase_id, mq.branch_off, tq);   // the window reaches block keys
+  __syncthreads();                                // every lane has its set: the second buffer may be written
+
+  int cur = 0;
+  for (int sb = k_begin; sb < k_end; sb += 128, cur ^= 1) {
+    const unsigned char* kv = stage0 + cur * kStageBytes4;      // the stage being computed
+    unsigned char* nb = stage0 + (cur ^ 1) * kStageBytes4;      // the stage being filled
+    OURO_ATTN_STAGE_HALF(nb, sb + 256 + 32 * st_tile)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int tile = sb + 32 * (kw + KW * u);
+      if (tile < k_end) {
+        const unsigned char* kl = kv + (kw + KW * u) * kWaveLds;
+        OURO_ATTN_COMPUTE_TILE(tile, kl, kl + kKBytes, ql)
+      }
+    }
+    __syncthreads();                              // stage sb fully read, stage sb+128 fully written
+  }
+#undef OURO_ATTN_STAGE_HALF
+
+  // ---- merge the two key groups of every row block through LDS ----
+  f32x4* slot_o = reinterpret_cast<f32x4*>(lds);
+  float* slot_ml = reinterpret_cast<float*>(lds + RW * kStateBytes);
+  if (kw == 1) {
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int ig = 0; ig < 4; ++ig) {
+        f32x4 v4 = {o[dt][4 * ig + 0], o[dt][4 * ig + 1], o[dt][4 * ig + 2], o[dt][4 * ig + 3]};
+        slot_o[(rw * 16 + dt * 4 + ig) * 64 + lane] = v4;
+      }
+    slot_ml[(rw * 64 + lane) * 2 + 0] = m_run;
+    slot_ml[(rw * 64 + lane) * 2 + 1] = l_run;
+  }
+  __syncthreads();
+  if (kw == 0) {
+    const float m_b = slot_ml[(rw * 64 + lane) * 2 + 0];
+    const float l_b = slot_ml[(rw * 64 + lane) * 2 + 1];
+    const float m_new = fmaxf(m_run, m_b);
+    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+    const float fa = exp2f(m_run - m_safe), fb = exp2f(m_b - m_safe);
+    m_run = m_new;
+    l_run = l_run * fa + l_b * fb;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int ig = 0; ig < 4; ++ig) {
+        const f32x4 ob = slot_o[(rw * 16 + dt * 4 + ig) * 64 + lane];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[dt][4 * ig + e] = o[dt][4 * ig + e] * fa + ob[e] * fb;
+      }
+  }
+  __syncthreads();
+
+  // ---- the kw = 0 wave of every row block stages its state row-major: stage_o[row][132], stage_ml[row][2] ----
+  float* stage_o = reinterpret_cast<float*>(lds);
+  float* stage_ml = stage_o + kRowsWg * kStageRow;
+  if (kw == 0) {
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const int lrow = 32 * rw + col;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int ig = 0; ig < 4; ++ig) {
+        f32x4 v4 = {o[dt][4 * ig + 0], o[dt][4 * ig + 1], o[dt][4 * ig + 2], o[dt][4 * ig + 3]};
+        *reinterpret_cast<f32x4*>(stage_o + lrow * kStageRow + 32 * dt + 8 * ig + 4 * half) = v4;
+      }
+    if (half == 0) {
+      stage_ml[lrow * 2 + 0] = m_run;
+      stage_ml[lrow * 2 + 1] = l_tot;
+    }
+  }
+  __syncthreads();
+
+  const int group = bg * a.nrb + rb;
+  if (whole) {
+    // ---- the workgroup saw every key of the sequence: normalise and write bf16, 16 B per thread ----
+    for (int p = tid; p < kRowsWg * 16; p += 512) {
+      const int row = p >> 4, c = p & 15;
+      const int r = rb * kRowsWg + row;
+      if (r >= M) continue;
+      const float inv = 1.0f / stage_ml[row * 2 + 1];
+      const f32x4 x0 = *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 8 * c);
+      const f32x4 x1 = *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 8 * c + 4);
+      f32x8 v8 = {x0[0] * inv, x0[1] * inv, x0[2] * inv, x0[3] * inv, x1[0] * inv, x1[1] * inv, x1[2] * inv, x1[3] * inv};
+      const int t = fdiv(r, a.div_g), hh = r - t * G;
+      __bf16* op = a.out + ((static_cast<size_t>(b) * T + t) * Hq + g * G + hh) * kD;
+      *reinterpret_cast<bf16x8*>(op + 8 * c) = __builtin_convertvector(v8, bf16x8);
+      if (a.lse && c == 0)
+        a.lse[(static_cast<size_t>(b) * Hq + g * G + hh) * T + t] =
+            (stage_ml[row * 2] + log2f(stage_ml[row * 2 + 1])) * kLn2;
+    }
+    return;
+  }
+
+  // ---- several chunks: leave a partial for the combine kernel (plain coalesced stores, no waiting) ----
+  const size_t pbase = (static_cast<size_t>(group) * a.nch + chunk) * kRowsWg;
+  for (int p = tid; p < kRowsWg * 32; p += 512) {
+    const int row = p >> 5, c = p & 31;
+    *reinterpret_cast<f32x4*>(a.part_o + (pbase + row) * kD + 4 * c) =
+        *reinterpret_cast<const f32x4*>(stage_o + row * kStageRow + 4 * c);
+  }
+  for (int p = tid; p < kRowsWg * 2; p += 512) a.part_ml[pbase * 2 + p] = stage_ml[p];
+}
+
 // Merge the chunk partials of every query row of the sequences that span several chunks:
 // out = sum_c 2^(m_c - m*) O_c / sum_c 2^(m_c - m*) l_c, chunks folded in ascending order
 // (deterministic).  One thread per (row, 8 head-dim elements); loads are issued four chunks
@@ -891,11 +1105,16 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
     if (e == hipSuccess)
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_rows_kernel<4>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds_bytes<4>());
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_rows8_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kRows8Lds);
     return e == hipSuccess ? static_cast<int>(OURO_OK) : hip_failed(e);
   });
   if (ready != OURO_OK) return ready;
   if (d.ev_start && hipEventRecord(static_cast<hipEvent_t>(d.ev_start), stream) != hipSuccess) return hip_failed(hipGetLastError());
-  if (plan.rw == 4)
+  if (plan.rw == 4 && plan.waves == 8)
+    hipLaunchKernelGGL(attn_bf16_rows8_kernel, dim3(grid), dim3(512), kRows8Lds, stream, a);
+  else if (plan.rw == 4)
     hipLaunchKernelGGL(attn_bf16_rows_kernel<4>, dim3(grid), dim3(256), rows_lds_bytes<4>(), stream, a);
   else if (plan.rw == 2)
     hipLaunchKernelGGL(attn_bf16_rows_kernel<2>, dim3(grid), dim3(256), rows_lds_bytes<2>(), stream, a);

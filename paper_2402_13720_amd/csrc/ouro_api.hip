@@ -54,8 +54,11 @@ AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
     const double t_keys = 6.0 + 0.095 * kv_mb * static_cast<double>((M + 31) / 32);
     p.rw = t_keys < t_rows ? 1 : 4;                  // (2 is built as well; measured no faster than 1 at 64 rows)
   }
-  const int rw_forced = d.plan_override & 0xff;
+  const int rw_forced = d.plan_override & 0x7f;
   if (rw_forced == 1 || rw_forced == 2 || rw_forced == 4) p.rw = rw_forced;
+  // four row blocks: the eight-wave kernel (two key groups per row block, two waves per SIMD) unless the four-wave one
+  // (one wave per SIMD, pipelined by hand; kept for comparison) is asked for
+  p.waves = (p.rw == 4 && !(d.plan_override & 0x80)) ? 8 : 4;
   p.rows_wg = 32 * p.rw;
   p.nrb = (M + p.rows_wg - 1) / p.rows_wg;
   const long groups = pairs * p.nrb;
@@ -197,11 +200,11 @@ size_t ouro_verify_attn_workspace(const ouro_attn_desc* desc) {
   return plan_attn_bf16(*desc).total();
 }
 
-int ouro_verify_attn_plan(const ouro_attn_desc* desc, int32_t plan[4]) {
+int ouro_verify_attn_plan(const ouro_attn_desc* desc, int32_t plan[5]) {
   if (!plan) return OURO_E_NULLPTR;
   const int st = validate_attn(desc, false);
   if (st != OURO_OK) return st;
-  plan[0] = plan[1] = plan[2] = plan[3] = 0;
+  plan[0] = plan[1] = plan[2] = plan[3] = plan[4] = 0;
   if (desc->dtype != OURO_BF16) {
     plan[1] = desc->max_seqlen + desc->T;
     plan[2] = 1;
@@ -210,6 +213,7 @@ int ouro_verify_attn_plan(const ouro_attn_desc* desc, int32_t plan[4]) {
   }
   const AttnPlan p = plan_attn_bf16(*desc);
   plan[0] = p.rw;
+  plan[4] = p.waves;
   plan[1] = p.chunk;
   plan[2] = p.nch;
   plan[3] = static_cast<int32_t>((static_cast<long>(desc->B) * desc->Hkv * p.nch + 7) / 8 * 8 * p.nrb);

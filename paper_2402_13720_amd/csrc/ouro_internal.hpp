@@ -60,6 +60,7 @@ __device__ __forceinline__ int fdiv(int n, FastDiv f) {
 // Launch plan of the bf16 split-KV kernel, derived on the host from shapes only.
 struct AttnPlan {
   int rw;          // 32-row query blocks per workgroup: 1 (waves split the keys), 2 or 4 (waves split the rows)
+  int waves;       // waves per workgroup: 4, or 8 (with rw = 4: two key groups per row block, two waves per SIMD)
   int rows_wg;     // query rows per workgroup: 32 * rw
   int nrb;         // row blocks per (sequence, KV head): ceil(T * G / rows_wg)
   int chunk;       // keys per workgroup (multiple of 128: four 32-key tiles, one per wave, at a time)

@@ -30,13 +30,14 @@ def upload_attention(cfg, inp, head_major=False):
 
 
 def run_attention(cfg, inp, want_lse=True, max_seqlen=None, head_major=False, rw=0, chunk=0):
-    """rw, chunk: force the bf16 kernel variant (row blocks per workgroup) and the keys per workgroup (0: heuristic)."""
+    """rw, chunk: force the bf16 kernel variant (row blocks per workgroup; 4 + 0x80: 4 row blocks with the four-wave
+    kernel) and the keys per workgroup (0: heuristic)."""
     from paper_2402_13720_amd import binding as ob
     t = upload_attention(cfg, inp, head_major)
     lse = torch.full((cfg.B, cfg.Hq, cfg.T), float("nan"), dtype=torch.float32, device=DEV) if want_lse else None
     out = ob.ouro_verify_attn(t["q"], t["k_cache"], t["v_cache"], t["cu_seqlens"], t["k_blk"], t["v_blk"], t["meta"],
                               max_seqlen=t["max_seqlen"] if max_seqlen is None else max_seqlen, lse=lse,
-                              head_major=head_major, plan=ob.plan_override(rw, chunk))
+                              head_major=head_major, plan=ob.plan_override(rw & 0x7f, chunk, bool(rw & 0x80)))
     torch.cuda.synchronize()
     return out, lse, t
 

@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_version_and_status_strings():
-    assert ob.lib.ouro_version() == 210
+    assert ob.lib.ouro_version() == 211
     assert ob.lib.ouro_status_string(0) == b"ok"
     for code in range(-9, 0):
         assert ob.lib.ouro_status_string(code) not in (b"ok", b"unknown status")
@@ -93,7 +93,7 @@ def test_attn_launch_shape_query():
     """The host-only plan query: which kernel, keys per workgroup, chunk slots, workgroups -- on the five workloads'
     shapes and on shapes where the choice between the two bf16 kernels flips."""
     f = ob.lib.ouro_verify_attn_plan
-    out = (C.c_int32 * 4)()
+    out = (C.c_int32 * 5)()
     assert f(None, out) == -1 and f(C.byref(_attn_desc()), None) == -1
     assert f(C.byref(_attn_desc(T=0)), out) == -2
 
@@ -101,14 +101,15 @@ def test_attn_launch_shape_query():
         assert f(C.byref(_attn_desc(**kw)), out) == 0
         return list(out)
 
-    assert plan() == [1, 512, 5, 320]                                               # 7B layer: key-split, 5 chunks x 64 groups
-    assert plan(T=128, Hq=40, Hkv=40, max_seqlen=4096) == [4, 768, 6, 240]          # 13B layer: row-split, one workgroup per CU
-    assert plan(T=64, Hq=64, Hkv=8, max_seqlen=4096) == [1, 2176, 2, 256]           # 70B GQA layer: little K/V, key-split wins
-    assert plan(B=16, T=32, max_seqlen=8192) == [1, 8320, 1, 512]                   # batched: one chunk (65 tiles x 4 waves) per sequence
+    assert plan() == [1, 512, 5, 320, 4]                                               # 7B layer: key-split, 5 chunks x 64 groups
+    assert plan(T=128, Hq=40, Hkv=40, max_seqlen=4096) == [4, 768, 6, 240, 8]       # 13B layer: row-split (8 waves), one workgroup per CU
+    assert plan(T=64, Hq=64, Hkv=8, max_seqlen=4096) == [1, 2176, 2, 256, 4]        # 70B GQA layer: little K/V, key-split wins
+    assert plan(B=16, T=32, max_seqlen=8192) == [1, 8320, 1, 512, 4]                # batched: one chunk (65 tiles x 4 waves) per sequence
     assert plan(B=16, T=32, Hq=64, Hkv=8, max_seqlen=4096)[0] == 4                  # GQA batch: K/V too large to re-stage per row block
     assert plan(T=128, Hq=40, Hkv=40, max_seqlen=8192)[0] == 4
-    assert plan(dtype=ob.OURO_F32, T=16, Hq=4, Hkv=4, D=64, max_seqlen=128) == [0, 144, 1, 64]
+    assert plan(dtype=ob.OURO_F32, T=16, Hq=4, Hkv=4, D=64, max_seqlen=128) == [0, 144, 1, 64, 0]
     assert plan(plan_override=ob.plan_override(2, 256))[:3] == [2, 256, 9]
+    assert plan(T=128, Hq=40, Hkv=40, max_seqlen=4096, plan_override=ob.plan_override(4, 0, four_waves=True)) == [4, 768, 6, 240, 4]
 
 
 def test_no_call_reads_the_process_environment(monkeypatch):

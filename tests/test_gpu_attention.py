@@ -66,7 +66,7 @@ def test_bf16_small_shapes(kw, branch):
 
 
 @pytest.mark.parametrize("head_major", [False, True])
-@pytest.mark.parametrize("rw", [1, 2, 4])
+@pytest.mark.parametrize("rw", [1, 2, 4, 4 + 0x80])
 @pytest.mark.parametrize("kw, chunk", [
     (dict(B=2, Hq=4, Hkv=2, L=(0, 300), gamma=10, K=5, beta_p=6), 0),         # 80 rows; one sequence is all block
     (dict(B=1, Hq=8, Hkv=1, L=517, gamma=16, K=8, beta_p=6), 128),            # GQA 8: 512 rows; 5 one-stage chunks
@@ -76,8 +76,9 @@ def test_bf16_small_shapes(kw, branch):
 ])
 def test_bf16_every_kernel_variant(kw, chunk, rw, head_major):
     """The launch heuristic picks the row blocks per workgroup (1: waves split the keys; 2, 4: waves split the
-    rows and share staged tiles) and the chunk length; force each combination so that all three kernels see
-    several stages, several chunks and a ragged tail, with the cache in either layout."""
+    rows and share staged tiles: 4 is the eight-wave kernel with two key groups per row block, 4 + 0x80 the
+    four-wave one) and the chunk length; force each combination so that every kernel sees several stages, several chunks and a ragged
+    tail, with the cache in either layout."""
     cfg = W.scaled(W.CONFIGS[2], **kw)
     _check(cfg, W.make_attention_inputs(cfg, 4321), head_major=head_major, rw=rw, chunk=chunk)
 
@@ -140,6 +141,7 @@ def test_full_size_configs_every_head_and_row(cfg_id, head_major):
 @pytest.mark.parametrize("cfg_id, kw, rw", [
     (2, dict(B=3, Hq=4, Hkv=2, L=(300, 1500)), 1),               # key-split kernel; the hint cuts chunk slots away
     (2, dict(B=2, Hq=16, Hkv=2, L=(300, 1500)), 4),              # row-split kernel
+    (2, dict(B=2, Hq=16, Hkv=2, L=(300, 1500)), 4 + 0x80),       # row-split kernel, four waves
     (1, dict(B=2, L=(100, 300)), 0),                             # fp32 kernel
 ])
 def test_length_beyond_the_hint_is_cut_to_the_hint(cfg_id, kw, rw):
@@ -217,7 +219,7 @@ def test_bf16_seeded_random_shapes(case):
     lo = int(rng.choice([0, 1, 31, 64, 200]))
     hi = lo + int(rng.choice([0, 1, 33, 250, 700]))
     cfg = W.scaled(W.CONFIGS[2], B=int(rng.integers(1, 5)), Hq=Hkv * G, Hkv=Hkv, L=(lo, hi), gamma=gamma, K=K, beta_p=bp)
-    rw = int(rng.choice([1, 2, 4]))
+    rw = int(rng.choice([1, 2, 4, 4 + 0x80]))
     chunk = int(rng.choice([0, 128, 256, 384]))
     inp = W.make_attention_inputs(cfg, 8000 + case, branch=str(rng.choice(["uniform", "last", "any"])))
     _check(cfg, inp, head_major=bool(rng.integers(0, 2)), rw=rw, chunk=chunk)
