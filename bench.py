@@ -48,6 +48,11 @@ def parse_args():
                     help="inside the timed region, record the per-call and per-kernel HIP events on every Nth step only "
                          "(each record is a packet on the stream and costs launch time); the kernel durations quoted "
                          "come from a separate block of instrumented steps after it")
+    ap.add_argument("--settle-steps", type=int, default=64,
+                    help="untimed steps of the workload run as the last part of the set-up, before the W warm-up steps: "
+                         "after the host-side set-up the chip needs some tens of milliseconds of load to reach the "
+                         "clocks it then sustains (measured: 20 timed steps behind 5 warm-up steps read 4-5 %% slower "
+                         "than behind 60)")
     ap.add_argument("--instrumented-steps", type=int, default=64,
                     help="untimed steps after the timed region with events around every call and main kernel (>= 50)")
     ap.add_argument("--with-layer", action="store_true",
@@ -448,7 +453,10 @@ def run_config(cfg_id, args, ob, W, torch, hip, peaks, headline):
     n_inst = max(50, args.instrumented_steps)
     ev_inst = [([hip.event() for _ in range(4)], [hip.event() for _ in range(4)]) for _ in range(n_inst)]
 
-    # ---- W warm-up steps, then exactly K timed steps ----
+    # ---- end of the set-up: bring the chip to its sustained clocks; then W warm-up steps, then exactly K timed steps ----
+    for i in range(max(0, args.settle_steps)):
+        step(i)
+    torch.cuda.synchronize()
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
@@ -496,7 +504,8 @@ def run_config(cfg_id, args, ob, W, torch, hip, peaks, headline):
                         st |= gstep(r)
                 if st == 0:
                     reps = max(1, steps // nrot)
-                    graph.replay()
+                    for _ in range(1 + max(0, args.settle_steps) // nrot):      # warm-up replays (clocks, as above)
+                        graph.replay()
                     torch.cuda.synchronize()
                     g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     g0.record(side)
@@ -602,6 +611,7 @@ def main():
         "config": {"workload": rec["workload"], "B": cfg.B, "T": cfg.T, "gamma": cfg.gamma, "K": cfg.K, "beta": cfg.beta_p,
                    "Hq": cfg.Hq, "Hkv": cfg.Hkv, "D": cfg.D, "cache_rows": x["total_rows"], "V": cfg.V,
                    "branch": args.branch, "rotated_copies": x["nrot"], "events_on_every_nth_timed_step": x["every"],
+                   "settle_steps_before_warmup": max(0, args.settle_steps),
                    "w_layout": args.w_layout if cfg.dtype == "bf16" else "row", "kv_layout": args.kv_layout},
         "call_us": rec["call_us"],
         "roofline": rec[dom],
