@@ -42,6 +42,8 @@
 // blocks) are congruent modulo 8, i.e. land on the same XCD and share its L2.
 #include <math.h>
 
+#include <algorithm>
+
 #include "ouro_internal.hpp"
 
 namespace ouro {
@@ -83,6 +85,8 @@ struct AttnArgs {
   int rows_wg;         // query rows per workgroup (32 x row blocks per workgroup)
   int nbg;             // B * Hkv
   FastDiv div_per, div_nbg, div_hkv, div_g, div_nrb, div_chunk;   // by 8 * nrb, B * Hkv, Hkv, G, nrb, chunk
+  int B;               // sequences
+  int round_seqs;      // sequences whose workgroups of one chunk index fill the chip once (>= 1): see sequence_at
   int max_seqlen;      // the host's bound on every length: grid, chunk slots and workspace were sized from it, so a
                        // longer device-side length is cut to it (a stale bound must not reach past any of them)
   float scale_log2;
@@ -122,6 +126,34 @@ __device__ __forceinline__ void wave_lds_fence() {
 __device__ __forceinline__ float max_across_halves(float x) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// ---- which sequence a workgroup takes ---------------------------------------------------------------------------------
+// Workgroups are handed to compute units in id order, and a compute unit's share of the memory system is bounded, so
+// with sequences of unequal length the launch ends with the compute units that happened to draw the long ones while the
+// rest idle (batched workload: 238 us in batch order against 216-220 us in any length-sorted order).  So position p
+// of the dispatch order is not sequence p but the sequence whose length has a given rank (longest first; ties by index):
+// ranks in descending order, except that the second chip-filling round runs backwards when two rounds are resident at
+// once (kSnake: the key-split kernel has two workgroups per compute unit, and the unit that drew the longest of the
+// first round then gets the shortest of the second).  Every wave ranks the lengths for itself, one sequence per lane
+// (up to 64 sequences; beyond that, and for a single sequence, positions are sequences).  The result is uniform.
+template <bool kSnake>
+__device__ __forceinline__ int sequence_at(const AttnArgs& a, int pos, int lane) {
+  const int B = a.B;
+  if (B < 2 || B > 64) return pos;
+  int li = -1;
+  if (lane < B) li = min(a.len ? a.len[lane] : static_cast<int>(a.cu[lane + 1] - a.cu[lane]), a.max_seqlen);
+  int rank = 0;                                   // sequences ahead of this lane's: longer, or as long with a lower index
+  for (int k = 0; k < B; ++k) {
+    const int v = __builtin_amdgcn_readlane(li, k);
+    rank += (v > li || (v == li && k < lane)) ? 1 : 0;
+  }
+  const int rs = a.round_seqs;
+  const int round = pos / rs, j = pos - round * rs;
+  const int m = min(rs, B - round * rs);          // sequences of this round
+  const int want = round * rs + ((kSnake && round == 1) ? m - 1 - j : j);
+  const unsigned long long hit = __ballot(lane < B && rank == want);
+  return hit ? __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(hit)) - 1) : pos;
 }
 
 // ---- the block part of the mask as bit sets ----------------------------------------------------------------------
@@ -296,8 +328,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
   // sees all chunk indices; pair-major order would give the rarely populated late chunks to a few XCDs
   const int nbg = a.nbg;
   const int chunk = fdiv(x, a.div_nbg);
-  const int bg = x - chunk * nbg;
-  const int b = fdiv(bg, a.div_hkv), g = bg - b * a.Hkv;
+  const int bgpos = x - chunk * nbg;
+  const int bpos = fdiv(bgpos, a.div_hkv), g = bgpos - bpos * a.Hkv;
+  const int b = sequence_at<true>(a, bpos, threadIdx.x & 63);   // by length rank, not batch order
+  const int bg = b * a.Hkv + g;
   const int T = a.T;
   const int col = lane & 31, half = lane >> 5;
   const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
@@ -556,8 +590,10 @@ __global__ __launch_bounds__(256) void attn_bf16_rows_kernel(AttnArgs a) {
   // sees all chunk indices; pair-major order would give the rarely populated late chunks to a few XCDs
   const int nbg = a.nbg;
   const int chunk = fdiv(x, a.div_nbg);
-  const int bg = x - chunk * nbg;
-  const int b = fdiv(bg, a.div_hkv), g = bg - b * a.Hkv;
+  const int bgpos = x - chunk * nbg;
+  const int bpos = fdiv(bgpos, a.div_hkv), g = bgpos - bpos * a.Hkv;
+  const int b = sequence_at<false>(a, bpos, threadIdx.x & 63);   // by length rank, not batch order
+  const int bg = b * a.Hkv + g;
   const int T = a.T;
   const int col = lane & 31, half = lane >> 5;
   const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
@@ -803,8 +839,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_rows8_kernel(AttnArgs a) {
   if (x >= a.n_x) return;
   const int nbg = a.nbg;
   const int chunk = fdiv(x, a.div_nbg);           // chunk-major, as in the kernels above
-  const int bg = x - chunk * nbg;
-  const int b = fdiv(bg, a.div_hkv), g = bg - b * a.Hkv;
+  const int bgpos = x - chunk * nbg;
+  const int bpos = fdiv(bgpos, a.div_hkv), g = bgpos - bpos * a.Hkv;
+  const int b = sequence_at<false>(a, bpos, threadIdx.x & 63);   // by length rank, not batch order
+  const int bg = b * a.Hkv + g;
   const int T = a.T;
   const int col = lane & 31, half = lane >> 5;
   const int G = a.G, M = a.M, Hq = a.Hq, Hkv = a.Hkv;
@@ -1094,6 +1132,8 @@ int launch_attn_bf16(const ouro_attn_desc& d, const AttnPlan& plan, float scale,
   a.scale_log2 = scale * 1.4426950408889634f;
   a.rows_wg = plan.rows_wg;
   a.max_seqlen = d.max_seqlen;
+  a.B = d.B;
+  a.round_seqs = std::max(1, 256 / (d.Hkv * plan.nrb));
   const unsigned grid = static_cast<unsigned>((a.n_x + 7) / 8) * 8u * plan.nrb;
   static DeviceOnce once;
   const int ready = device_once(once, [] {
