@@ -205,6 +205,18 @@ def test_softmax_scale_given_by_the_caller(cfg_id, kw, scale):
     assert np.abs(dflt["out"] - ref["out"]).max() > 5 * attn_tol(cfg)          # the case can tell the two scales apart
 
 
+@pytest.mark.parametrize("B, rw, equal", [(2, 1, True), (16, 1, False), (63, 1, False), (64, 1, False), (64, 4, False),
+                                          (65, 1, False), (70, 4, False), (40, 2, True)])
+def test_bf16_many_sequences_taken_by_length_rank(B, rw, equal):
+    """The bf16 kernels hand sequences to workgroups by length rank (every wave ranks up to 64 lengths itself; with more
+    sequences, in batch order): every sequence must still be served exactly once, with lengths all different, with
+    ties, with a full wave of sequences and with one more than that."""
+    lens = np.full(B, 97) if equal else np.random.default_rng(B).permutation(B) * 5 % 211   # several ties, one empty
+    cfg = W.scaled(W.CONFIGS[2], B=B, Hq=2, Hkv=2, L=(0, 300), gamma=4, K=2, beta_p=3)
+    inp = W.make_attention_inputs(cfg, 99 + B, seqlens=lens)
+    _check(cfg, inp, head_major=bool(B & 1), rw=rw)
+
+
 @pytest.mark.parametrize("case", range(24))
 def test_bf16_seeded_random_shapes(case):
     """A seeded sweep over shapes nobody picked by hand: batch, head grouping, draft layout, cache lengths from empty to
