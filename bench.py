@@ -196,7 +196,7 @@ def measured_peaks(ob, torch, hip):
 
     us = timed(lambda: ob.lib.ouro_probe_stream_read(buf.data_ptr(), nbytes, sink.data_ptr(), hs), 20, 5)
     out["hbm_stream_read_GBs"] = nbytes / us / 1e3
-    out["hbm_stream_read"] = "2 GiB, 16-byte loads, 16 KB per wave in flight, 2048 workgroups; %.1f us" % us
+    out["hbm_stream_read"] = "2 GiB, 16-byte non-temporal loads, 16 KB per wave in flight, 2048 workgroups; %.1f us" % us
     wgs, rounds = 1024, 2048
     us = timed(lambda: ob.lib.ouro_probe_mfma_bf16(wgs, rounds, sink.data_ptr(), hs), 10, 3)
     out["mfma_bf16_loop_TFLOPs"] = wgs * 4 * rounds * 16 * 32768.0 / us / 1e6

@@ -392,7 +392,7 @@ OURO_API int ouro_silu_mul(const ouro_silu_mul_desc* desc, void* hip_stream);
 /* Measurement aids (not part of the verification path; used by the benchmark to state    */
 /* every kernel's rate against what the machine at hand delivers, next to the datasheet).  */
 /* ------------------------------------------------------------------------------------ */
-/* One streaming read of `bytes` (>= 1 MiB; whole 16 KB blocks are read, 16-byte loads, 2048 workgroups) of the DEVICE
+/* One streaming read of `bytes` (>= 1 MiB; whole 16 KB blocks are read, 16-byte non-temporal loads, 2048 workgroups) of the DEVICE
  * buffer buf; sink: 4 writable DEVICE bytes (never written for ordinary data).  HBM rate = bytes / kernel time when
  * the buffer exceeds the last-level cache. */
 OURO_API int ouro_probe_stream_read(const void* buf, size_t bytes, void* sink, void* hip_stream);

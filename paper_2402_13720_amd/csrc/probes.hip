@@ -21,7 +21,7 @@ __global__ __launch_bounds__(256) void probe_stream_read_kernel(const u32x4* __r
   for (size_t base = wave * (64 * U); base + 64 * U <= n16; base += nwaves * (64 * U)) {
     u32x4 v[U];
 #pragma unroll
-    for (int i = 0; i < U; ++i) v[i] = p[base + i * 64 + lane];
+    for (int i = 0; i < U; ++i) v[i] = __builtin_nontemporal_load(p + base + i * 64 + lane);   // streamed once: not kept in L2
 #pragma unroll
     for (int i = 0; i < U; ++i) acc += v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
   }
