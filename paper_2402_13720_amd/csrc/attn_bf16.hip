@@ -2,13 +2,16 @@
 //
 // What is computed (Sec. 3.2, Eq. (8)): every block row attends to the whole cached prefix
 // of its sequence plus the block tokens of its own lengthened draft.  The block part of the
-// mask is evaluated from per-token (phrase_id, branch_off) pairs (the row's pair in registers,
-// the phrase ids of the block keys in a small LDS table); only the key tiles that overlap the
-// block (the last T keys) pay for it, cache tiles are mask-free.
+// mask is evaluated from per-token (phrase_id, branch_off) pairs (per query row a 128-bit set of
+// the block keys it sees, formed once from a small LDS table of key classes); only the key tiles
+// that overlap the block (the last T keys) pay for it, cache tiles are mask-free.
 //
-// Two kernels share the tile building blocks below: attn_bf16_kernel (the waves of a workgroup
-// split the keys; described next) and attn_bf16_rows_kernel (the waves split the query rows and
-// share the staged tiles; described where it is defined).
+// Three kernels share the tile building blocks below: attn_bf16_kernel (the waves of a workgroup
+// split the keys; described next), attn_bf16_rows8_kernel (eight waves, 128 query rows: the waves
+// split rows and keys and share the staged tiles) and its four-wave predecessor
+// attn_bf16_rows_kernel (each described where it is defined).  Workgroups take sequences by
+// length rank (sequence_at), and K/V that only one workgroup reads is loaded with the
+// non-temporal hint (kStreamKV).
 //
 // Work decomposition.  Query rows of one (sequence, KV head) are the T*G rows of the G query
 // heads sharing that KV head (row = t*G + head_in_group), cut into row blocks of 32 rows.
