@@ -139,24 +139,53 @@ __device__ __forceinline__ float max_across_halves(float x) {
 // ranks in descending order, except that the second chip-filling round runs backwards when two rounds are resident at
 // once (kSnake: the key-split kernel has two workgroups per compute unit, and the unit that drew the longest of the
 // first round then gets the shortest of the second).  Every wave ranks the lengths for itself, one sequence per lane
-// (up to 64 sequences; beyond that, and for a single sequence, positions are sequences).  The result is uniform.
+// (four per lane from 65 to 256 sequences; beyond that, and for a single sequence, positions are sequences).  The result
+// is uniform.
 template <bool kSnake>
 __device__ __forceinline__ int sequence_at(const AttnArgs& a, int pos, int lane) {
   const int B = a.B;
-  if (B < 2 || B > 64) return pos;
-  int li = -1;
-  if (lane < B) li = min(a.len ? a.len[lane] : static_cast<int>(a.cu[lane + 1] - a.cu[lane]), a.max_seqlen);
-  int rank = 0;                                   // sequences ahead of this lane's: longer, or as long with a lower index
-  for (int k = 0; k < B; ++k) {
-    const int v = __builtin_amdgcn_readlane(li, k);
-    rank += (v > li || (v == li && k < lane)) ? 1 : 0;
-  }
+  if (B < 2 || B > 256) return pos;
   const int rs = a.round_seqs;
   const int round = pos / rs, j = pos - round * rs;
   const int m = min(rs, B - round * rs);          // sequences of this round
   const int want = round * rs + ((kSnake && round == 1) ? m - 1 - j : j);
-  const unsigned long long hit = __ballot(lane < B && rank == want);
-  return hit ? __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(hit)) - 1) : pos;
+  auto length = [&](int i) {
+    return i < B ? min(a.len ? a.len[i] : static_cast<int>(a.cu[i + 1] - a.cu[i]), a.max_seqlen) : -1;
+  };
+  if (B <= 64) {
+    const int li = length(lane);
+    int rank = 0;                                 // sequences ahead of this lane's: longer, or as long with a lower index
+    for (int k = 0; k < B; ++k) {
+      const int v = __builtin_amdgcn_readlane(li, k);
+      rank += (v > li || (v == li && k < lane)) ? 1 : 0;
+    }
+    const unsigned long long hit = __ballot(lane < B && rank == want);
+    return hit ? __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(hit)) - 1) : pos;
+  }
+  // 65 .. 256 sequences: four per lane (sequence lane + 64 q), the same count against every other length
+  int li[4], rank[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    li[q] = length(lane + 64 * q);
+    rank[q] = 0;
+  }
+#pragma unroll
+  for (int qq = 0; qq < 4; ++qq) {
+    const int nk = min(64, B - 64 * qq);
+    for (int kk = 0; kk < nk; ++kk) {
+      const int v = __builtin_amdgcn_readlane(li[qq], kk);
+      const int k = 64 * qq + kk;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) rank[q] += (v > li[q] || (v == li[q] && k < lane + 64 * q)) ? 1 : 0;
+    }
+  }
+  int b = pos;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const unsigned long long hit = __ballot(lane + 64 * q < B && rank[q] == want);
+    if (hit) b = 64 * q + __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(hit)) - 1);
+  }
+  return b;
 }
 
 // ---- the block part of the mask as bit sets ----------------------------------------------------------------------

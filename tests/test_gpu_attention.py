@@ -206,11 +206,12 @@ def test_softmax_scale_given_by_the_caller(cfg_id, kw, scale):
 
 
 @pytest.mark.parametrize("B, rw, equal", [(2, 1, True), (16, 1, False), (63, 1, False), (64, 1, False), (64, 4, False),
-                                          (65, 1, False), (70, 4, False), (40, 2, True)])
+                                          (65, 1, False), (70, 4, False), (40, 2, True), (130, 1, False),
+                                          (256, 1, False), (256, 4, False), (257, 1, False)])
 def test_bf16_many_sequences_taken_by_length_rank(B, rw, equal):
-    """The bf16 kernels hand sequences to workgroups by length rank (every wave ranks up to 64 lengths itself; with more
-    sequences, in batch order): every sequence must still be served exactly once, with lengths all different, with
-    ties, with a full wave of sequences and with one more than that."""
+    """The bf16 kernels hand sequences to workgroups by length rank (every wave ranks the lengths itself: one per lane up
+    to 64 sequences, four per lane up to 256; with more sequences, in batch order): every sequence must still be served
+    exactly once, with lengths all different, with ties, at and around every one of those limits."""
     lens = np.full(B, 97) if equal else np.random.default_rng(B).permutation(B) * 5 % 211   # several ties, one empty
     cfg = W.scaled(W.CONFIGS[2], B=B, Hq=2, Hkv=2, L=(0, 300), gamma=4, K=2, beta_p=3)
     inp = W.make_attention_inputs(cfg, 99 + B, seqlens=lens)
