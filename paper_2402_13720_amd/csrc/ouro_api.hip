@@ -26,8 +26,11 @@ int hip_failed(hipError_t e) {
 // More rows (long drafts, grouped-query heads), two ways, chosen by a cost estimate fitted to measurements:
 //  * the "row-split" kernel: the workgroup keeps 4 row blocks and its waves share the staged tiles; one workgroup
 //    per compute unit, the chunk count the largest that still lets every workgroup be resident at once.  K/V crosses
-//    from L2 to a compute unit once per 128 rows, but a workgroup has only ~64 KB in flight and works through its
-//    stages at ~4.2 us each under load: about 12 + 4.2 * stages microseconds;
+//    from L2 to a compute unit once per 128 rows, but a workgroup has only ~64 KB in flight, and the many chunk
+//    slots it needs to fill the chip leave several times the fp32 partials of the other plan, which the merge
+//    launch reads back and the kernels after it have to flush: about 12 + 4.2 * stages microseconds in the
+//    step as a whole (fitted with the four-wave kernel; the eight-wave one now launched is ~3 us faster as a
+//    kernel, its partials cost the same);
 //  * the key-split kernel with one workgroup per 32-row block: every row block stages the K/V window again, so K/V
 //    crosses L2 -> compute unit once per 32 rows (measured ~11 TB/s in aggregate), but two workgroups per compute
 //    unit keep twice the bytes in flight and hide each other's latencies: about 6 + 0.095 us per MB of (row blocks x
