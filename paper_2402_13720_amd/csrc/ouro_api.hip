@@ -27,15 +27,14 @@ int hip_failed(hipError_t e) {
 //  * the "row-split" kernel: the workgroup keeps 4 row blocks and its waves share the staged tiles; one workgroup
 //    per compute unit, the chunk count the largest that still lets every workgroup be resident at once.  K/V crosses
 //    from L2 to a compute unit once per 128 rows, but a workgroup has only ~64 KB in flight, and the many chunk
-//    slots it needs to fill the chip leave several times the fp32 partials of the other plan, which the merge
-//    launch reads back and the kernels after it have to flush: about 12 + 4.2 * stages microseconds in the
-//    step as a whole (fitted with the four-wave kernel; the eight-wave one now launched is ~3 us faster as a
-//    kernel, its partials cost the same);
+//    slots it needs to fill the chip leave several times the fp32 partials of the other plan for the merge launch
+//    to read back: about 10 + 3.6 * stages microseconds (eight-wave kernel, merge included in the constant);
 //  * the key-split kernel with one workgroup per 32-row block: every row block stages the K/V window again, so K/V
 //    crosses L2 -> compute unit once per 32 rows (measured ~11 TB/s in aggregate), but two workgroups per compute
 //    unit keep twice the bytes in flight and hide each other's latencies: about 6 + 0.095 us per MB of (row blocks x
-//    K/V bytes).  It wins where the K/V of the launch is small (few KV heads, one sequence): e.g. 64 query / 8 KV
-//    heads x 64 block tokens over 4096 cached tokens, 29.5 us against 35.0 us.
+//    K/V bytes).  It wins where the K/V of the launch is small and the row blocks few (a short cache, a few hundred
+//    rows at most); at 64 query / 8 KV heads x 64 block tokens over 4096 cached tokens (16 row blocks) the two are
+//    within 4 us of each other and the row-split kernel gives the shorter step (119.9 us against 121.0 us).
 // The descriptor's plan_override (row blocks per workgroup, keys per chunk) replaces the estimate in tests and tuning.
 AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
   AttnPlan p{};
@@ -53,7 +52,7 @@ AttnPlan plan_attn_bf16(const ouro_attn_desc& d) {
   if (M > 64) {
     const double kv_mb = 2.0 * static_cast<double>(maxn) * static_cast<double>(pairs) * 256.0 / 1.0e6;   // upper bound
     const double rounds4 = static_cast<double>((groups4 + 255) / 256);
-    const double t_rows = 12.0 + 4.2 * static_cast<double>(stages_wg4) * rounds4;
+    const double t_rows = 10.0 + 3.6 * static_cast<double>(stages_wg4) * rounds4;
     const double t_keys = 6.0 + 0.095 * kv_mb * static_cast<double>((M + 31) / 32);
     p.rw = t_keys < t_rows ? 1 : 4;                  // (2 is built as well; measured no faster than 1 at 64 rows)
   }

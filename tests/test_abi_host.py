@@ -103,7 +103,8 @@ def test_attn_launch_shape_query():
 
     assert plan() == [1, 512, 5, 320, 4]                                               # 7B layer: key-split, 5 chunks x 64 groups
     assert plan(T=128, Hq=40, Hkv=40, max_seqlen=4096) == [4, 768, 6, 240, 8]       # 13B layer: row-split (8 waves), one workgroup per CU
-    assert plan(T=64, Hq=64, Hkv=8, max_seqlen=4096) == [1, 2176, 2, 256, 4]        # 70B GQA layer: little K/V, key-split wins
+    assert plan(T=64, Hq=64, Hkv=8, max_seqlen=4096) == [4, 640, 7, 224, 8]         # 70B GQA layer: 16 row blocks, row-split
+    assert plan(T=96, Hq=8, Hkv=8, max_seqlen=1024)[0] == 1                         # few row blocks, little K/V: key-split wins
     assert plan(B=16, T=32, max_seqlen=8192) == [1, 8320, 1, 512, 4]                # batched: one chunk (65 tiles x 4 waves) per sequence
     assert plan(B=16, T=32, Hq=64, Hkv=8, max_seqlen=4096)[0] == 4                  # GQA batch: K/V too large to re-stage per row block
     assert plan(T=128, Hq=40, Hkv=40, max_seqlen=8192)[0] == 4
