@@ -65,7 +65,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(ouro_attn_desc d, float sc
     if (vis) {
       float dot = 0.f;
       const float4* k4 = reinterpret_cast<const float4*>(krow);
-#pragma unroll 4
+#pragma unroll 16
       for (int i = 0; i < D / 4; ++i) {
         const float4 kv = k4[i];
         dot = fmaf(q_s[4 * i + 0], kv.x, dot);
@@ -90,15 +90,25 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(ouro_attn_desc d, float sc
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < DPL; ++i) acc[i] *= alpha;
+    // sixteen value rows per round, loaded before any is used (a hidden key has p = 0 and adds nothing; its row is in
+    // bounds, the values are finite); keys in ascending order, as a one-by-one loop would take them
     const int cnt = min(64, n - base);
-    for (int j = 0; j < cnt; ++j) {
-      const float pj = p_s[j];
-      if (pj == 0.f) continue;                   // wave-uniform
-      const int kj = base + j;
-      const float* vrow = kj < L ? vc + static_cast<size_t>(cu0 + kj) * row_stride + g * head_stride
-                                 : vb + (static_cast<size_t>(kj - L) * Hkv + g) * D;
+    for (int j0 = 0; j0 < cnt; j0 += 16) {
+      float vv[16][DPL], pj[16];
 #pragma unroll
-      for (int i = 0; i < DPL; ++i) acc[i] = fmaf(pj, vrow[lane + 64 * i], acc[i]);
+      for (int u = 0; u < 16; ++u) {
+        const int j = min(j0 + u, cnt - 1);
+        const int kj = base + j;
+        const float* vrow = kj < L ? vc + static_cast<size_t>(cu0 + kj) * row_stride + g * head_stride
+                                   : vb + (static_cast<size_t>(kj - L) * Hkv + g) * D;
+        pj[u] = j0 + u < cnt ? p_s[j] : 0.f;
+#pragma unroll
+        for (int i = 0; i < DPL; ++i) vv[u][i] = vrow[lane + 64 * i];
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u)
+#pragma unroll
+        for (int i = 0; i < DPL; ++i) acc[i] = fmaf(pj[u], vv[u][i], acc[i]);
     }
   }
   float* out = static_cast<float*>(d.out) + ((static_cast<size_t>(b) * T + t) * Hq + h) * D;

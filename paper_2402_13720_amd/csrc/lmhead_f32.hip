@@ -31,20 +31,42 @@ __global__ __launch_bounds__(256) void lmhead_f32_kernel(ouro_lmhead_desc d, int
   const float* w = static_cast<const float*>(d.w);
   const int per_wave = slab / 4;
   const int v_lo = blockIdx.x * slab + wave * per_wave;
+  // Four hidden rows at a time against one vocabulary row: their loads are independent, so one memory round trip
+  // serves four dot products and the four cross-lane sums overlap (each dot product keeps its own order of operations).
   for (int v = v_lo; v < min(v_lo + per_wave, V); ++v) {
     const float4* wrow = reinterpret_cast<const float4*>(w + static_cast<size_t>(v) * Hd);
-    for (int r = 0; r < nr; ++r) {
-      const float4* hrow = reinterpret_cast<const float4*>(hidden + static_cast<size_t>(r0 + r) * Hd);
-      float dot = 0.f;
-      for (int i = lane; i < Hd / 4; i += 64) {
-        const float4 a = hrow[i], c = wrow[i];
-        dot = fmaf(a.x, c.x, dot);
-        dot = fmaf(a.y, c.y, dot);
-        dot = fmaf(a.z, c.z, dot);
-        dot = fmaf(a.w, c.w, dot);
+    for (int rb = 0; rb < nr; rb += 4) {
+      const float4* hrow[4];
+      float dot[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        hrow[u] = reinterpret_cast<const float4*>(hidden + static_cast<size_t>(r0 + min(rb + u, nr - 1)) * Hd);
+        dot[u] = 0.f;
       }
-      for (int off = 32; off >= 1; off >>= 1) dot += __shfl_xor(dot, off);
-      if (lane == 0 && dot > best_v[r]) { best_v[r] = dot; best_i[r] = v; }   // v ascending: strict > keeps the lowest id
+      for (int i = lane; i < Hd / 4; i += 64) {
+        const float4 c = wrow[i];
+        float4 a4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) a4[u] = hrow[u][i];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          dot[u] = fmaf(a4[u].x, c.x, dot[u]);
+          dot[u] = fmaf(a4[u].y, c.y, dot[u]);
+          dot[u] = fmaf(a4[u].z, c.z, dot[u]);
+          dot[u] = fmaf(a4[u].w, c.w, dot[u]);
+        }
+      }
+      for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) dot[u] += __shfl_xor(dot[u], off);
+      }
+      if (lane == 0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int r = rb + u;
+          if (r < nr && dot[u] > best_v[r]) { best_v[r] = dot[u]; best_i[r] = v; }   // v ascending: strict > keeps the lowest id
+        }
+      }
     }
   }
   __syncthreads();

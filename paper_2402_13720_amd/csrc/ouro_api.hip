@@ -90,7 +90,7 @@ LmPlan plan_lmhead(const ouro_lmhead_desc& d) {
   LmPlan p{};
   if (d.dtype == OURO_F32) {
     p.variant = 0;
-    p.slab = 32;
+    p.slab = 8;                                      // two vocabulary rows per wave: many short workgroups (the path is latency-bound)
     p.rtile = 1024;
   } else if (d.R <= 64) {
     p.variant = 1;
