@@ -113,7 +113,10 @@ __global__ __launch_bounds__(kThreads) void lmhead_bf16_tile_kernel(TileArgs a) 
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mt][nt][i] = 0.f;
 
-#define OURO_GLOAD_W(P, KT) wreg[P] = *reinterpret_cast<const u32x4*>(wbase + static_cast<size_t>(KT) * wstep + woff[P]);
+// (W with the non-temporal hint: the two row tiles that share a W line run side by side on one XCD, so the hint costs this
+// kernel nothing, and the 262 MB it would otherwise leave in L2 and in the memory-side cache cost the kernel after it
+// 8 us: the batched attention runs 186 us behind this kernel with the hint, 194 us without)
+#define OURO_GLOAD_W(P, KT) wreg[P] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wbase + static_cast<size_t>(KT) * wstep + woff[P]));
 #define OURO_GLOAD_H(P, KT) hreg[P] = *reinterpret_cast<const u32x4*>(hbase + static_cast<size_t>(KT) * (kBK * 2) + hoff[P]);
 #define OURO_STORE_W(P, BUF) *reinterpret_cast<u32x4*>(lds + (BUF) * kBufBytes + (P) * 4096 + wr0) = wreg[P];
 #define OURO_STORE_H(P, BUF) *reinterpret_cast<u32x4*>(lds + (BUF) * kBufBytes + kTileBytes + (P) * 4096 + wr0) = hreg[P];
