@@ -218,21 +218,25 @@ def test_bf16_many_sequences_taken_by_length_rank(B, rw, equal):
     _check(cfg, inp, head_major=bool(B & 1), rw=rw)
 
 
-@pytest.mark.parametrize("case", range(24))
+@pytest.mark.parametrize("case", range(48))
 def test_bf16_seeded_random_shapes(case):
-    """A seeded sweep over shapes nobody picked by hand: batch, head grouping, draft layout, cache lengths from empty to
-    a few tiles, the kernel variant, the chunk length, the cache layout and the branch rule (including phrases that hang
-    off the cached prefix, branch offset -1) all drawn per case."""
+    """A seeded sweep over shapes nobody picked by hand: batch (up to 70 sequences), head grouping (up to 8 query heads
+    per KV head), draft layout, cache lengths from empty to a few dozen tiles, the kernel variant, the chunk length, the
+    cache layout and the branch rule (including phrases that hang off the cached prefix, branch offset -1) all drawn per
+    case."""
     rng = np.random.default_rng(7000 + case)
-    Hkv = int(rng.choice([1, 2, 3]))
-    G = int(rng.choice([1, 1, 2, 4]))
-    gamma = int(rng.integers(1, 20))
-    K = int(rng.integers(0, 6))
+    Hkv = int(rng.choice([1, 2, 3, 8]))
+    G = int(rng.choice([1, 1, 2, 4, 8]))
+    gamma = int(rng.integers(1, 33))
+    K = int(rng.integers(0, 9))
     bp = int(rng.integers(1, 7)) if K else 0
-    lo = int(rng.choice([0, 1, 31, 64, 200]))
-    hi = lo + int(rng.choice([0, 1, 33, 250, 700]))
-    cfg = W.scaled(W.CONFIGS[2], B=int(rng.integers(1, 5)), Hq=Hkv * G, Hkv=Hkv, L=(lo, hi), gamma=gamma, K=K, beta_p=bp)
-    rw = int(rng.choice([1, 2, 4, 4 + 0x80]))
-    chunk = int(rng.choice([0, 128, 256, 384]))
+    while gamma + K * bp > 128:
+        K -= 1
+    lo = int(rng.choice([0, 1, 31, 64, 200, 900]))
+    hi = lo + int(rng.choice([0, 1, 33, 250, 700, 2500]))
+    B = int(rng.choice([1, 2, 3, 5, 9, 17, 33, 70]))
+    cfg = W.scaled(W.CONFIGS[2], B=B, Hq=Hkv * G, Hkv=Hkv, L=(lo, hi), gamma=gamma, K=K, beta_p=bp)
+    rw = int(rng.choice([0, 1, 2, 4, 4 + 0x80]))
+    chunk = int(rng.choice([0, 128, 256, 384, 1024]))
     inp = W.make_attention_inputs(cfg, 8000 + case, branch=str(rng.choice(["uniform", "last", "any"])))
     _check(cfg, inp, head_major=bool(rng.integers(0, 2)), rw=rw, chunk=chunk)
